@@ -1,0 +1,317 @@
+"""CPU oracle for the XKV decode hot path.  TEST INFRASTRUCTURE ONLY.
+
+This module is the slow, plain definition that the HIP library is checked
+against.  Nothing in the product path may import it: only the tests, the smoke
+check and the CPU-baseline leg of the benchmark do.  It shares no code with the
+HIP library and imports nothing from it.
+
+Everything here is NumPy in float64 on one unit at a time.  A *unit* is one
+(layer, sequence, KV head): n cached tokens with a K row and a V row of d
+channels each, an fp32 importance score and an int32 original position.
+
+What follows which passage of the paper (arXiv 2412.05896):
+
+* ``attend_score``      Eq. 1 (Z = softmax(QK^T/sqrt(d_k)) V) and Eq. 2
+                        (W_attn); the score update is the Select + Merge step
+                        of Eq. 3 / Alg. 2 steps 2-3 with the decode query as the
+                        observation row and "sum" in place of "mean".
+* ``pooled_keys``       Alg. 2 step 4 (Pooling) as described with the attention
+                        processing module in Sec. 4.1.
+* ``evict_compact``     Alg. 2 steps 5-7 (TopK, EvictByIndex on K and V).
+* ``retention_ratio``   Eq. 4 (R_i), as a fraction.
+* ``allocate_budgets``  Alg. 1 (allocation list + wait list greedy) for the
+                        two problems of Eq. 17 and Eq. 18.
+
+Parity pins: every function here is pinned by tests that do not go through it
+(brute force, closed forms, a library routine, hand-worked cases).  The whole
+multi-step decode trajectory has no number printed in the paper to compare
+with: "parity unpinned" for the trajectory as a whole, it is pinned only
+through its per-step parts.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "as_f64",
+    "attend_score",
+    "pooled_keys",
+    "select_keep",
+    "evict_compact",
+    "retention_ratio",
+    "allocate_budgets",
+    "OracleUnit",
+]
+
+
+# --------------------------------------------------------------------------
+# storage helpers
+# --------------------------------------------------------------------------
+def as_f64(x: np.ndarray) -> np.ndarray:
+    """Exact float64 value of stored elements.
+
+    ``x`` is either an fp32 array or a uint16 array of bfloat16 bit patterns
+    (the upper half of the fp32 encoding).  Both conversions are exact.
+    """
+    x = np.asarray(x)
+    if x.dtype == np.uint16:
+        return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    if x.dtype == np.float32 or x.dtype == np.float64:
+        return x.astype(np.float64)
+    raise TypeError(f"unsupported element type {x.dtype}")
+
+
+# --------------------------------------------------------------------------
+# Eq. 1 / Eq. 2 and the score update
+# --------------------------------------------------------------------------
+def attend_score(q, K, V, score, scale=None):
+    """One decode query group against one unit.
+
+    q      [G, d]   queries of the G query heads that share this KV head
+    K, V   [n, d]   cached rows, *including* the token appended this step
+    score  [n]      fp32 importance so far (0 for the appended token)
+    scale           logit scale; default 1/sqrt(d)  (Eq. 1)
+
+    Returns ``out`` [G, d] fp32, ``new_score`` [n] fp32 and the fp64
+    probability matrix ``p`` [G, n] (rows sum to 1).  With n = 0 the output is
+    zero and there is nothing to score.
+    """
+    q = as_f64(q)
+    K = as_f64(K)
+    V = as_f64(V)
+    G, d = q.shape
+    n = K.shape[0]
+    if scale is None:
+        scale = 1.0 / np.sqrt(float(d))
+    scale = float(scale)
+    out = np.zeros((G, d), dtype=np.float64)
+    p = np.zeros((G, n), dtype=np.float64)
+    if n == 0:
+        return out.astype(np.float32), np.zeros(0, dtype=np.float32), p
+    for g in range(G):
+        s = scale * (K @ q[g])                # logits  q.K_j / sqrt(d)
+        m = np.max(s)
+        e = np.exp(s - m)
+        p[g] = e / np.sum(e)                  # Eq. 2, one row of W_attn
+        out[g] = p[g] @ V                     # Eq. 1
+    mass = np.sum(p, axis=0)                  # Merge over the group's rows (sum)
+    new_score = (np.asarray(score, dtype=np.float32).astype(np.float64) + mass).astype(np.float32)
+    return out.astype(np.float32), new_score, p
+
+
+# --------------------------------------------------------------------------
+# Alg. 2 step 4: pooling
+# --------------------------------------------------------------------------
+def pooled_keys(score, pool_size: int) -> np.ndarray:
+    """Window sum of width ``pool_size`` (odd), stride 1, same length, zeros
+    outside the array.  Adds are fp32 and go left to right over the window, so
+    the result is defined bit for bit.  (Average pooling times the constant
+    window width: the ranking is the same.)
+    """
+    if pool_size < 1 or pool_size % 2 == 0:
+        raise ValueError("pool_size must be odd and >= 1")
+    s = np.asarray(score, dtype=np.float32)
+    n = s.shape[0]
+    h = pool_size // 2
+    if h == 0:
+        return s.copy()
+    padded = np.zeros(n + 2 * h, dtype=np.float32)
+    padded[h:h + n] = s
+    acc = padded[0:n].copy()                  # term j-h
+    for t in range(1, pool_size):             # then j-h+1 ... j+h, in order
+        acc = (acc + padded[t:t + n]).astype(np.float32)
+    return acc
+
+
+# --------------------------------------------------------------------------
+# Alg. 2 step 5: TopK
+# --------------------------------------------------------------------------
+def select_keep(score, pos, budget: int, pool_size: int = 1, n_protect: int = 0) -> np.ndarray:
+    """Slots kept by the top-``budget`` rule, as a sorted index array.
+
+    Key = pooled score; the ``n_protect`` most recent original positions
+    (pos >= 1 + max(pos) - n_protect) are never candidates for eviction, they
+    get key +inf.  Order is (key descending, slot ascending); the first
+    min(budget, n) slots of that order are kept.
+    """
+    s = np.asarray(score, dtype=np.float32)
+    n = s.shape[0]
+    kk = min(int(budget), n)
+    if kk <= 0:
+        return np.zeros(0, dtype=np.int64)
+    key = pooled_keys(s, pool_size)
+    if n_protect > 0 and n > 0:
+        pos = np.asarray(pos)
+        P = 1 + int(np.max(pos))
+        key = key.copy()
+        key[pos >= P - n_protect] = np.inf
+    order = np.argsort(-key.astype(np.float64), kind="stable")
+    return np.sort(order[:kk])
+
+
+# --------------------------------------------------------------------------
+# Alg. 2 steps 5-7: TopK + EvictByIndex, in place by hole filling
+# --------------------------------------------------------------------------
+def evict_compact(K, V, score, pos, budget: int, pool_size: int = 1, n_protect: int = 0):
+    """Keep the top-``budget`` tokens of a unit and compact it.
+
+    The kept tokens that sit at slots >= k' (k' = min(budget, n)) are moved,
+    in ascending slot order, into the evicted slots < k', in ascending slot
+    order.  Everything else stays where it is.  Returns the new
+    (K, V, score, pos), each of length k', and ``kept_idx`` [k'] = the slot
+    each final slot's content came from.
+    """
+    K = np.asarray(K)
+    V = np.asarray(V)
+    score = np.asarray(score, dtype=np.float32)
+    pos = np.asarray(pos, dtype=np.int32)
+    n = score.shape[0]
+    kk = min(int(budget), n)
+    keep = select_keep(score, pos, budget, pool_size, n_protect)
+    kept = np.zeros(n, dtype=bool)
+    kept[keep] = True
+    holes = [s for s in range(kk) if not kept[s]]
+    movers = [s for s in range(kk, n) if kept[s]]
+    assert len(holes) == len(movers)
+    kept_idx = np.arange(kk, dtype=np.int32)
+    for hslot, mslot in zip(holes, movers):
+        kept_idx[hslot] = mslot
+    return (K[kept_idx].copy(), V[kept_idx].copy(), score[kept_idx].copy(),
+            pos[kept_idx].copy(), kept_idx)
+
+
+# --------------------------------------------------------------------------
+# Eq. 4
+# --------------------------------------------------------------------------
+def retention_ratio(w, n: int) -> float:
+    """R = Sum(TopK(n, w)) / Sum(w) as a fraction in [0, 1]."""
+    w = np.asarray(w, dtype=np.float64)
+    tot = float(np.sum(w))
+    if tot == 0.0:
+        return 0.0
+    top = np.sort(w)[::-1][:max(int(n), 0)]
+    return float(np.sum(top) / tot)
+
+
+# --------------------------------------------------------------------------
+# Alg. 1
+# --------------------------------------------------------------------------
+def _layer_tables(w):
+    """Per layer: values sorted ascending (the listing's Sort(W)) and their sum.
+
+    The sum is taken in float64 over the ascending values, one after the
+    other, so its value does not depend on who computes it.
+    """
+    srt, tot = [], []
+    for w_l in w:
+        a = np.asarray(w_l, dtype=np.float32)
+        if a.ndim != 1:
+            raise ValueError("each w_l must be a vector")
+        if not np.all(np.isfinite(a)) or np.any(a < 0):
+            raise ValueError("w must be finite and non-negative")
+        a = np.sort(a).astype(np.float64)
+        srt.append(a)
+        tot.append(float(np.add.accumulate(a)[-1]) if a.size else 0.0)
+    return srt, tot
+
+
+def allocate_budgets(w, total_size=None, target_ravg=None, min_budget=None, max_budget=None):
+    """Greedy allocation with an allocation list and a wait list (Alg. 1).
+
+    w            list of L vectors (any order, non-negative)
+    total_size   N of Eq. 17: fill until sum(n_l) = N        (first branch)
+    target_ravg  set value of Eq. 18, a fraction: fill until R_total/L >= it
+                 (second branch); exactly one of the two is given
+    min_budget / max_budget  optional per-layer floors and caps
+
+    The wait-list entry of a layer whose current size is n is its (n+1)-th
+    largest value divided by the layer's sum, i.e. what R_avg*L gains from the
+    next token of that layer (Eq. 21); an exhausted layer waits with -inf.
+    Equal maxima go to the lowest layer index.
+    Returns (budgets int64 [L], R_avg fraction).
+    """
+    if (total_size is None) == (target_ravg is None):
+        raise ValueError("give exactly one of total_size / target_ravg")
+    L = len(w)
+    srt, tot = _layer_tables(w)
+    lens = [a.size for a in srt]
+    lo = [0] * L if min_budget is None else [int(x) for x in min_budget]
+    hi = list(lens) if max_budget is None else [min(int(x), t) for x, t in zip(max_budget, lens)]
+    for l in range(L):
+        if lo[l] < 0 or lo[l] > hi[l]:
+            raise ValueError("infeasible: floor above cap")
+
+    def contribution(l, n):                   # (n+1)-th largest, normalised
+        if n >= hi[l]:
+            return -np.inf
+        if tot[l] == 0.0:
+            return 0.0
+        return srt[l][-(n + 1)] / tot[l]
+
+    list_a = list(lo)                                         # allocation list
+    list_w = [contribution(l, list_a[l]) for l in range(L)]   # wait list
+    r_total = 0.0
+    for l in range(L):                        # importance already held by the floors
+        for r in range(list_a[l]):
+            r_total += (srt[l][-(r + 1)] / tot[l]) if tot[l] != 0.0 else 0.0
+
+    def step():
+        nonlocal r_total
+        maximum = max(list_w)
+        index = list_w.index(maximum)         # first (lowest) layer with the maximum
+        r_total += maximum
+        list_a[index] += 1
+        list_w[index] = contribution(index, list_a[index])
+
+    if total_size is not None:
+        N = int(total_size)
+        if N < sum(lo) or N > sum(hi):
+            raise ValueError("infeasible total size")
+        for _ in range(N - sum(lo)):
+            step()
+    else:
+        target = float(target_ravg)
+        while r_total / L < target and max(list_w) > -np.inf:
+            step()
+
+    ravg = 0.0
+    for l in range(L):
+        if tot[l] != 0.0 and list_a[l] > 0:
+            ravg += float(np.sum(srt[l][::-1][:list_a[l]] / tot[l]))
+    ravg /= L
+    return np.asarray(list_a, dtype=np.int64), ravg
+
+
+# --------------------------------------------------------------------------
+# a unit with state, for multi-step runs
+# --------------------------------------------------------------------------
+class OracleUnit:
+    """State of one (layer, sequence, KV head) across decode steps."""
+
+    def __init__(self, K, V, score=None, pos=None):
+        self.K = np.array(K, copy=True)
+        self.V = np.array(V, copy=True)
+        n = self.K.shape[0]
+        self.score = np.zeros(n, np.float32) if score is None else np.array(score, np.float32)
+        self.pos = np.arange(n, dtype=np.int32) if pos is None else np.array(pos, np.int32)
+
+    @property
+    def n(self):
+        return self.K.shape[0]
+
+    def append(self, k_new, v_new, pos_new):
+        """The new token's K/V row joins the cache with score 0 (Sec. 4.1,
+        generation phase)."""
+        self.K = np.concatenate([self.K, np.asarray(k_new).reshape(1, -1)], axis=0)
+        self.V = np.concatenate([self.V, np.asarray(v_new).reshape(1, -1)], axis=0)
+        self.score = np.concatenate([self.score, np.zeros(1, np.float32)])
+        self.pos = np.concatenate([self.pos, np.asarray([pos_new], np.int32)])
+
+    def attend(self, q, scale=None):
+        out, self.score, p = attend_score(q, self.K, self.V, self.score, scale)
+        return out, p
+
+    def evict(self, budget, pool_size=1, n_protect=0):
+        self.K, self.V, self.score, self.pos, kept_idx = evict_compact(
+            self.K, self.V, self.score, self.pos, budget, pool_size, n_protect)
+        return kept_idx
