@@ -1,0 +1,195 @@
+/*
+ * xkv.h - C ABI of libxkv: the decode hot path of XKV (arXiv 2412.05896,
+ * "Personalized KV Cache Memory Reduction for Long-Context LLM Inference") on
+ * one AMD MI355X (gfx950).
+ *
+ * The library keeps a ragged KV cache in which every layer (and sequence) has
+ * its own token budget, and provides
+ *   - xkv_allocate_budgets      host solver for the per-layer cache sizes
+ *   - xkv_decode_attend_score   one decode step of attention over the cache
+ *                               that also accumulates every cached token's
+ *                               attention probability into its importance
+ *   - xkv_evict_compact         keep the top-budget tokens per (layer, KV
+ *                               head) and compact K, V, score, pos in place
+ *
+ * Conventions for every call
+ *   - Pointers marked HOST are ordinary host memory, pointers marked DEVICE
+ *     are device memory of the current HIP device.  All are owned by the
+ *     caller; the library allocates no device memory and frees nothing.
+ *     Scratch comes in through `workspace` (xkv_workspace_bytes).
+ *   - Device work is enqueued on `hip_stream` (a hipStream_t, NULL = default
+ *     stream) and the call returns without waiting.  The host `len` table is
+ *     updated at enqueue time: lengths never depend on data.
+ *   - Argument errors are detected before anything is enqueued and leave all
+ *     state untouched.  No call throws, aborts or synchronises the device.
+ *   - Calls on one cache must be ordered by the caller (same stream).
+ */
+#ifndef XKV_H
+#define XKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t xkv_status;
+
+enum {
+  XKV_OK = 0,
+  XKV_ERR_INVALID_ARG = -1, /* NULL, bad range, bad value */
+  XKV_ERR_INFEASIBLE = -2,  /* allocator constraints cannot be met */
+  XKV_ERR_CAPACITY = -3,    /* a stream or the workspace is too small */
+  XKV_ERR_UNSUPPORTED = -4, /* head_dim / dtype / group size not built */
+  XKV_ERR_DEVICE = -5       /* a HIP launch failed */
+};
+
+enum { XKV_F32 = 0, XKV_BF16 = 1 };
+
+enum {
+  XKV_ALLOC_TOTAL_SIZE = 0, /* Eq. 17: maximise R_avg s.t. sum n_i = total */
+  XKV_ALLOC_TARGET_RAVG = 1 /* Eq. 18: minimise sum n_i s.t. R_avg >= target */
+};
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char* xkv_status_string(xkv_status s);
+
+/*
+ * Adaptive allocation (Alg. 1; objectives Eq. 17 and Eq. 18; retention ratio
+ * Eq. 4).  Host only, touches no device.
+ *
+ *   w[l]          HOST, len[l] non-negative finite floats: the attention-score
+ *                 distribution vector of layer l, in any order; not modified
+ *   mode          XKV_ALLOC_TOTAL_SIZE: budgets sum to total_size exactly and
+ *                 maximise R_avg = (1/L) sum_l Sum(TopK(n_l, w_l)) / Sum(w_l).
+ *                 XKV_ALLOC_TARGET_RAVG: the greedy stops as soon as
+ *                 R_avg >= target_ravg (a fraction in [0,1]); total_size is
+ *                 ignored.
+ *   min_budget    HOST [n_layers] floors, NULL = 0
+ *   max_budget    HOST [n_layers] caps, NULL = len (values above len[l] are
+ *                 clamped to len[l])
+ *   budgets_out   HOST [n_layers]
+ *   ravg_out      HOST, R_avg of the result as a fraction; may be NULL
+ *
+ * Equal contributions go to the lower layer index, so the result is unique.
+ * A layer whose w sums to zero contributes 0 per token.
+ * Errors: INVALID_ARG (NULL, n_layers <= 0, negative len, NaN/Inf/negative w,
+ * bad mode, target outside [0,1]); INFEASIBLE (min > max, sum(min) >
+ * total_size, total_size > sum(max)).
+ */
+xkv_status xkv_allocate_budgets(int32_t n_layers, const float* const* w, const int64_t* len,
+                                int32_t mode, int64_t total_size, double target_ravg,
+                                const int64_t* min_budget, const int64_t* max_budget,
+                                int64_t* budgets_out, double* ravg_out);
+
+/*
+ * The ragged cache.  Region (l, b) holds n_kv_heads streams, one per KV head,
+ * each with room for cap[l*batch+b] tokens ("slots") of which the first
+ * len[l*batch+b] are live; all heads of a region have the same length.
+ * Stream (l, b, h) starts at slot  S = region_off[l*batch+b] + h*cap[l*batch+b]:
+ *   its K rows are k[(S + j)*head_dim .. +head_dim), likewise v;
+ *   score[S + j] is the token's accumulated attention mass (fp32);
+ *   pos[S + j]   is the token's original position in the sequence.
+ * Rows are contiguous [slot][head_dim]; k and v must be 16-byte aligned.
+ * The order of slots inside a stream carries no meaning (attention does not
+ * depend on it); pos travels with each row.
+ */
+typedef struct {
+  int32_t n_layers, batch, n_q_heads, n_kv_heads, head_dim;
+  int32_t dtype;             /* XKV_F32 or XKV_BF16: element type of k, v, q */
+  int64_t arena_slots;       /* slots in each of k, v, score, pos (for bounds checks) */
+  void* k;                   /* DEVICE [arena_slots][head_dim] */
+  void* v;                   /* DEVICE [arena_slots][head_dim] */
+  float* score;              /* DEVICE [arena_slots] */
+  int32_t* pos;              /* DEVICE [arena_slots] */
+  const int64_t* region_off; /* HOST [n_layers*batch], in slots */
+  const int32_t* cap;        /* HOST [n_layers*batch] */
+  int32_t* len;              /* HOST [n_layers*batch], updated by the library */
+} xkv_cache;
+
+/*
+ * Bytes of device workspace that any later call on at most
+ * max_layers_per_call layers of this cache can need, whatever the lengths
+ * (computed from cap, not len).  Errors: INVALID_ARG, UNSUPPORTED.
+ */
+xkv_status xkv_workspace_bytes(const xkv_cache* cache, int32_t max_layers_per_call,
+                               size_t* bytes_out);
+
+/*
+ * One decode step over layers [layer_begin, layer_end)  (Eq. 1 and Eq. 2; the
+ * generation phase of Sec. 4.1; scoring = the Select and Merge steps of Eq. 3 /
+ * Alg. 2 with the decode query as the observation row and a sum as the merge).
+ *
+ * For every (l, b, h): if k_new/v_new are given, the new token's rows are
+ * appended at slot len (score 0, pos = pos_new[b]) and len grows by one; then
+ * for each of the G = n_q_heads/n_kv_heads query heads g of KV head h
+ *     p_j   = softmax_j( scale * q_g . K_j )      over all len live slots
+ *     out_g = sum_j p_j V_j
+ * and score[j] += sum_g p_j.  Products are exact, sums are fp32.
+ *
+ *   q        DEVICE [layers][batch][n_q_heads][head_dim], cache dtype; query
+ *            head hq reads KV head hq / G
+ *   k_new, v_new  DEVICE [layers][batch][n_kv_heads][head_dim]; both NULL = no
+ *            append
+ *   pos_new  HOST [batch]; ignored without append
+ *   softmax_scale  0 = 1/sqrt(head_dim)
+ *   out      DEVICE [layers][batch][n_q_heads][head_dim] fp32.  A stream with
+ *            no live slot gives a zero row.
+ *
+ * Supported: head_dim 64 or 128, G in {1, 2, 4, 8}.
+ * Errors: INVALID_ARG, UNSUPPORTED, CAPACITY (len + 1 > cap on append, or the
+ * workspace is too small), DEVICE.  Results are bit-reproducible: no atomics.
+ */
+xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                   const void* q, const void* k_new, const void* v_new,
+                                   const int32_t* pos_new, float softmax_scale, float* out,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Eviction of layers [layer_begin, layer_end)  (Alg. 2 steps 4-7: Pooling,
+ * TopK, EvictByIndex on K and V).
+ *
+ * For every (l, b, h) with n = len and k' = min(budgets[(l-layer_begin)*batch+b], n):
+ *   key_j = score_j, or for pool_size > 1 the fp32 sum, added left to right,
+ *           of score over the window of pool_size slots centred on j (zeros
+ *           outside the stream);
+ *   tokens whose pos is among the n_protect highest positions of the stream
+ *           (pos >= 1 + max pos - n_protect) are never evicted;
+ *   the k' tokens with the largest key are kept, equal keys by lower slot;
+ *   kept tokens at slots >= k' are moved, in ascending order, into the
+ *           evicted slots < k', in ascending order (K, V, score and pos move
+ *           together; nothing else moves); len becomes k'.
+ *
+ *   budgets       HOST [layers][batch], each >= 0 and >= n_protect
+ *   pool_size     odd, >= 1
+ *   kept_idx_out  DEVICE [arena_slots] or NULL: entry S + s (s < k') receives
+ *                 the slot, before the call, of the token now at slot s
+ *
+ * budget >= len is not an error: nothing moves and kept_idx is the identity.
+ * Scores are expected to be non-negative and not NaN (they are sums of
+ * probabilities); otherwise the selection is unspecified.
+ * Errors: INVALID_ARG, CAPACITY (workspace too small), DEVICE.
+ */
+xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                             const int32_t* budgets, int32_t pool_size, int32_t n_protect,
+                             int32_t* kept_idx_out, void* workspace, size_t workspace_bytes,
+                             void* hip_stream);
+
+/*
+ * Per-kernel timing for benchmarks.  While enabled, the two calls above record
+ * HIP events around their dominant kernel (the K/V streaming kernel of
+ * xkv_decode_attend_score, kernel index 0, and the selection kernel of
+ * xkv_evict_compact, kernel index 1) on the stream they launch on.
+ * xkv_profile_read waits for those events, returns the number of launches and
+ * their summed duration in milliseconds since the last xkv_profile_enable(1),
+ * and keeps them until the next enable.  Off by default; not for use under
+ * stream capture.
+ */
+xkv_status xkv_profile_enable(int32_t on);
+xkv_status xkv_profile_read(int32_t kernel_index, int64_t* launches_out, double* total_ms_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XKV_H */

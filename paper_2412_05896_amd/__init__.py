@@ -1,0 +1,21 @@
+"""MI355X-native decode hot path of XKV (arXiv 2412.05896).
+
+A thin ctypes binding over libxkv.so, the C-ABI library declared in
+include/xkv.h.  Every step of the path runs in the library's HIP kernels (or, for
+the budget allocator, its host C++); this package only marshals arguments.
+PyTorch supplies device memory and streams, nothing else.
+"""
+from .binding import (  # noqa: F401
+    XKV_ALLOC_TARGET_RAVG,
+    XKV_ALLOC_TOTAL_SIZE,
+    XkvCache,
+    XkvError,
+    load,
+    status_string,
+    xkv_allocate_budgets,
+    xkv_decode_attend_score,
+    xkv_evict_compact,
+    xkv_profile_enable,
+    xkv_profile_read,
+    xkv_workspace_bytes,
+)

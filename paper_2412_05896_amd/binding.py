@@ -1,0 +1,208 @@
+"""ctypes binding of libxkv.so: argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libxkv.so")
+
+XKV_F32, XKV_BF16 = 0, 1
+XKV_ALLOC_TOTAL_SIZE, XKV_ALLOC_TARGET_RAVG = 0, 1
+
+EXPORTS = (
+    "xkv_status_string", "xkv_allocate_budgets", "xkv_workspace_bytes",
+    "xkv_decode_attend_score", "xkv_evict_compact", "xkv_profile_enable", "xkv_profile_read",
+)
+
+
+class XkvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+class _CacheStruct(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int32), ("batch", C.c_int32), ("n_q_heads", C.c_int32),
+        ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("dtype", C.c_int32),
+        ("arena_slots", C.c_int64),
+        ("k", C.c_void_p), ("v", C.c_void_p), ("score", C.c_void_p), ("pos", C.c_void_p),
+        ("region_off", C.c_void_p), ("cap", C.c_void_p), ("len", C.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def load():
+    """Loads libxkv.so (built in-tree by __graft_entry__.build()).  There is no
+    fallback: without the library nothing here works."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python __graft_entry__.py` (build()) first")
+    try:
+        import torch  # noqa: F401  (its HIP runtime must be the one the library binds to)
+    except Exception:
+        pass
+    lib = C.CDLL(LIB_PATH)
+    lib.xkv_status_string.restype = C.c_char_p
+    lib.xkv_status_string.argtypes = [C.c_int32]
+    lib.xkv_allocate_budgets.restype = C.c_int32
+    lib.xkv_allocate_budgets.argtypes = [
+        C.c_int32, C.POINTER(C.c_void_p), C.c_void_p, C.c_int32, C.c_int64, C.c_double,
+        C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
+    lib.xkv_workspace_bytes.restype = C.c_int32
+    lib.xkv_workspace_bytes.argtypes = [C.POINTER(_CacheStruct), C.c_int32, C.POINTER(C.c_size_t)]
+    lib.xkv_decode_attend_score.restype = C.c_int32
+    lib.xkv_decode_attend_score.argtypes = [
+        C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+        C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.xkv_evict_compact.restype = C.c_int32
+    lib.xkv_evict_compact.argtypes = [
+        C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
+        C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.xkv_profile_enable.restype = C.c_int32
+    lib.xkv_profile_enable.argtypes = [C.c_int32]
+    lib.xkv_profile_read.restype = C.c_int32
+    lib.xkv_profile_read.argtypes = [C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().xkv_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise XkvError(status, where)
+
+
+def _ptr(t) -> Optional[int]:
+    """Address of a torch tensor / numpy array (None stays NULL)."""
+    if t is None:
+        return None
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr()
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+# ---------------------------------------------------------------------------
+def xkv_allocate_budgets(w: Sequence[np.ndarray], mode: int = XKV_ALLOC_TOTAL_SIZE,
+                         total_size: int = 0, target_ravg: float = 0.0,
+                         min_budget=None, max_budget=None):
+    """-> (budgets int64 [L], R_avg).  w: one fp32 vector per layer."""
+    lib = load()
+    L = len(w)
+    arrs = [np.ascontiguousarray(x, dtype=np.float32) for x in w]
+    ptrs = (C.c_void_p * max(L, 1))(*[a.ctypes.data for a in arrs])
+    lens = np.asarray([a.size for a in arrs], dtype=np.int64)
+    lo = None if min_budget is None else np.ascontiguousarray(min_budget, dtype=np.int64)
+    hi = None if max_budget is None else np.ascontiguousarray(max_budget, dtype=np.int64)
+    out = np.zeros(max(L, 1), dtype=np.int64)
+    ravg = C.c_double(0.0)
+    st = lib.xkv_allocate_budgets(L, ptrs, lens.ctypes.data, int(mode), int(total_size),
+                                  float(target_ravg), _ptr(lo), _ptr(hi), out.ctypes.data,
+                                  C.byref(ravg))
+    _check(st, "xkv_allocate_budgets")
+    return out[:L], ravg.value
+
+
+class XkvCache:
+    """Owns the arenas (torch tensors) and the host tables of one ragged cache
+    and the xkv_cache struct that points at them."""
+
+    def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, dtype, caps, device="cuda"):
+        import torch
+        caps = np.ascontiguousarray(caps, dtype=np.int32).reshape(n_layers * batch)
+        self.n_layers, self.batch = int(n_layers), int(batch)
+        self.n_q_heads, self.n_kv_heads, self.head_dim = int(n_q_heads), int(n_kv_heads), int(head_dim)
+        self.dtype = dtype
+        self.torch_dtype = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+        sizes = caps.astype(np.int64) * n_kv_heads
+        self.region_off = np.zeros(n_layers * batch, dtype=np.int64)
+        if sizes.size > 1:
+            self.region_off[1:] = np.cumsum(sizes)[:-1]
+        self.cap = caps
+        self.len = np.zeros(n_layers * batch, dtype=np.int32)
+        self.arena_slots = int(sizes.sum())
+        slots = max(self.arena_slots, 1)
+        self.k = torch.zeros((slots, head_dim), dtype=self.torch_dtype, device=device)
+        self.v = torch.zeros((slots, head_dim), dtype=self.torch_dtype, device=device)
+        self.score = torch.zeros(slots, dtype=torch.float32, device=device)
+        self.pos = torch.zeros(slots, dtype=torch.int32, device=device)
+        self.struct = _CacheStruct()
+        self.refresh()
+
+    def refresh(self):
+        s = self.struct
+        s.n_layers, s.batch, s.n_q_heads = self.n_layers, self.batch, self.n_q_heads
+        s.n_kv_heads, s.head_dim = self.n_kv_heads, self.head_dim
+        s.dtype = XKV_F32 if self.dtype == "f32" else XKV_BF16
+        s.arena_slots = self.arena_slots
+        s.k, s.v, s.score, s.pos = (self.k.data_ptr(), self.v.data_ptr(),
+                                    self.score.data_ptr(), self.pos.data_ptr())
+        s.region_off = self.region_off.ctypes.data
+        s.cap = self.cap.ctypes.data
+        s.len = self.len.ctypes.data
+
+    def stream_slot(self, l, b, h) -> int:
+        i = l * self.batch + b
+        return int(self.region_off[i]) + h * int(self.cap[i])
+
+    def length(self, l, b) -> int:
+        return int(self.len[l * self.batch + b])
+
+
+def xkv_workspace_bytes(cache: XkvCache, max_layers_per_call: int) -> int:
+    out = C.c_size_t(0)
+    _check(load().xkv_workspace_bytes(C.byref(cache.struct), int(max_layers_per_call), C.byref(out)),
+           "xkv_workspace_bytes")
+    return out.value
+
+
+def xkv_decode_attend_score(cache: XkvCache, layer_begin, layer_end, q, k_new, v_new, pos_new,
+                            out, workspace, softmax_scale: float = 0.0, stream=None):
+    """q/k_new/v_new/out/workspace: torch device tensors; pos_new: int32 host array [B]."""
+    pn = None if pos_new is None else np.ascontiguousarray(pos_new, dtype=np.int32)
+    st = load().xkv_decode_attend_score(
+        C.byref(cache.struct), int(layer_begin), int(layer_end), _ptr(q), _ptr(k_new), _ptr(v_new),
+        _ptr(pn), float(softmax_scale), _ptr(out), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    _check(st, "xkv_decode_attend_score")
+
+
+def xkv_evict_compact(cache: XkvCache, layer_begin, layer_end, budgets, workspace, pool_size: int = 1,
+                      n_protect: int = 0, kept_idx_out=None, stream=None):
+    """budgets: int32 host array [layers, B]."""
+    bud = None if budgets is None else np.ascontiguousarray(budgets, dtype=np.int32)
+    st = load().xkv_evict_compact(
+        C.byref(cache.struct), int(layer_begin), int(layer_end), _ptr(bud), int(pool_size),
+        int(n_protect), _ptr(kept_idx_out), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    _check(st, "xkv_evict_compact")
+
+
+def xkv_profile_enable(on: bool):
+    _check(load().xkv_profile_enable(1 if on else 0), "xkv_profile_enable")
+
+
+def xkv_profile_read(kernel_index: int):
+    n, ms = C.c_int64(0), C.c_double(0.0)
+    _check(load().xkv_profile_read(int(kernel_index), C.byref(n), C.byref(ms)), "xkv_profile_read")
+    return n.value, ms.value

@@ -1,0 +1,368 @@
+// xkv_evict_compact: per-(layer, sequence, KV head) top-budget selection and
+// in-place compaction (Alg. 2 steps 4-7 of the paper: Pooling, TopK,
+// EvictByIndex on K and V).
+//
+//  evict_select   one workgroup per stream.  Builds the keys (score, or its
+//                 pooled window sum; +inf for protected tokens), finds the
+//                 k'-th largest key by a 4-pass radix select on the fp32 bit
+//                 pattern (scores are non-negative, so unsigned order = float
+//                 order), then walks the slots in order to decide what is kept
+//                 (equal keys: lower slot first) and to number the holes
+//                 (evicted slots < k') and the movers (kept slots >= k').
+//                 When every stream of the call moves only a few rows, the
+//                 same workgroup moves them; otherwise it leaves the two lists
+//                 in the workspace for
+//  evict_move     which copies mover i over hole i, several workgroups per
+//                 stream.  Sources are all >= k' and destinations all < k', so
+//                 the copy is free of hazards.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <limits>
+
+#include "device_util.h"
+#include "xkv_internal.h"
+
+namespace xkv {
+namespace {
+
+constexpr int kSelThreads = 512;
+constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kMoveThreads = 256;
+constexpr int kFuseMax = 64;     // moves the selecting workgroup does itself
+constexpr int kWsAlign = 32;     // workspace words per stream are a multiple of this
+
+struct EvictPair {
+  int64_t slot0;   // first slot of the region
+  int32_t cap;     // slots per stream
+  int32_t n;       // live slots
+  int32_t k;       // slots to keep, already min(budget, n)
+  int32_t ws0;     // first workspace word of the region (per array)
+};
+
+struct EvictParams {
+  void* k;
+  void* v;
+  float* score;
+  int32_t* pos;
+  int32_t* kept_idx;     // may be null
+  uint32_t* ws_keys;
+  int32_t* ws_holes;
+  int32_t* ws_movers;
+  int32_t* ws_count;     // moves per stream of this launch
+  int32_t n_pairs;
+  int32_t n_kv_heads;
+  int32_t pool;
+  int32_t n_protect;
+  int32_t row_bytes;
+  int32_t fused;
+  int32_t pad_;
+  EvictPair pairs[kMaxPairs];
+};
+
+__device__ __forceinline__ int ws_stride(int n) { return (n + kWsAlign - 1) / kWsAlign * kWsAlign; }
+
+// Copies the token at slot src over slot dst: K row, V row, score, pos.
+__device__ __forceinline__ void move_row(const EvictParams& P, int64_t stream_slot, int dst, int src,
+                                         int lane) {
+  const int frags = P.row_bytes >> 4;
+  if (lane < frags) {
+    char* kb = static_cast<char*>(P.k) + stream_slot * P.row_bytes;
+    char* vb = static_cast<char*>(P.v) + stream_slot * P.row_bytes;
+    const int64_t so = static_cast<int64_t>(src) * P.row_bytes + lane * 16;
+    const int64_t dof = static_cast<int64_t>(dst) * P.row_bytes + lane * 16;
+    const uint4 a = *reinterpret_cast<const uint4*>(kb + so);
+    const uint4 b = *reinterpret_cast<const uint4*>(vb + so);
+    *reinterpret_cast<uint4*>(kb + dof) = a;
+    *reinterpret_cast<uint4*>(vb + dof) = b;
+  } else if (lane == 32) {
+    P.score[stream_slot + dst] = P.score[stream_slot + src];
+  } else if (lane == 33) {
+    P.pos[stream_slot + dst] = P.pos[stream_slot + src];
+  } else if (lane == 34 && P.kept_idx != nullptr) {
+    P.kept_idx[stream_slot + dst] = src;
+  }
+}
+
+// Number of set bits of a wave-wide vote below this lane.
+__device__ __forceinline__ int rank_in_wave(unsigned long long vote) {
+  return __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(vote >> 32),
+                                   __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(vote), 0));
+}
+
+__global__ __launch_bounds__(kSelThreads) void evict_select(const EvictParams P) {
+  __shared__ unsigned hist[256];
+  __shared__ int scan_sh[kSelWaves];
+  __shared__ int cnt_sh[3][kSelWaves];
+  __shared__ unsigned sel_bin, sel_need;
+  __shared__ int hole_l[kFuseMax], mover_l[kFuseMax];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int u = blockIdx.x;
+  const int p = u / P.n_kv_heads;
+  const int h = u - p * P.n_kv_heads;
+  const EvictPair pd = P.pairs[p];
+  const int n = pd.n;
+  const int kk = pd.k;
+  const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
+  const float* score = P.score + stream_slot;
+  const int32_t* pos = P.pos + stream_slot;
+  int32_t* kept = P.kept_idx ? P.kept_idx + stream_slot : nullptr;
+
+  if (kk >= n || kk == 0) {                 // nothing to select
+    if (kept != nullptr)
+      for (int j = tid; j < kk; j += kSelThreads) kept[j] = j;
+    if (tid == 0) P.ws_count[u] = 0;
+    return;
+  }
+  const int64_t ws_off = static_cast<int64_t>(pd.ws0) + static_cast<int64_t>(h) * ws_stride(n);
+  uint32_t* keys = P.ws_keys + ws_off;
+  int32_t* holes_g = P.ws_holes + ws_off;
+  int32_t* movers_g = P.ws_movers + ws_off;
+
+  // ---- keys ----------------------------------------------------------------
+  const bool derived = P.pool > 1 || P.n_protect > 0;
+  if (derived) {
+    int limit = std::numeric_limits<int>::min();      // protected: pos >= limit
+    const bool protect = P.n_protect > 0;
+    if (protect) {
+      int mx = std::numeric_limits<int>::min();
+      for (int j = tid; j < n; j += kSelThreads) mx = max(mx, pos[j]);
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) mx = max(mx, __shfl_xor(mx, off));
+      if (lane == 0) scan_sh[wave] = mx;
+      __syncthreads();
+      mx = scan_sh[0];
+#pragma unroll
+      for (int w = 1; w < kSelWaves; ++w) mx = max(mx, scan_sh[w]);
+      const long long lim = static_cast<long long>(mx) + 1 - P.n_protect;
+      limit = lim < std::numeric_limits<int>::min() ? std::numeric_limits<int>::min()
+                                                    : static_cast<int>(lim);
+      __syncthreads();
+    }
+    const int half = P.pool >> 1;
+    for (int j = tid; j < n; j += kSelThreads) {
+      // window sum, fp32, left to right, zeros outside the stream
+      int x = j - half;
+      float acc = (x >= 0 && x < n) ? score[x] : 0.0f;
+      for (int t = 1; t < P.pool; ++t) {
+        ++x;
+        const float term = (x >= 0 && x < n) ? score[x] : 0.0f;
+        acc = acc + term;
+      }
+      unsigned key = __float_as_uint(acc);
+      if (protect && pos[j] >= limit) key = 0x7f800000u;
+      keys[j] = key;
+    }
+    __syncthreads();
+  }
+  auto key_at = [&](int j) -> unsigned { return derived ? keys[j] : __float_as_uint(score[j]); };
+
+  // ---- radix select: the kk-th largest key -----------------------------------
+  unsigned prefix = 0, mask = 0, need = static_cast<unsigned>(kk);
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int j = tid; j < n; j += kSelThreads) {
+      const unsigned key = key_at(j);
+      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    // Thread t < 256 takes bin 255 - t; an inclusive scan over t finds the bin
+    // in which the running count, from the top, reaches `need`.
+    unsigned cnt = 0, incl = 0;
+    if (tid < 256) {
+      cnt = hist[255 - tid];
+      incl = cnt;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const unsigned y = __shfl_up(incl, off);
+        if (lane >= off) incl += y;
+      }
+      if (lane == 63) scan_sh[wave] = static_cast<int>(incl);
+    }
+    __syncthreads();
+    if (tid < 256) {
+      for (int w = 0; w < wave; ++w) incl += static_cast<unsigned>(scan_sh[w]);
+      const unsigned before = incl - cnt;
+      if (before < need && need <= incl) {
+        sel_bin = 255u - static_cast<unsigned>(tid);
+        sel_need = need - before;
+      }
+    }
+    __syncthreads();
+    prefix |= sel_bin << shift;
+    mask |= 255u << shift;
+    need = sel_need;
+    __syncthreads();
+  }
+  const unsigned thr = prefix;              // keys above are kept, `need` of the equal ones too
+
+  // ---- walk the slots in order ---------------------------------------------
+  int carry_eq = 0, carry_h = 0, carry_m = 0;
+  for (int base = 0; base < n; base += kSelThreads) {
+    const int j = base + tid;
+    const bool live = j < n;
+    const unsigned key = live ? key_at(j) : 0u;
+    const bool is_eq = live && key == thr;
+    const unsigned long long v_eq = __ballot(is_eq);
+    if (lane == 0) cnt_sh[0][wave] = __popcll(v_eq);
+    __syncthreads();
+    int eq_rank = carry_eq + rank_in_wave(v_eq), eq_tot = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) {
+      const int cw = cnt_sh[0][w];
+      if (w < wave) eq_rank += cw;
+      eq_tot += cw;
+    }
+    carry_eq += eq_tot;
+    const bool keep = live && (key > thr || (is_eq && eq_rank < static_cast<int>(need)));
+    const bool is_hole = live && j < kk && !keep;
+    const bool is_mover = live && j >= kk && keep;
+    const unsigned long long v_h = __ballot(is_hole);
+    const unsigned long long v_m = __ballot(is_mover);
+    if (lane == 0) {
+      cnt_sh[1][wave] = __popcll(v_h);
+      cnt_sh[2][wave] = __popcll(v_m);
+    }
+    __syncthreads();
+    int h_rank = carry_h + rank_in_wave(v_h), m_rank = carry_m + rank_in_wave(v_m);
+    int h_tot = 0, m_tot = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) {
+      const int ch = cnt_sh[1][w], cm = cnt_sh[2][w];
+      if (w < wave) { h_rank += ch; m_rank += cm; }
+      h_tot += ch;
+      m_tot += cm;
+    }
+    carry_h += h_tot;
+    carry_m += m_tot;
+    if (is_hole) { if (P.fused) hole_l[h_rank] = j; else holes_g[h_rank] = j; }
+    if (is_mover) { if (P.fused) mover_l[m_rank] = j; else movers_g[m_rank] = j; }
+    if (kept != nullptr && keep && j < kk) kept[j] = j;
+    __syncthreads();                        // cnt_sh is reused by the next tile
+  }
+
+  if (!P.fused) {
+    if (tid == 0) P.ws_count[u] = carry_h;
+    return;
+  }
+  if (tid == 0) P.ws_count[u] = 0;
+  for (int i = wave; i < carry_h; i += kSelWaves) move_row(P, stream_slot, hole_l[i], mover_l[i], lane);
+}
+
+__global__ __launch_bounds__(kMoveThreads) void evict_move(const EvictParams P) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int u = blockIdx.x;
+  const int moves = P.ws_count[u];
+  if (moves == 0) return;
+  const int p = u / P.n_kv_heads;
+  const int h = u - p * P.n_kv_heads;
+  const EvictPair pd = P.pairs[p];
+  const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
+  const int64_t ws_off = static_cast<int64_t>(pd.ws0) + static_cast<int64_t>(h) * ws_stride(pd.n);
+  const int32_t* holes = P.ws_holes + ws_off;
+  const int32_t* movers = P.ws_movers + ws_off;
+  const int waves = kMoveThreads / 64;
+  for (int i = blockIdx.y * waves + wave; i < moves; i += gridDim.y * waves)
+    move_row(P, stream_slot, holes[i], movers[i], lane);
+}
+
+}  // namespace
+}  // namespace xkv
+
+extern "C" xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                        const int32_t* budgets, int32_t pool_size,
+                                        int32_t n_protect, int32_t* kept_idx_out, void* workspace,
+                                        size_t workspace_bytes, void* hip_stream) {
+  using namespace xkv;
+  xkv_status st = check_cache(cache);
+  if (st != XKV_OK) return st;
+  st = check_layers(cache, layer_begin, layer_end);
+  if (st != XKV_OK) return st;
+  if (budgets == nullptr) return XKV_ERR_INVALID_ARG;
+  if (pool_size < 1 || (pool_size & 1) == 0 || n_protect < 0) return XKV_ERR_INVALID_ARG;
+
+  const int B = cache->batch, hkv = cache->n_kv_heads;
+  const int64_t first = static_cast<int64_t>(layer_begin) * B;
+  const int64_t n_pairs = static_cast<int64_t>(layer_end - layer_begin) * B;
+  int64_t words = 0;            // workspace words per array
+  int64_t max_moves = 0;
+  bool any_work = false;
+  for (int64_t i = 0; i < n_pairs; ++i) {
+    const int64_t bud = budgets[i];
+    if (bud < 0 || bud < n_protect) return XKV_ERR_INVALID_ARG;
+    const int64_t n = cache->len[first + i];
+    const int64_t kk = std::min(bud, n);
+    if (kk < n && kk > 0) {
+      max_moves = std::max(max_moves, std::min(kk, n - kk));
+      any_work = true;
+    }
+    words += ceil_div(n, kWsAlign) * kWsAlign * hkv;
+  }
+  const int64_t units = n_pairs * hkv;
+  const uint64_t need_bytes = static_cast<uint64_t>(words) * 12 + static_cast<uint64_t>(units) * 4;
+  if (workspace == nullptr || need_bytes > workspace_bytes) return XKV_ERR_CAPACITY;
+  if (reinterpret_cast<uintptr_t>(workspace) & 3u) return XKV_ERR_INVALID_ARG;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (any_work || kept_idx_out != nullptr) {
+    EvictParams P;
+    P.k = cache->k; P.v = cache->v; P.score = cache->score; P.pos = cache->pos;
+    P.kept_idx = kept_idx_out;
+    P.ws_keys = static_cast<uint32_t*>(workspace);
+    P.ws_holes = reinterpret_cast<int32_t*>(P.ws_keys + words);
+    P.ws_movers = P.ws_holes + words;
+    int32_t* counts = P.ws_movers + words;
+    P.n_kv_heads = hkv;
+    P.pool = pool_size;
+    P.n_protect = n_protect;
+    P.row_bytes = cache->head_dim * (cache->dtype == XKV_F32 ? 4 : 2);
+    P.fused = max_moves <= kFuseMax ? 1 : 0;
+    P.pad_ = 0;
+    const unsigned move_blocks =
+        static_cast<unsigned>(std::min<int64_t>(64, std::max<int64_t>(1, ceil_div(max_moves, 64))));
+
+    int64_t word0 = 0;
+    for (int64_t g0 = 0; g0 < n_pairs; g0 += kMaxPairs) {
+      const int np = static_cast<int>(std::min<int64_t>(kMaxPairs, n_pairs - g0));
+      // A launch addresses its workspace with 32-bit word offsets.
+      P.ws_keys = static_cast<uint32_t*>(workspace) + word0;
+      P.ws_holes = reinterpret_cast<int32_t*>(static_cast<uint32_t*>(workspace) + words) + word0;
+      P.ws_movers = reinterpret_cast<int32_t*>(static_cast<uint32_t*>(workspace) + 2 * words) + word0;
+      P.ws_count = counts + g0 * hkv;
+      int64_t w = 0;
+      for (int i = 0; i < np; ++i) {
+        const int64_t idx = first + g0 + i;
+        EvictPair& pd = P.pairs[i];
+        pd.slot0 = cache->region_off[idx];
+        pd.cap = cache->cap[idx];
+        pd.n = cache->len[idx];
+        pd.k = static_cast<int32_t>(std::min<int64_t>(budgets[g0 + i], pd.n));
+        if (w > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;
+        pd.ws0 = static_cast<int32_t>(w);
+        w += ceil_div(pd.n, kWsAlign) * kWsAlign * hkv;
+      }
+      P.n_pairs = np;
+      const int tok = profile_begin(1, stream);
+      hipLaunchKernelGGL(evict_select, dim3(static_cast<unsigned>(np * hkv)), dim3(kSelThreads), 0,
+                         stream, P);
+      profile_end(tok, stream);
+      if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+      if (!P.fused) {
+        hipLaunchKernelGGL(evict_move, dim3(static_cast<unsigned>(np * hkv), move_blocks),
+                           dim3(kMoveThreads), 0, stream, P);
+        if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+      }
+      word0 += w;
+    }
+  }
+  for (int64_t i = 0; i < n_pairs; ++i) {
+    const int64_t n = cache->len[first + i];
+    cache->len[first + i] = static_cast<int32_t>(std::min<int64_t>(budgets[i], n));
+  }
+  return XKV_OK;
+}

@@ -1,0 +1,43 @@
+// Internal declarations shared by the translation units of libxkv.
+#ifndef XKV_INTERNAL_H
+#define XKV_INTERNAL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "xkv.h"
+
+namespace xkv {
+
+// Tokens of one stream handled by one workgroup of the K/V streaming kernel.
+constexpr int kChunk = 256;
+// (layer, sequence) regions described in the kernel arguments of one launch.
+constexpr int kMaxPairs = 128;
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Floats of workspace per (stream, chunk): for each of the G query heads of the
+// stream, kChunk un-normalised probabilities, head_dim partial outputs and the
+// chunk's (max, sum).
+inline int64_t attend_record_floats(int group, int head_dim) {
+  return static_cast<int64_t>(group) * (kChunk + head_dim + 2);
+}
+
+// Checks everything about a cache descriptor that can be checked on the host.
+xkv_status check_cache(const xkv_cache* c);
+// Checks a layer range against a checked cache.
+xkv_status check_layers(const xkv_cache* c, int32_t layer_begin, int32_t layer_end);
+
+// Workspace needs, in bytes, for `layers` layers in the worst case (by cap).
+size_t attend_workspace_bytes(const xkv_cache* c, int32_t layers);
+size_t evict_workspace_bytes(const xkv_cache* c, int32_t layers);
+
+// Per-kernel event timing (xkv_profile_*).  begin() returns a token >= 0 when
+// timing is on and records the start event on the stream; end() records the
+// stop event.  Both are no-ops when timing is off.
+int profile_begin(int kernel_index, void* stream);
+void profile_end(int token, void* stream);
+
+}  // namespace xkv
+
+#endif  // XKV_INTERNAL_H

@@ -1,0 +1,127 @@
+"""GPU parity: xkv_decode_attend_score against the oracle, unit by unit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import xkv_oracle as orc
+from gpu_util import TOL, get_unit, random_fill, rel_err, storage
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, append, seed, scale=0.0, layer_range=None):
+    lens = np.asarray(lens, np.int32).reshape(L, B)
+    caps = lens + 2
+    cache = xkv.XkvCache(L, B, Hq, Hkv, d, dtype, caps)
+    random_fill(cache, lens, seed)
+    G = Hq // Hkv
+    l0, l1 = layer_range or (0, L)
+    g = torch.Generator(device="cpu").manual_seed(seed + 1)
+    q = torch.randn((l1 - l0, B, Hq, d), generator=g).to(cache.torch_dtype).cuda()
+    kn = torch.randn((l1 - l0, B, Hkv, d), generator=g).to(cache.torch_dtype).cuda()
+    vn = torch.randn((l1 - l0, B, Hkv, d), generator=g).to(cache.torch_dtype).cuda()
+    pos_new = np.arange(B, dtype=np.int32) + 10000
+    out = torch.full((l1 - l0, B, Hq, d), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(xkv.xkv_workspace_bytes(cache, L), dtype=torch.uint8, device="cuda")
+    before = {(l, b, h): get_unit(cache, l, b, h) for l in range(L) for b in range(B) for h in range(Hkv)}
+    xkv.xkv_decode_attend_score(cache, l0, l1, q, kn if append else None, vn if append else None,
+                                pos_new if append else None, out, ws, softmax_scale=scale)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    worst_o = worst_s = 0.0
+    for (l, b, h), (K, V, score, pos) in before.items():
+        n_now = cache.length(l, b)
+        if not (l0 <= l < l1):
+            assert n_now == lens[l, b]
+            K2, V2, s2, p2 = get_unit(cache, l, b, h)
+            assert np.array_equal(K2, K) and np.array_equal(s2, score)       # untouched
+            continue
+        u = orc.OracleUnit(K, V, score, pos)
+        if append:
+            u.append(storage(kn[l - l0, b, h]), storage(vn[l - l0, b, h]), pos_new[b])
+        assert n_now == u.n
+        o, _ = u.attend(storage(q[l - l0, b, h * G:(h + 1) * G]), None if scale == 0.0 else scale)
+        K2, V2, s2, p2 = get_unit(cache, l, b, h)
+        assert np.array_equal(K2, u.K) and np.array_equal(V2, u.V) and np.array_equal(p2, u.pos)
+        for gq in range(G):
+            worst_o = max(worst_o, rel_err(out[l - l0, b, h * G + gq], o[gq]))
+        worst_s = max(worst_s, rel_err(s2, u.score))
+    assert worst_o <= TOL[dtype], f"out rel err {worst_o}"
+    assert worst_s <= TOL[dtype], f"score rel err {worst_s}"
+    return worst_o, worst_s
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128), ("bf16", 64), ("f32", 128)])
+@pytest.mark.parametrize("G", [1, 2, 4, 8])
+def test_shapes_and_groups(xkv, dtype, d, G):
+    """Lengths span empty, one slot, a ragged tail, exactly one chunk, several chunks."""
+    Hkv = 2
+    lens = [[0, 1], [255, 256], [257, 700]]
+    print(f"case dtype={dtype} d={d} G={G} append", flush=True)
+    run_case(xkv, dtype, d, Hkv * G, Hkv, 3, 2, lens, True, seed=7 + G)
+    print(f"case dtype={dtype} d={d} G={G} no-append", flush=True)
+    run_case(xkv, dtype, d, Hkv * G, Hkv, 3, 2, lens, False, seed=17 + G)
+
+
+def test_empty_stream_without_append_gives_zero_row(xkv):
+    cache = xkv.XkvCache(1, 1, 2, 2, 64, "f32", [[4]])
+    q = torch.randn((1, 1, 2, 64), device="cuda")
+    out = torch.full((1, 1, 2, 64), 5.0, device="cuda")
+    ws = torch.empty(xkv.xkv_workspace_bytes(cache, 1), dtype=torch.uint8, device="cuda")
+    xkv.xkv_decode_attend_score(cache, 0, 1, q, None, None, None, out, ws)
+    torch.cuda.synchronize()
+    assert not out.cpu().numpy().any() and cache.length(0, 0) == 0
+
+
+def test_layer_subrange_and_custom_scale(xkv):
+    run_case(xkv, "f32", 64, 4, 4, 4, 1, [[300], [10], [513], [64]], True, seed=3, scale=0.2,
+             layer_range=(1, 3))
+
+
+def test_many_regions_span_several_launch_groups(xkv):
+    """More (layer, sequence) regions than one launch describes."""
+    L, B = 5, 60
+    r = np.random.default_rng(0)
+    lens = r.integers(0, 400, size=(L, B))
+    run_case(xkv, "bf16", 128, 4, 1, L, B, lens, True, seed=5)
+
+
+def test_long_stream_many_chunks(xkv):
+    o, s = run_case(xkv, "bf16", 128, 2, 2, 1, 1, [[20000]], True, seed=9)
+    print("long stream rel err", o, s)
+    run_case(xkv, "f32", 64, 1, 1, 1, 1, [[33000]], True, seed=10)
+
+
+def test_bit_reproducible(xkv):
+    outs = []
+    for _ in range(2):
+        cache = xkv.XkvCache(2, 1, 4, 2, 128, "bf16", [[1500], [900]])
+        random_fill(cache, [[1490], [890]], 21)
+        g = torch.Generator(device="cpu").manual_seed(1)
+        q = torch.randn((2, 1, 4, 128), generator=g).bfloat16().cuda()
+        kn = torch.randn((2, 1, 2, 128), generator=g).bfloat16().cuda()
+        out = torch.empty((2, 1, 4, 128), dtype=torch.float32, device="cuda")
+        ws = torch.empty(xkv.xkv_workspace_bytes(cache, 2), dtype=torch.uint8, device="cuda")
+        xkv.xkv_decode_attend_score(cache, 0, 2, q, kn, kn, np.zeros(1, np.int32), out, ws)
+        torch.cuda.synchronize()
+        outs.append((out.cpu().numpy().copy(), cache.score.cpu().numpy().copy()))
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_mass_conservation_on_device(xkv):
+    """Each decode step adds exactly G to the total score of a stream."""
+    cache = xkv.XkvCache(1, 2, 8, 2, 128, "bf16", [[3000, 3000]])
+    random_fill(cache, [[1000, 2900]], 33)
+    cache.score.zero_()
+    g = torch.Generator(device="cpu").manual_seed(2)
+    ws = torch.empty(xkv.xkv_workspace_bytes(cache, 1), dtype=torch.uint8, device="cuda")
+    out = torch.empty((1, 2, 8, 128), dtype=torch.float32, device="cuda")
+    for step in range(5):
+        q = torch.randn((1, 2, 8, 128), generator=g).bfloat16().cuda()
+        kn = torch.randn((1, 2, 2, 128), generator=g).bfloat16().cuda()
+        xkv.xkv_decode_attend_score(cache, 0, 1, q, kn, kn, np.array([7, 8], np.int32), out, ws)
+        torch.cuda.synchronize()
+        for b in range(2):
+            for h in range(2):
+                _, _, sc, _ = get_unit(cache, 0, b, h)
+                assert abs(float(sc.astype(np.float64).sum()) - 4.0 * (step + 1)) < 1e-3

@@ -189,7 +189,8 @@ def fill_prompt_cache(w: Workload, k_arena: torch.Tensor, v_arena: torch.Tensor,
     Arenas are [arena_slots, d] (k, v) and [arena_slots] (score, pos)."""
     dev = k_arena.device
     T, Hkv, d = w.context, w.n_kv_heads, w.head_dim
-    if dev.type == "cpu":
+    if dev.type == "cpu" or w.n_layers * w.batch * Hkv * T * d <= (1 << 26):
+        # small caches come from the CPU generator: bit-reproducible anywhere
         g = torch.Generator(device="cpu")
         g.manual_seed(w.seed)
         # one bit-reproducible draw per tensor, [L, B, Hkv, T, d]
@@ -200,8 +201,8 @@ def fill_prompt_cache(w: Workload, k_arena: torch.Tensor, v_arena: torch.Tensor,
                 i = l * w.batch + b
                 for h in range(Hkv):
                     s0 = int(region_off[i]) + h * int(cap[i])
-                    k_arena[s0:s0 + T] = kk[l, b, h].to(k_arena.dtype)
-                    v_arena[s0:s0 + T] = vv[l, b, h].to(v_arena.dtype)
+                    k_arena[s0:s0 + T] = kk[l, b, h].to(k_arena.dtype).to(dev)
+                    v_arena[s0:s0 + T] = vv[l, b, h].to(v_arena.dtype).to(dev)
     else:
         g = torch.Generator(device=dev)
         g.manual_seed(w.seed)
