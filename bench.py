@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the XKV decode hot path on one MI355X.
+
+A *step* is one decode step of the whole path over every layer: append the new
+token, attention over the ragged cache with per-token scoring
+(xkv_decode_attend_score), then top-budget eviction and compaction
+(xkv_evict_compact).  The cache starts from the full prompt; the first warm-up
+step therefore evicts context+1 -> budget in every layer (reported as `step0_ms`)
+and the timed steps run in the steady state budget+1 -> budget.
+
+Prints ONE JSON line: decode attend+evict layer-steps per second (layers x
+steps / elapsed), the HBM roofline of the dominant kernel and the CPU oracle's
+rate on a bounded sample of the same work.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="timed decode steps (default: the workload's run minus warm-up)")
+    ap.add_argument("--warmup", type=int, default=1, help="untimed steps; the first one is the prompt-sized eviction")
+    ap.add_argument("--workload", default="llama2_7b_32k")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time budget of the oracle baseline (0 = skip)")
+    ap.add_argument("--no-roofline-pass", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain device copy of 1 GiB x 10 (reference point for HBM byte counters)")
+    return ap.parse_args()
+
+
+def make_budgets(xkv, wl, w):
+    """int32 [L, B] per the workload's rule; also returns allocator timings."""
+    import numpy as np
+    info = {}
+    if w.budget_rule == "fixed":
+        bud = np.repeat(np.asarray(w.fixed_budgets, np.int32)[:, None], w.batch, axis=1)
+    elif w.budget_rule == "dirichlet":
+        bud = wl.dirichlet_budgets(w.n_layers, w.batch, w.context, w.total_budget, w.seed)
+    else:
+        curves = wl.zipf_importance_curves(w.n_layers, w.context, w.seed)
+        floor = [w.min_budget] * w.n_layers if w.min_budget else None
+        t0 = time.perf_counter()
+        b1, ravg = xkv.xkv_allocate_budgets(curves, total_size=w.total_budget, min_budget=floor)
+        info = {"lib_ms": (time.perf_counter() - t0) * 1e3, "r_avg": ravg, "curves": curves, "floor": floor}
+        bud = np.repeat(b1.astype(np.int32)[:, None], w.batch, axis=1)
+    return np.ascontiguousarray(bud, dtype=np.int32), info
+
+
+def algorithmic_bytes(w, lens_after_append):
+    """K and V rows read once plus the fp32 score read and written, per live
+    token per KV head: (2*d*e + 8) bytes."""
+    per_token = 2 * w.head_dim * w.elem_bytes + 8
+    return int(lens_after_append.astype("int64").sum()) * w.n_kv_heads * per_token
+
+
+def cpu_baseline(w, wl, cache, budgets, q, kn, vn, pos_new, seconds):
+    """The oracle, as it stands, on a seeded sample of units of one steady-state
+    step (append + attention/scoring + eviction), one thread."""
+    import numpy as np
+    from oracle import xkv_oracle as orc
+    try:
+        from threadpoolctl import threadpool_limits
+        limiter = threadpool_limits(limits=1)
+    except Exception:                                   # pragma: no cover
+        limiter = None
+    G = w.group
+    units = [(l, b, h) for l in range(w.n_layers) for b in range(w.batch) for h in range(w.n_kv_heads)]
+    order = np.random.default_rng(w.seed).permutation(len(units))
+    spent, done, tokens = 0.0, 0, 0
+    for idx in order:
+        l, b, h = units[idx]
+        n = cache.length(l, b)
+        s0 = cache.stream_slot(l, b, h)
+        K = wl.to_numpy_storage(cache.k[s0:s0 + n])
+        V = wl.to_numpy_storage(cache.v[s0:s0 + n])
+        sc = cache.score[s0:s0 + n].cpu().numpy()
+        ps = cache.pos[s0:s0 + n].cpu().numpy()
+        qq = wl.to_numpy_storage(q[l, b, h * G:(h + 1) * G])
+        kk = wl.to_numpy_storage(kn[l, b, h])
+        vv = wl.to_numpy_storage(vn[l, b, h])
+        t0 = time.perf_counter()
+        u = orc.OracleUnit(K, V, sc, ps)
+        u.append(kk, vv, int(pos_new[b]))
+        u.attend(qq)
+        u.evict(int(budgets[l, b]))
+        spent += time.perf_counter() - t0
+        done += 1
+        tokens += n + 1
+        if spent >= seconds:
+            break
+    if limiter is not None:
+        limiter.restore_original_limits() if hasattr(limiter, "restore_original_limits") else None
+    units_per_layer_step = w.batch * w.n_kv_heads
+    # extrapolated by token count: the sample's tokens per second over the mean tokens of a layer-step
+    mean_tokens_per_layer_step = float((budgets.astype("int64") + 1).sum()) * w.n_kv_heads / w.n_layers
+    rate = (tokens / spent) / mean_tokens_per_layer_step
+    return {"value": rate, "unit": "layer-steps/s", "cores": 1, "kind": "oracle",
+            "sample": f"{done} of {len(units)} (layer, sequence, KV-head) units of one steady-state step, "
+                      f"{spent:.1f} s of NumPy float64 on one thread, extrapolated by token count "
+                      f"({units_per_layer_step} units per layer-step)"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2412_05896_amd as xkv
+    import xkv_workloads as wl
+
+    xkv.load()
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 10
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4,
+                          "copies": 10, "ms_per_copy": dt * 1e3, "GBps_read_plus_write": 2 * src.numel() * 4 / dt / 1e9}))
+        return
+    w = wl.WORKLOADS[args.workload]
+    W = max(args.warmup, 0)
+    K = args.steps if args.steps is not None else max(w.decode_steps - W, 1)
+    L, B = w.n_layers, w.batch
+
+    budgets, alloc = make_budgets(xkv, wl, w)
+    caps = np.full((L, B), wl.round_up(w.context + 1, 8), dtype=np.int32)
+    cache = xkv.XkvCache(L, B, w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, caps)
+    wl.fill_prompt_cache(w, cache.k, cache.v, cache.score, cache.pos, cache.region_off, cache.cap)
+    cache.len[:] = w.context
+    n_in = W + K + 1
+    gen_steps = min(n_in, 256)
+    q, kn, vn, pos_new = wl.decode_inputs(w, steps=gen_steps, device="cuda")
+    out = torch.empty((L, B, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    ws = torch.empty(xkv.xkv_workspace_bytes(cache, L), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    pos_step = np.zeros(B, np.int32)
+
+    alg_bytes = [0]
+
+    def step(t):
+        i = t % gen_steps
+        pos_step[:] = w.context + t
+        alg_bytes[0] += algorithmic_bytes(w, cache.len + 1)
+        xkv.xkv_decode_attend_score(cache, 0, L, q[i], kn[i], vn[i], pos_step, out, ws, stream=stream)
+        xkv.xkv_evict_compact(cache, 0, L, budgets, ws, stream=stream)
+
+    t = 0
+    step0_ms = None
+    for _ in range(W):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        step(t)
+        torch.cuda.synchronize()
+        if t == 0:
+            step0_ms = (time.perf_counter() - t0) * 1e3
+        t += 1
+
+
+    torch.cuda.synchronize()
+    alg_bytes[0] = 0
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step(t)
+        t += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    alg_bytes_timed = alg_bytes[0]
+    ms_per_step = elapsed / K * 1e3
+    value = L * K / elapsed
+
+    roofline = None
+    steady = bool(np.all(cache.len.reshape(L, B) <= budgets))
+    if not args.no_roofline_pass:
+        alg_bytes_step = algorithmic_bytes(w, cache.len + 1)
+        xkv.xkv_profile_enable(True)
+        for _ in range(K):
+            step(t)
+            t += 1
+        torch.cuda.synchronize()
+        launches, total_ms = xkv.xkv_profile_read(0)
+        sel_launches, sel_ms = xkv.xkv_profile_read(1)
+        xkv.xkv_profile_enable(False)
+        launches_per_step = launches / K
+        bytes_per_launch = alg_bytes_step / launches_per_step
+        achieved = bytes_per_launch / (total_ms / launches * 1e-3) / 1e9
+        traffic = None
+        tfile = os.path.join(ROOT, "profiles", f"attend_partial_{w.name}_hbm_traffic.txt")
+        if os.path.exists(tfile):
+            for line in open(tfile):
+                if line.startswith("traffic_bytes_per_launch:"):
+                    traffic = float(line.split(":")[1])
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                    "kernel": "attend_partial", "avg_launch_ms": total_ms / launches,
+                    "launches_per_step": launches_per_step, "algorithmic_bytes_per_launch": bytes_per_launch,
+                    "evict_select_avg_ms": (sel_ms / sel_launches) if sel_launches else None}
+
+    cpu = None
+    if args.cpu_seconds > 0:
+        i = t % gen_steps
+        pos_step[:] = w.context + t
+        cpu = cpu_baseline(w, wl, cache, budgets, q[i], kn[i], vn[i], pos_step, args.cpu_seconds)
+
+    allocator = None
+    if alloc:
+        from oracle import xkv_oracle as orc
+        t0 = time.perf_counter()
+        ref, _ = orc.allocate_budgets(alloc["curves"], total_size=w.total_budget, min_budget=alloc["floor"])
+        allocator = {"xkv_allocate_budgets_ms": alloc["lib_ms"], "oracle_ms": (time.perf_counter() - t0) * 1e3,
+                     "identical": bool(np.array_equal(ref, budgets[:, 0])), "r_avg": alloc["r_avg"]}
+
+    step_gbs = alg_bytes_timed / elapsed / 1e9
+    line = {
+        "metric": "decode attend+evict layer-steps/sec; achieved HBM GB/s vs MI355X peak",
+        "value": value, "unit": "layer-steps/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "layers": L, "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "batch": B, "context": w.context,
+                   "total_budget": int(budgets[:, 0].sum()), "budget_frac": w.budget_frac,
+                   "budget_min": int(budgets.min()), "budget_max": int(budgets.max()),
+                   "schedule": "every step, every layer: append, attend+score, evict to budget",
+                   "steady_state": steady},
+        "step0_ms": step0_ms,
+        "algorithmic_bytes_per_step": alg_bytes_timed / K,
+        "step_hbm_gbs": step_gbs, "step_hbm_frac": step_gbs / HBM_PEAK_GBS,
+        "roofline": roofline, "cpu_baseline": cpu, "allocator": allocator,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

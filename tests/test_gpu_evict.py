@@ -50,7 +50,7 @@ def run_case(xkv, dtype, d, Hkv, L, B, lens, budgets, pool, protect, seed, ties,
 @pytest.mark.parametrize("pool,protect", [(1, 0), (7, 0), (1, 8), (7, 8), (3, 1)])
 def test_selection_and_compaction(xkv, ties, pool, protect):
     lens = [[1, 9], [64, 511], [512, 513], [1500, 4100]]
-    budgets = [[1, 8], [20, 300], [511, 100], [1499, 1000]]
+    budgets = np.maximum(np.array([[1, 8], [20, 300], [511, 100], [1499, 1000]]), protect)
     print(f"case ties={ties} pool={pool} protect={protect}", flush=True)
     run_case(xkv, "f32", 64, 2, 4, 2, lens, budgets, pool, protect, seed=1, ties=ties,
              pos_sequential=protect > 0)
