@@ -11,10 +11,11 @@
 //                   e_j = 2^(s_j - m_c) and the partial output sum_j e_j V_j,
 //                   and writes all of that to the workspace.  The workgroup
 //                   that owns the last slot also stores the appended token.
-//  attend_finalize  one workgroup per stream.  Merges the chunk statistics into
-//                   the stream's (m, l), writes out = sum_c w_c o_c with
-//                   w_c = 2^(m_c - m) / l, and adds p_j = e_j w_c(j), summed
-//                   over the G query heads, to score[j].
+//  attend_finalize  same grid.  Every workgroup merges the chunk statistics of
+//                   its stream into (m, l) and the chunk weights
+//                   w_c = 2^(m_c - m) / l, adds p_j = e_j w_c, summed over the G
+//                   query heads, to score[j] for its own chunk, and computes
+//                   its share of the channels of out = sum_c w_c o_c.
 //
 // The ragged geometry travels in the kernel arguments (at most kMaxPairs
 // (layer, sequence) regions per launch), so nothing is copied to the device
@@ -61,6 +62,27 @@ struct AttendParams {
   PairDesc pairs[kMaxPairs];
 };
 
+// Finds the region, KV head and chunk of workgroup `bid` (same numbering in
+// both kernels): the last pair whose first workgroup is <= bid.  A stream with
+// no live slot still owns one workgroup.
+struct Work { int pair_local, h, c, nchunks; };
+__device__ __forceinline__ Work locate(const AttendParams& P, int bid) {
+  int lo = 0, hi = P.n_pairs - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (P.pairs[mid].block0 <= bid) lo = mid; else hi = mid - 1;
+  }
+  Work w;
+  w.pair_local = lo;
+  w.nchunks = (P.pairs[lo].n + kChunk - 1) / kChunk;
+  const int per_head = w.nchunks > 0 ? w.nchunks : 1;
+  const int local = bid - P.pairs[lo].block0;
+  w.h = local / per_head;
+  w.c = local - w.h * per_head;
+  return w;
+}
+
+
 // Loads kNB consecutive wave-wide fragments of a stream (rows first_row,
 // first_row + RPW, ...) into registers.  Rows at or past n read as zero.  With
 // append_here, row n-1 comes from `newrow` (the token being appended) and is
@@ -73,7 +95,7 @@ __device__ __forceinline__ void load_rows(uint4 (&reg)[kNB], char* base, const c
 #pragma unroll
     for (int i = 0; i < kNB; ++i) {
       const int64_t off = static_cast<int64_t>(first_row + i * RPW) * ROWB + cl * 16;
-      reg[i] = *reinterpret_cast<const uint4*>(base + off);
+      reg[i] = load_stream16(base + off);
     }
   } else {
 #pragma unroll
@@ -86,7 +108,7 @@ __device__ __forceinline__ void load_rows(uint4 (&reg)[kNB], char* base, const c
           x = *reinterpret_cast<const uint4*>(newrow + cl * 16);
           *reinterpret_cast<uint4*>(base + off) = x;     // the append itself
         } else {
-          x = *reinterpret_cast<const uint4*>(base + off);
+          x = load_stream16(base + off);
         }
       }
       reg[i] = x;
@@ -117,18 +139,12 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
   const int cl = lane % LPR;                // 16-byte column of the row
   const int bid = blockIdx.x;
 
-  // Region of this workgroup: last pair whose first workgroup is <= bid.
-  int lo = 0, hi = P.n_pairs - 1;
-  while (lo < hi) {
-    const int mid = (lo + hi + 1) >> 1;
-    if (P.pairs[mid].block0 <= bid) lo = mid; else hi = mid - 1;
-  }
+  const Work wk = locate(P, bid);
+  const int lo = wk.pair_local;
   const PairDesc pd = P.pairs[lo];
   const int n = pd.n;
-  const int nchunks = (n + kChunk - 1) / kChunk;
-  const int local = bid - pd.block0;
-  const int h = local / nchunks;
-  const int c = local - h * nchunks;
+  if (n == 0) return;                       // an empty stream: the finalize kernel zeroes its output
+  const int h = wk.h, c = wk.c;
   const int pair = P.pair_base + lo;
   const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
   char* kbase = static_cast<char*>(P.k) + stream_slot * ROWB;
@@ -277,22 +293,21 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int u = blockIdx.x;
-  const int p = u / P.n_kv_heads;
-  const int h = u - p * P.n_kv_heads;
-  const PairDesc pd = P.pairs[p];
-  const int n = pd.n;
-  const int pair = P.pair_base + p;
+  const Work wk = locate(P, blockIdx.x);
+  const PairDesc pd = P.pairs[wk.pair_local];
+  const int n = pd.n, h = wk.h, c_own = wk.c, nchunks = wk.nchunks;
+  const int pair = P.pair_base + wk.pair_local;
   float* out = P.out + (static_cast<int64_t>(pair) * P.n_kv_heads + h) * G * D;
   if (n == 0) {
     for (int idx = tid; idx < G * D; idx += kThreads) out[idx] = 0.0f;
     return;
   }
-  const int nchunks = (n + kChunk - 1) / kChunk;
-  const float* rec0 = P.ws + (static_cast<int64_t>(pd.block0) + static_cast<int64_t>(h) * nchunks) * REC;
+  const float* rec0 =
+      P.ws + (static_cast<int64_t>(pd.block0) + static_cast<int64_t>(h) * nchunks) * REC;
 
+  // Stream statistics from the chunk statistics; every workgroup of the stream
+  // repeats this small reduction (in the same order, so all agree bit for bit).
   for (int g = 0; g < G; ++g) {
-    // stream maximum
     float m = -INFINITY;
     for (int c = tid; c < nchunks; c += kThreads)
       m = fmaxf(m, rec0[static_cast<int64_t>(c) * REC + G * (kChunk + D) + 2 * g]);
@@ -301,7 +316,6 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P
     __syncthreads();
     m = fmaxf(fmaxf(red_sh[0], red_sh[1]), fmaxf(red_sh[2], red_sh[3]));
     __syncthreads();
-    // stream sum, and the un-normalised weight of every chunk
     float l = 0.0f;
     for (int c = tid; c < nchunks; c += kThreads) {
       const float* ml = rec0 + static_cast<int64_t>(c) * REC + G * (kChunk + D) + 2 * g;
@@ -318,28 +332,31 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P
     __syncthreads();
   }
 
-  // out_g = sum_c w_c o_c
-  for (int idx = tid; idx < G * D; idx += kThreads) {
-    const int g = idx / D;
-    float o = 0.0f;
-    for (int c = 0; c < nchunks; ++c)
-      o = fmaf(w_sh[g * nchunks + c], rec0[static_cast<int64_t>(c) * REC + G * kChunk + idx], o);
-    out[idx] = o;
-  }
-
-  // score_j += sum_g e_gj w_gc ; the appended token starts from zero.
+  // score_j += sum_g e_gj w_gc for the slots of this chunk; the appended token
+  // starts from zero.
   const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
-  float* score = P.score + stream_slot;
-  for (int j = tid; j < n; j += kThreads) {
-    const int c = j / kChunk, t = j - c * kChunk;
-    const float* e = rec0 + static_cast<int64_t>(c) * REC + t;
+  const int j = c_own * kChunk + tid;
+  if (j < n) {
+    const float* e = rec0 + static_cast<int64_t>(c_own) * REC + tid;
     float add = 0.0f;
 #pragma unroll
-    for (int g = 0; g < G; ++g) add = fmaf(e[g * kChunk], w_sh[g * nchunks + c], add);
+    for (int g = 0; g < G; ++g) add = fmaf(e[g * kChunk], w_sh[g * nchunks + c_own], add);
+    float* score = P.score + stream_slot;
     const float old = (P.append && j == n - 1) ? 0.0f : score[j];
     score[j] = old + add;
   }
-  if (P.append && tid == 0) P.pos[stream_slot + n - 1] = pd.pos_new;
+  if (P.append && c_own == 0 && tid == 0) P.pos[stream_slot + n - 1] = pd.pos_new;
+
+  // out_g = sum_c w_c o_c.  The G*D output channels of the stream are dealt
+  // round-robin to its workgroups; one wave sums one channel over the chunks.
+  for (int idx = c_own + wave * nchunks; idx < G * D; idx += kWaves * nchunks) {
+    const int g = idx / D;
+    float o = 0.0f;
+    for (int c = lane; c < nchunks; c += 64)
+      o = fmaf(w_sh[g * nchunks + c], rec0[static_cast<int64_t>(c) * REC + G * kChunk + idx], o);
+    o = wave_sum(o);
+    if (lane == 0) out[idx] = o;
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -402,10 +419,10 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
     if (n > cache->cap[first + i]) return XKV_ERR_CAPACITY;
     const int64_t chunks = ceil_div(n, kChunk);
     max_chunks = std::max(max_chunks, chunks);
-    total_blocks += chunks * hkv;
+    total_blocks += std::max<int64_t>(chunks, 1) * hkv;
   }
   const int64_t rec = attend_record_floats(G, D);
-  if (workspace == nullptr && total_blocks > 0) return XKV_ERR_INVALID_ARG;
+  if (workspace == nullptr) return XKV_ERR_INVALID_ARG;
   if (static_cast<uint64_t>(total_blocks) * rec * sizeof(float) > workspace_bytes)
     return XKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(workspace) & 3u) return XKV_ERR_INVALID_ARG;
@@ -433,19 +450,17 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
       pd.n = cache->len[idx] + (append ? 1 : 0);
       pd.block0 = static_cast<int32_t>(blocks);
       pd.pos_new = append ? pos_new[(g0 + i) % B] : 0;
-      blocks += ceil_div(pd.n, kChunk) * hkv;
+      blocks += std::max<int64_t>(ceil_div(pd.n, kChunk), 1) * hkv;
     }
     if (blocks > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;
     P.n_pairs = np;
     P.pair_base = static_cast<int32_t>(g0);
     P.ws = static_cast<float*>(workspace) + blocks_done * rec;
-    if (blocks > 0) {
-      const int tok = profile_begin(0, stream);
-      hipLaunchKernelGGL(partial, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, stream, P);
-      profile_end(tok, stream);
-      if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
-    }
-    hipLaunchKernelGGL(finalize, dim3(static_cast<unsigned>(np * hkv)), dim3(kThreads), fin_lds,
+    const int tok = profile_begin(0, stream);
+    hipLaunchKernelGGL(partial, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, stream, P);
+    profile_end(tok, stream);
+    if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+    hipLaunchKernelGGL(finalize, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), fin_lds,
                        stream, P);
     if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     blocks_done += blocks;

@@ -29,6 +29,15 @@ template <> struct Unpack<BF16> {
   }
 };
 
+// 16-byte load of data that is read once per kernel: the non-temporal hint keeps
+// the stream from displacing other lines in the caches, which measurably raises
+// the HBM read rate of a pure streaming kernel on this GPU.
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+  const v4u t = __builtin_nontemporal_load(static_cast<const v4u*>(p));
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 // One DPP move: every lane reads the lane that `kCtrl` names within its row of
 // 16 lanes.  Only controls whose source lane always exists are used here.
 template <int kCtrl>

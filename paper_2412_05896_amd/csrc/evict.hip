@@ -30,6 +30,7 @@ constexpr int kSelThreads = 512;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kMoveThreads = 256;
 constexpr int kFuseMax = 64;     // moves the selecting workgroup does itself
+constexpr int kSmallE = 8;       // evictions per stream found by repeated minimum search
 constexpr int kWsAlign = 32;     // workspace words per stream are a multiple of this
 
 struct EvictPair {
@@ -56,7 +57,7 @@ struct EvictParams {
   int32_t n_protect;
   int32_t row_bytes;
   int32_t fused;
-  int32_t pad_;
+  int32_t small;         // every stream evicts at most kSmallE tokens
   EvictPair pairs[kMaxPairs];
 };
 
@@ -96,6 +97,9 @@ __global__ __launch_bounds__(kSelThreads) void evict_select(const EvictParams P)
   __shared__ int cnt_sh[3][kSelWaves];
   __shared__ unsigned sel_bin, sel_need;
   __shared__ int hole_l[kFuseMax], mover_l[kFuseMax];
+  __shared__ unsigned long long best_sh[kSelWaves];
+  __shared__ int ev_sh[kSmallE];
+  __shared__ int moves_sh;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -159,6 +163,67 @@ __global__ __launch_bounds__(kSelThreads) void evict_select(const EvictParams P)
     __syncthreads();
   }
   auto key_at = [&](int j) -> unsigned { return derived ? keys[j] : __float_as_uint(score[j]); };
+
+  // ---- few evictions: the steady state of decoding ----------------------------
+  // The evicted tokens are the last ones in (key descending, slot ascending)
+  // order, i.e. the smallest under (key ascending, slot descending).  Packing
+  // (key, ~slot) into 64 bits turns that into a plain minimum; E rounds, each
+  // taking the smallest pack above the previous one, find them one by one.
+  if (P.small) {
+    const int E = n - kk;
+    unsigned long long last = 0;            // every pack is > 0: ~slot has its top bit set
+    for (int r = 0; r < E; ++r) {
+      unsigned long long best = ~0ull;
+      for (int j = tid; j < n; j += kSelThreads) {
+        const unsigned long long pk =
+            (static_cast<unsigned long long>(key_at(j)) << 32) | (0xffffffffu - static_cast<unsigned>(j));
+        if (pk > last && pk < best) best = pk;
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) {
+        const unsigned long long o = __shfl_xor(best, off);
+        best = o < best ? o : best;
+      }
+      if (lane == 0) best_sh[wave] = best;
+      __syncthreads();
+      best = best_sh[0];
+#pragma unroll
+      for (int w = 1; w < kSelWaves; ++w) best = best_sh[w] < best ? best_sh[w] : best;
+      last = best;
+      if (tid == 0) ev_sh[r] = static_cast<int>(0xffffffffu - static_cast<unsigned>(best & 0xffffffffull));
+      __syncthreads();
+    }
+    if (tid == 0) {
+      // holes: evicted slots below kk, ascending; movers: the survivors among
+      // the E slots [kk, n), ascending.
+      for (int a = 1; a < E; ++a) {          // insertion sort of at most kSmallE slots
+        const int x = ev_sh[a];
+        int b = a - 1;
+        while (b >= 0 && ev_sh[b] > x) { ev_sh[b + 1] = ev_sh[b]; --b; }
+        ev_sh[b + 1] = x;
+      }
+      int nh = 0, nm = 0;
+      for (int a = 0; a < E; ++a)
+        if (ev_sh[a] < kk) hole_l[nh++] = ev_sh[a];
+      for (int s = kk; s < n; ++s) {
+        bool evicted = false;
+        for (int a = 0; a < E; ++a) evicted = evicted || ev_sh[a] == s;
+        if (!evicted) mover_l[nm++] = s;
+      }
+      moves_sh = nh;
+      P.ws_count[u] = 0;
+    }
+    __syncthreads();
+    const int moves = moves_sh;
+    if (kept != nullptr)
+      for (int j = tid; j < kk; j += kSelThreads) {
+        bool is_hole = false;
+        for (int a = 0; a < moves; ++a) is_hole = is_hole || hole_l[a] == j;
+        if (!is_hole) kept[j] = j;
+      }
+    for (int i = wave; i < moves; i += kSelWaves) move_row(P, stream_slot, hole_l[i], mover_l[i], lane);
+    return;
+  }
 
   // ---- radix select: the kk-th largest key -----------------------------------
   unsigned prefix = 0, mask = 0, need = static_cast<unsigned>(kk);
@@ -290,7 +355,7 @@ extern "C" xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, i
   const int64_t first = static_cast<int64_t>(layer_begin) * B;
   const int64_t n_pairs = static_cast<int64_t>(layer_end - layer_begin) * B;
   int64_t words = 0;            // workspace words per array
-  int64_t max_moves = 0;
+  int64_t max_moves = 0, max_evict = 0;
   bool any_work = false;
   for (int64_t i = 0; i < n_pairs; ++i) {
     const int64_t bud = budgets[i];
@@ -299,6 +364,7 @@ extern "C" xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, i
     const int64_t kk = std::min(bud, n);
     if (kk < n && kk > 0) {
       max_moves = std::max(max_moves, std::min(kk, n - kk));
+      max_evict = std::max(max_evict, n - kk);
       any_work = true;
     }
     words += ceil_div(n, kWsAlign) * kWsAlign * hkv;
@@ -322,7 +388,7 @@ extern "C" xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, i
     P.n_protect = n_protect;
     P.row_bytes = cache->head_dim * (cache->dtype == XKV_F32 ? 4 : 2);
     P.fused = max_moves <= kFuseMax ? 1 : 0;
-    P.pad_ = 0;
+    P.small = max_evict <= kSmallE ? 1 : 0;
     const unsigned move_blocks =
         static_cast<unsigned>(std::min<int64_t>(64, std::max<int64_t>(1, ceil_div(max_moves, 64))));
 

@@ -62,7 +62,7 @@ size_t attend_workspace_bytes(const xkv_cache* c, int32_t layers) {
   const size_t rec = static_cast<size_t>(attend_record_floats(group, c->head_dim)) * sizeof(float);
   const int hkv = c->n_kv_heads;
   return top_layers_sum(c, layers, [=](int64_t cap) {
-    return static_cast<size_t>(ceil_div(cap, kChunk)) * hkv * rec;
+    return static_cast<size_t>(std::max<int64_t>(ceil_div(cap, kChunk), 1)) * hkv * rec;
   });
 }
 

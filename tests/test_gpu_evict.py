@@ -94,3 +94,15 @@ def test_many_regions_span_several_launch_groups(xkv):
     lens = r.integers(1, 300, size=(L, B))
     budgets = np.maximum(1, (lens * r.random((L, B))).astype(np.int32))
     run_case(xkv, "bf16", 64, 2, L, B, lens, budgets, 1, 0, seed=9, ties=True)
+
+
+@pytest.mark.parametrize("pool,protect", [(1, 0), (7, 8)])
+def test_few_evictions_per_stream(xkv, pool, protect):
+    """Between 0 and 8 evictions per stream (the steady state of decoding evicts one),
+    with ties, including the case where the newest slots are themselves evicted."""
+    lens = np.array([[40, 600], [513, 2049], [1025, 9], [300, 4100]])
+    drop = np.array([[0, 1], [2, 8], [5, 3], [8, 7]])
+    for ties in (True, False):
+        print(f"case few evictions ties={ties} pool={pool} protect={protect}", flush=True)
+        run_case(xkv, "bf16", 128, 2, 4, 2, lens, np.maximum(lens - drop, protect), pool, protect, seed=11, ties=ties,
+                 pos_sequential=protect > 0)
