@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--workload", default="llama2_7b_32k")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time budget of the oracle baseline (0 = skip)")
     ap.add_argument("--no-roofline-pass", action="store_true")
+    ap.add_argument("--keep-prompt-arena", action="store_true",
+                    help="stay in the prompt-sized arena after the first eviction instead of moving to one sized by the budgets")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of 1 GiB x 10 (reference point for HBM byte counters)")
     return ap.parse_args()
@@ -56,6 +58,29 @@ def make_budgets(xkv, wl, w):
         info = {"lib_ms": (time.perf_counter() - t0) * 1e3, "r_avg": ravg, "curves": curves, "floor": floor}
         bud = np.repeat(b1.astype(np.int32)[:, None], w.batch, axis=1)
     return np.ascontiguousarray(bud, dtype=np.int32), info
+
+
+def repack(xkv, cache, budgets, slack=1):
+    """Moves the live tokens into a cache whose streams have room for budget +
+    slack tokens only (rounded up to 8 slots): the memory the method saves is
+    actually released, and the steady state runs in the small arena."""
+    import numpy as np
+    import torch
+    L, B = cache.n_layers, cache.batch
+    caps = ((budgets.astype(np.int64) + slack + 7) // 8 * 8).astype(np.int32)
+    new = xkv.XkvCache(L, B, cache.n_q_heads, cache.n_kv_heads, cache.head_dim, cache.dtype, caps)
+    new.len[:] = cache.len
+    for l in range(L):
+        for b in range(B):
+            n = cache.length(l, b)
+            for h in range(cache.n_kv_heads):
+                a, d = cache.stream_slot(l, b, h), new.stream_slot(l, b, h)
+                new.k[d:d + n] = cache.k[a:a + n]
+                new.v[d:d + n] = cache.v[a:a + n]
+                new.score[d:d + n] = cache.score[a:a + n]
+                new.pos[d:d + n] = cache.pos[a:a + n]
+    torch.cuda.synchronize()
+    return new
 
 
 def algorithmic_bytes(w, lens_after_append):
@@ -160,12 +185,15 @@ def main():
 
     alg_bytes = [0]
 
+    state = {"cache": cache, "ws": ws}
+
     def step(t):
         i = t % gen_steps
+        c = state["cache"]
         pos_step[:] = w.context + t
-        alg_bytes[0] += algorithmic_bytes(w, cache.len + 1)
-        xkv.xkv_decode_attend_score(cache, 0, L, q[i], kn[i], vn[i], pos_step, out, ws, stream=stream)
-        xkv.xkv_evict_compact(cache, 0, L, budgets, ws, stream=stream)
+        alg_bytes[0] += algorithmic_bytes(w, c.len + 1)
+        xkv.xkv_decode_attend_score(c, 0, L, q[i], kn[i], vn[i], pos_step, out, state["ws"], stream=stream)
+        xkv.xkv_evict_compact(c, 0, L, budgets, state["ws"], stream=stream)
 
     t = 0
     step0_ms = None
@@ -176,6 +204,16 @@ def main():
         torch.cuda.synchronize()
         if t == 0:
             step0_ms = (time.perf_counter() - t0) * 1e3
+            if not args.keep_prompt_arena:
+                # the prompt-sized arena has done its job: continue in one sized by the budgets
+                packed = repack(xkv, cache, budgets)
+                del ws, cache
+                state["cache"] = None
+                state["ws"] = None
+                torch.cuda.empty_cache()
+                cache = packed
+                ws = torch.empty(xkv.xkv_workspace_bytes(cache, L), dtype=torch.uint8, device="cuda")
+                state["cache"], state["ws"] = cache, ws
         t += 1
 
 
@@ -243,6 +281,8 @@ def main():
                    "total_budget": int(budgets[:, 0].sum()), "budget_frac": w.budget_frac,
                    "budget_min": int(budgets.min()), "budget_max": int(budgets.max()),
                    "schedule": "every step, every layer: append, attend+score, evict to budget",
+                   "arena": "prompt-sized" if args.keep_prompt_arena or W == 0 else "budget-sized after the first eviction",
+                   "kv_arena_bytes": int(2 * cache.arena_slots * w.head_dim * w.elem_bytes),
                    "steady_state": steady},
         "step0_ms": step0_ms,
         "algorithmic_bytes_per_step": alg_bytes_timed / K,

@@ -11,11 +11,11 @@
 //                   e_j = 2^(s_j - m_c) and the partial output sum_j e_j V_j,
 //                   and writes all of that to the workspace.  The workgroup
 //                   that owns the last slot also stores the appended token.
-//  attend_finalize  same grid.  Every workgroup merges the chunk statistics of
-//                   its stream into (m, l) and the chunk weights
-//                   w_c = 2^(m_c - m) / l, adds p_j = e_j w_c, summed over the G
-//                   query heads, to score[j] for its own chunk, and computes
-//                   its share of the channels of out = sum_c w_c o_c.
+//  attend_finalize  one workgroup per (stream, 4 chunks).  Every workgroup merges
+//                   the chunk statistics of its stream into (m, l) and the chunk
+//                   weights w_c = 2^(m_c - m) / l, adds p_j = e_j w_c, summed over
+//                   the G query heads, to score[j] for its own slots, and
+//                   computes its share of the channels of out = sum_c w_c o_c.
 //
 // The ragged geometry travels in the kernel arguments (at most kMaxPairs
 // (layer, sequence) regions per launch), so nothing is copied to the device
@@ -40,8 +40,8 @@ struct PairDesc {
   int64_t slot0;    // first slot of the region
   int32_t cap;      // slots per stream
   int32_t n;        // live slots, the appended token included
-  int32_t block0;   // first partial-kernel workgroup of the region in this launch
-  int32_t pos_new;  // original position of the appended token
+  int32_t block0;   // first streaming-kernel workgroup of the region in this launch
+  int32_t fblock0;  // first finalize-kernel workgroup of the region in this launch
 };
 
 struct AttendParams {
@@ -60,7 +60,11 @@ struct AttendParams {
   int32_t n_kv_heads;
   int32_t append;
   PairDesc pairs[kMaxPairs];
+  int32_t pos_new[kMaxPairs];  // original position of the token appended to each region
 };
+
+// Chunks of one stream that one workgroup of the finalize kernel covers.
+constexpr int kFinalChunks = 4;
 
 // Finds the region, KV head and chunk of workgroup `bid` (same numbering in
 // both kernels): the last pair whose first workgroup is <= bid.  A stream with
@@ -84,11 +88,12 @@ __device__ __forceinline__ Work locate(const AttendParams& P, int bid) {
 
 
 // Loads kNB consecutive wave-wide fragments of a stream (rows first_row,
-// first_row + RPW, ...) into registers.  Rows at or past n read as zero.  With
-// append_here, row n-1 comes from `newrow` (the token being appended) and is
-// stored into the stream by the same lanes.
+// first_row + RPW, ...) into registers, without branches: rows at or past n are
+// clamped to row n-1 (in bounds; their logits are masked later and their
+// probabilities are zero), and with append_here the lanes of row n-1 read the
+// token being appended from `newrow` instead of the not yet written slot.
 template <int ROWB, int RPW, int kNB>
-__device__ __forceinline__ void load_rows(uint4 (&reg)[kNB], char* base, const char* newrow,
+__device__ __forceinline__ void load_rows(uint4 (&reg)[kNB], const char* base, const char* newrow,
                                           int first_row, int n, bool full, bool append_here,
                                           int cl) {
   if (full) {
@@ -101,18 +106,24 @@ __device__ __forceinline__ void load_rows(uint4 (&reg)[kNB], char* base, const c
 #pragma unroll
     for (int i = 0; i < kNB; ++i) {
       const int r = first_row + i * RPW;
-      const int64_t off = static_cast<int64_t>(r) * ROWB + cl * 16;
-      uint4 x = make_uint4(0, 0, 0, 0);
-      if (r < n) {
-        if (append_here && r == n - 1) {
-          x = *reinterpret_cast<const uint4*>(newrow + cl * 16);
-          *reinterpret_cast<uint4*>(base + off) = x;     // the append itself
-        } else {
-          x = load_stream16(base + off);
-        }
-      }
-      reg[i] = x;
+      const int rc = r < n ? r : n - 1;
+      const char* src = base + static_cast<int64_t>(rc) * ROWB + cl * 16;
+      if (append_here && r == n - 1) src = newrow + cl * 16;
+      reg[i] = load_stream16(src);
     }
+  }
+}
+
+// The append itself: the lanes that hold row n-1 (read from the new token's
+// row by load_rows) store it into the stream.
+template <int ROWB, int RPW, int kNB>
+__device__ __forceinline__ void store_appended(const uint4 (&reg)[kNB], char* base, int first_row,
+                                               int n, int cl) {
+#pragma unroll
+  for (int i = 0; i < kNB; ++i) {
+    const int r = first_row + i * RPW;
+    if (r == n - 1)
+      *reinterpret_cast<uint4*>(base + static_cast<int64_t>(r) * ROWB + cl * 16) = reg[i];
   }
 }
 
@@ -174,12 +185,12 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
   const bool full = (c + 1) * kChunk <= n && !append_here;
   constexpr int NV = V_EARLY ? NT : 1;
   uint4 vreg[NV];
-  if constexpr (V_EARLY)
-    load_rows<ROWB, RPW, NV>(vreg, vbase, vnew, row0 + sub, n, full, append_here, cl);
 #pragma unroll
   for (int b0 = 0; b0 < NT; b0 += kTB) {
     uint4 kreg[kTB];
     load_rows<ROWB, RPW, kTB>(kreg, kbase, knew, row0 + b0 * RPW + sub, n, full, append_here, cl);
+    if constexpr (V_EARLY)
+      if (b0 == 0) load_rows<ROWB, RPW, NV>(vreg, vbase, vnew, row0 + sub, n, full, append_here, cl);
     // Logits: scale * q_g . K_j in base-2 units, one per (row, g).
 #pragma unroll
     for (int i = 0; i < kTB; ++i) {
@@ -196,7 +207,10 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
         if (cl == 0) s_sh[g][lr] = valid ? a * P.scale_log2e : -INFINITY;
       }
     }
+    if (append_here) store_appended<ROWB, RPW, kTB>(kreg, kbase, row0 + b0 * RPW + sub, n, cl);
   }
+  if constexpr (V_EARLY)
+    if (append_here) store_appended<ROWB, RPW, NV>(vreg, vbase, row0 + sub, n, cl);
   __syncthreads();
 
   // Chunk statistics.  Thread t owns row t of the chunk.
@@ -217,7 +231,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
     m_c[g] = m;
     const float e = fast_exp2(s_own[g] - m);      // 0 for rows past the end
     s_sh[g][tid] = e;
-    rec[g * kChunk + tid] = e;
+    store_stream(&rec[g * kChunk + tid], e);
     const float ws = wave_sum(e);
     if (lane == 0) red_sh[1][g][wave] = ws;
   }
@@ -234,8 +248,8 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
 #pragma unroll
     for (int g = 0; g < G; ++g)
       if (g == tid) {
-        rec[G * (kChunk + D) + 2 * g] = m_c[g];
-        rec[G * (kChunk + D) + 2 * g + 1] = l_c[g];
+        store_stream(&rec[G * (kChunk + D) + 2 * g], m_c[g]);
+        store_stream(&rec[G * (kChunk + D) + 2 * g + 1], l_c[g]);
       }
   }
 
@@ -248,8 +262,10 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
 #pragma unroll
   for (int b0 = 0; b0 < NT; b0 += kTB) {
     uint4 vlate[kTB];
-    if constexpr (!V_EARLY)
+    if constexpr (!V_EARLY) {
       load_rows<ROWB, RPW, kTB>(vlate, vbase, vnew, row0 + b0 * RPW + sub, n, full, append_here, cl);
+      if (append_here) store_appended<ROWB, RPW, kTB>(vlate, vbase, row0 + b0 * RPW + sub, n, cl);
+    }
 #pragma unroll
     for (int i = 0; i < kTB; ++i) {
       float vf[EPL];
@@ -279,7 +295,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
     float o = o_sh[0][g][ch];
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) o += o_sh[w][g][ch];
-    rec[G * kChunk + idx] = o;
+    store_stream(&rec[G * kChunk + idx], o);
   }
 }
 
@@ -287,30 +303,73 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
 template <int D, int G>
 __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P) {
   constexpr int REC = G * (kChunk + D + 2);
-  extern __shared__ float w_sh[];           // [G][nchunks] chunk weights
+  constexpr int GD = G * D;
+  extern __shared__ float dyn_sh[];         // [G][nchunks] chunk weights, then [G][nchunks] chunk sums
   __shared__ float red_sh[kWaves];
+  __shared__ float o_red[kThreads];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const Work wk = locate(P, blockIdx.x);
-  const PairDesc pd = P.pairs[wk.pair_local];
-  const int n = pd.n, h = wk.h, c_own = wk.c, nchunks = wk.nchunks;
-  const int pair = P.pair_base + wk.pair_local;
-  float* out = P.out + (static_cast<int64_t>(pair) * P.n_kv_heads + h) * G * D;
+  const int bid = blockIdx.x;
+
+  // Region: last pair whose first finalize workgroup is <= bid.
+  int lo = 0, hi = P.n_pairs - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (P.pairs[mid].fblock0 <= bid) lo = mid; else hi = mid - 1;
+  }
+  const PairDesc pd = P.pairs[lo];
+  const int n = pd.n;
+  const int nchunks = (n + kChunk - 1) / kChunk;
+  const int nblk = nchunks > 0 ? (nchunks + kFinalChunks - 1) / kFinalChunks : 1;
+  const int local = bid - pd.fblock0;
+  const int h = local / nblk;
+  const int blk = local - h * nblk;
+  const int pair = P.pair_base + lo;
+  float* out = P.out + (static_cast<int64_t>(pair) * P.n_kv_heads + h) * GD;
   if (n == 0) {
-    for (int idx = tid; idx < G * D; idx += kThreads) out[idx] = 0.0f;
+    for (int idx = tid; idx < GD; idx += kThreads) out[idx] = 0.0f;
     return;
   }
   const float* rec0 =
       P.ws + (static_cast<int64_t>(pd.block0) + static_cast<int64_t>(h) * nchunks) * REC;
+  const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
+  float* score = P.score + stream_slot;
+  float* w_sh = dyn_sh;
+  float* l_sh = dyn_sh + G * nchunks;
 
-  // Stream statistics from the chunk statistics; every workgroup of the stream
-  // repeats this small reduction (in the same order, so all agree bit for bit).
+  // Start the loads that do not depend on the statistics: the un-normalised
+  // probabilities and the old scores of this workgroup's slots.
+  float e_r[kFinalChunks][G], old_r[kFinalChunks];
+#pragma unroll
+  for (int i = 0; i < kFinalChunks; ++i) {
+    const int c = blk * kFinalChunks + i;
+    const int j = c * kChunk + tid;
+    old_r[i] = 0.0f;
+#pragma unroll
+    for (int g = 0; g < G; ++g) e_r[i][g] = 0.0f;
+    if (c < nchunks && j < n) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) e_r[i][g] = rec0[static_cast<int64_t>(c) * REC + g * kChunk + tid];
+      if (!(P.append && j == n - 1)) old_r[i] = score[j];   // the appended token starts from zero
+    }
+  }
+
+  // Stream statistics from the chunk statistics.  Every workgroup of the stream
+  // repeats this small reduction in the same order, so all agree bit for bit.
+  for (int c = tid; c < nchunks; c += kThreads) {
+    const float* ml = rec0 + static_cast<int64_t>(c) * REC + G * (kChunk + D);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      w_sh[g * nchunks + c] = ml[2 * g];
+      l_sh[g * nchunks + c] = ml[2 * g + 1];
+    }
+  }
+  __syncthreads();
   for (int g = 0; g < G; ++g) {
     float m = -INFINITY;
-    for (int c = tid; c < nchunks; c += kThreads)
-      m = fmaxf(m, rec0[static_cast<int64_t>(c) * REC + G * (kChunk + D) + 2 * g]);
+    for (int c = tid; c < nchunks; c += kThreads) m = fmaxf(m, w_sh[g * nchunks + c]);
     m = wave_max(m);
     if (lane == 0) red_sh[wave] = m;
     __syncthreads();
@@ -318,10 +377,9 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P
     __syncthreads();
     float l = 0.0f;
     for (int c = tid; c < nchunks; c += kThreads) {
-      const float* ml = rec0 + static_cast<int64_t>(c) * REC + G * (kChunk + D) + 2 * g;
-      const float wgt = fast_exp2(ml[0] - m);
+      const float wgt = fast_exp2(w_sh[g * nchunks + c] - m);
       w_sh[g * nchunks + c] = wgt;
-      l += wgt * ml[1];
+      l += wgt * l_sh[g * nchunks + c];
     }
     l = wave_sum(l);
     if (lane == 0) red_sh[wave] = l;
@@ -332,30 +390,47 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P
     __syncthreads();
   }
 
-  // score_j += sum_g e_gj w_gc for the slots of this chunk; the appended token
-  // starts from zero.
-  const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
-  const int j = c_own * kChunk + tid;
-  if (j < n) {
-    const float* e = rec0 + static_cast<int64_t>(c_own) * REC + tid;
-    float add = 0.0f;
+  // score_j += sum_g e_gj w_gc
 #pragma unroll
-    for (int g = 0; g < G; ++g) add = fmaf(e[g * kChunk], w_sh[g * nchunks + c_own], add);
-    float* score = P.score + stream_slot;
-    const float old = (P.append && j == n - 1) ? 0.0f : score[j];
-    score[j] = old + add;
+  for (int i = 0; i < kFinalChunks; ++i) {
+    const int c = blk * kFinalChunks + i;
+    const int j = c * kChunk + tid;
+    if (c < nchunks && j < n) {
+      float add = 0.0f;
+#pragma unroll
+      for (int g = 0; g < G; ++g) add = fmaf(e_r[i][g], w_sh[g * nchunks + c], add);
+      score[j] = old_r[i] + add;
+    }
   }
-  if (P.append && c_own == 0 && tid == 0) P.pos[stream_slot + n - 1] = pd.pos_new;
+  if (P.append && blk == 0 && tid == 0) P.pos[stream_slot + n - 1] = P.pos_new[lo];
 
-  // out_g = sum_c w_c o_c.  The G*D output channels of the stream are dealt
-  // round-robin to its workgroups; one wave sums one channel over the chunks.
-  for (int idx = c_own + wave * nchunks; idx < G * D; idx += kWaves * nchunks) {
-    const int g = idx / D;
+  // out = sum_c w_c o_c.  The G*D channels of the stream are split evenly over
+  // its workgroups.  Within a workgroup the threads form (channel, slice)
+  // pairs; a slice sums every S-th chunk, then the slices are added in order.
+  const int cpb = (GD + nblk - 1) / nblk;
+  const int ch_first = blk * cpb;
+  const int nch = min(cpb, GD - ch_first);
+  for (int tb = 0; tb < nch; tb += kThreads) {
+    const int tn = min(kThreads, nch - tb);
+    const int S = kThreads / tn;
+    const int ch_l = tid % tn, slice = tid / tn;
     float o = 0.0f;
-    for (int c = lane; c < nchunks; c += 64)
-      o = fmaf(w_sh[g * nchunks + c], rec0[static_cast<int64_t>(c) * REC + G * kChunk + idx], o);
-    o = wave_sum(o);
-    if (lane == 0) out[idx] = o;
+    if (slice < S) {
+      const int idx = ch_first + tb + ch_l;
+      const int g = idx / D;
+      const float* col = rec0 + G * kChunk + idx;
+#pragma unroll 4
+      for (int c = slice; c < nchunks; c += S)
+        o = fmaf(w_sh[g * nchunks + c], col[static_cast<int64_t>(c) * REC], o);
+    }
+    __syncthreads();
+    o_red[tid] = o;
+    __syncthreads();
+    if (tid < tn) {
+      float tot = o_red[tid];
+      for (int sl = 1; sl < S; ++sl) tot += o_red[sl * tn + tid];
+      out[ch_first + tb + tid] = tot;
+    }
   }
 }
 
@@ -414,6 +489,7 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
   const int64_t n_pairs = static_cast<int64_t>(layer_end - layer_begin) * B;
   int64_t total_blocks = 0;
   int64_t max_chunks = 0;
+  const int fin_chunks = kFinalChunks;
   for (int64_t i = 0; i < n_pairs; ++i) {
     const int64_t n = static_cast<int64_t>(cache->len[first + i]) + (append ? 1 : 0);
     if (n > cache->cap[first + i]) return XKV_ERR_CAPACITY;
@@ -426,7 +502,7 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
   if (static_cast<uint64_t>(total_blocks) * rec * sizeof(float) > workspace_bytes)
     return XKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(workspace) & 3u) return XKV_ERR_INVALID_ARG;
-  const size_t fin_lds = static_cast<size_t>(std::max<int64_t>(max_chunks, 1)) * G * sizeof(float);
+  const size_t fin_lds = static_cast<size_t>(std::max<int64_t>(max_chunks, 1)) * G * 2 * sizeof(float);
   if (fin_lds > 48 * 1024) return XKV_ERR_UNSUPPORTED;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -441,7 +517,7 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
   int64_t blocks_done = 0;
   for (int64_t g0 = 0; g0 < n_pairs; g0 += kMaxPairs) {
     const int np = static_cast<int>(std::min<int64_t>(kMaxPairs, n_pairs - g0));
-    int64_t blocks = 0;
+    int64_t blocks = 0, fblocks = 0;
     for (int i = 0; i < np; ++i) {
       const int64_t idx = first + g0 + i;
       PairDesc& pd = P.pairs[i];
@@ -449,8 +525,11 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
       pd.cap = cache->cap[idx];
       pd.n = cache->len[idx] + (append ? 1 : 0);
       pd.block0 = static_cast<int32_t>(blocks);
-      pd.pos_new = append ? pos_new[(g0 + i) % B] : 0;
-      blocks += std::max<int64_t>(ceil_div(pd.n, kChunk), 1) * hkv;
+      pd.fblock0 = static_cast<int32_t>(fblocks);
+      P.pos_new[i] = append ? pos_new[(g0 + i) % B] : 0;
+      const int64_t chunks = ceil_div(pd.n, kChunk);
+      blocks += std::max<int64_t>(chunks, 1) * hkv;
+      fblocks += std::max<int64_t>(ceil_div(chunks, fin_chunks), 1) * hkv;
     }
     if (blocks > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;
     P.n_pairs = np;
@@ -460,7 +539,7 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
     hipLaunchKernelGGL(partial, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, stream, P);
     profile_end(tok, stream);
     if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
-    hipLaunchKernelGGL(finalize, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), fin_lds,
+    hipLaunchKernelGGL(finalize, dim3(static_cast<unsigned>(fblocks)), dim3(kThreads), fin_lds,
                        stream, P);
     if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     blocks_done += blocks;

@@ -38,6 +38,11 @@ __device__ __forceinline__ uint4 load_stream16(const void* p) {
   return make_uint4(t.x, t.y, t.z, t.w);
 }
 
+// Store of a result that the same kernel never reads back.  Written through the
+// cache without staying resident; next to a large streaming read this costs
+// measurably less read bandwidth than an ordinary write-back store.
+__device__ __forceinline__ void store_stream(float* p, float v) { __builtin_nontemporal_store(v, p); }
+
 // One DPP move: every lane reads the lane that `kCtrl` names within its row of
 // 16 lanes.  Only controls whose source lane always exists are used here.
 template <int kCtrl>
