@@ -60,27 +60,13 @@ def make_budgets(xkv, wl, w):
     return np.ascontiguousarray(bud, dtype=np.int32), info
 
 
-def repack(xkv, cache, budgets, slack=1):
+def repack(cache, budgets, slack=1):
     """Moves the live tokens into a cache whose streams have room for budget +
     slack tokens only (rounded up to 8 slots): the memory the method saves is
     actually released, and the steady state runs in the small arena."""
     import numpy as np
-    import torch
-    L, B = cache.n_layers, cache.batch
     caps = ((budgets.astype(np.int64) + slack + 7) // 8 * 8).astype(np.int32)
-    new = xkv.XkvCache(L, B, cache.n_q_heads, cache.n_kv_heads, cache.head_dim, cache.dtype, caps)
-    new.len[:] = cache.len
-    for l in range(L):
-        for b in range(B):
-            n = cache.length(l, b)
-            for h in range(cache.n_kv_heads):
-                a, d = cache.stream_slot(l, b, h), new.stream_slot(l, b, h)
-                new.k[d:d + n] = cache.k[a:a + n]
-                new.v[d:d + n] = cache.v[a:a + n]
-                new.score[d:d + n] = cache.score[a:a + n]
-                new.pos[d:d + n] = cache.pos[a:a + n]
-    torch.cuda.synchronize()
-    return new
+    return cache.resized(caps)
 
 
 def algorithmic_bytes(w, lens_after_append):
@@ -206,7 +192,7 @@ def main():
             step0_ms = (time.perf_counter() - t0) * 1e3
             if not args.keep_prompt_arena:
                 # the prompt-sized arena has done its job: continue in one sized by the budgets
-                packed = repack(xkv, cache, budgets)
+                packed = repack(cache, budgets)
                 del ws, cache
                 state["cache"] = None
                 state["ws"] = None

@@ -161,6 +161,29 @@ class XkvCache:
         s.cap = self.cap.ctypes.data
         s.len = self.len.ctypes.data
 
+    def resized(self, caps) -> "XkvCache":
+        """A copy of the live tokens in a new cache whose streams have the
+        capacities ``caps`` [L, B] (each >= the current length).  Plain device
+        copies; used to leave the prompt-sized arena once the first eviction has
+        shrunk every layer to its budget."""
+        import torch
+        new = XkvCache(self.n_layers, self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim,
+                       self.dtype, caps, device=self.k.device)
+        if np.any(new.cap < self.len):
+            raise ValueError("new capacity below the current length")
+        new.len[:] = self.len
+        for l in range(self.n_layers):
+            for b in range(self.batch):
+                n = self.length(l, b)
+                for h in range(self.n_kv_heads):
+                    a, d = self.stream_slot(l, b, h), new.stream_slot(l, b, h)
+                    new.k[d:d + n] = self.k[a:a + n]
+                    new.v[d:d + n] = self.v[a:a + n]
+                    new.score[d:d + n] = self.score[a:a + n]
+                    new.pos[d:d + n] = self.pos[a:a + n]
+        torch.cuda.synchronize()
+        return new
+
     def stream_slot(self, l, b, h) -> int:
         i = l * self.batch + b
         return int(self.region_off[i]) + h * int(self.cap[i])
