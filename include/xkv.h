@@ -177,6 +177,17 @@ xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, int32_t laye
                              void* hip_stream);
 
 /*
+ * Process-wide options, for tests and benchmarks.
+ *   XKV_CFG_ATTEND_PATH  how xkv_decode_attend_score runs: 0 = the library's
+ *       choice (default; at present the two kernels); 1 = a streaming kernel plus
+ *       a finalize kernel; 2 = one fused cooperative launch that keeps the logits
+ *       in LDS, or XKV_ERR_UNSUPPORTED when the call does not fit the chip at once.
+ * Errors: INVALID_ARG for an unknown key or value.
+ */
+enum { XKV_CFG_ATTEND_PATH = 1 };
+xkv_status xkv_configure(int32_t key, int64_t value);
+
+/*
  * Per-kernel timing for benchmarks.  While enabled, the two calls above record
  * HIP events around their dominant kernel (the K/V streaming kernel of
  * xkv_decode_attend_score, kernel index 0, and the selection kernel of

@@ -8,11 +8,13 @@ PyTorch supplies device memory and streams, nothing else.
 from .binding import (  # noqa: F401
     XKV_ALLOC_TARGET_RAVG,
     XKV_ALLOC_TOTAL_SIZE,
+    XKV_CFG_ATTEND_PATH,
     XkvCache,
     XkvError,
     load,
     status_string,
     xkv_allocate_budgets,
+    xkv_configure,
     xkv_decode_attend_score,
     xkv_evict_compact,
     xkv_profile_enable,

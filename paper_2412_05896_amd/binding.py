@@ -16,7 +16,9 @@ XKV_ALLOC_TOTAL_SIZE, XKV_ALLOC_TARGET_RAVG = 0, 1
 EXPORTS = (
     "xkv_status_string", "xkv_allocate_budgets", "xkv_workspace_bytes",
     "xkv_decode_attend_score", "xkv_evict_compact", "xkv_profile_enable", "xkv_profile_read",
+    "xkv_configure",
 )
+XKV_CFG_ATTEND_PATH = 1
 
 
 class XkvError(RuntimeError):
@@ -67,6 +69,8 @@ def load():
     lib.xkv_evict_compact.argtypes = [
         C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
         C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.xkv_configure.restype = C.c_int32
+    lib.xkv_configure.argtypes = [C.c_int32, C.c_int64]
     lib.xkv_profile_enable.restype = C.c_int32
     lib.xkv_profile_enable.argtypes = [C.c_int32]
     lib.xkv_profile_read.restype = C.c_int32
@@ -219,6 +223,10 @@ def xkv_evict_compact(cache: XkvCache, layer_begin, layer_end, budgets, workspac
         int(n_protect), _ptr(kept_idx_out), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     _check(st, "xkv_evict_compact")
+
+
+def xkv_configure(key: int, value: int):
+    _check(load().xkv_configure(int(key), int(value)), "xkv_configure")
 
 
 def xkv_profile_enable(on: bool):

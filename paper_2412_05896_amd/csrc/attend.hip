@@ -2,20 +2,29 @@
 // per-token attention-mass scoring (Eq. 1 and Eq. 2 of the paper; scoring is the
 // Select + Merge step of Eq. 3 with the decode query as observation row).
 //
-// Two kernels per launch group, no atomics:
+// A stream (layer, sequence, KV head) is cut into strips of `strip_rows` slots.
+// Two kernels per launch, no atomics, results bit-reproducible:
 //
-//  attend_partial   one workgroup per (stream, chunk of 256 slots).  Streams
-//                   the chunk's K and V rows once with 16-byte loads, computes
-//                   the G logits of every row, the chunk's softmax statistics
-//                   (max m_c, sum l_c), the un-normalised probabilities
-//                   e_j = 2^(s_j - m_c) and the partial output sum_j e_j V_j,
-//                   and writes all of that to the workspace.  The workgroup
-//                   that owns the last slot also stores the appended token.
-//  attend_finalize  one workgroup per (stream, 4 chunks).  Every workgroup merges
-//                   the chunk statistics of its stream into (m, l) and the chunk
-//                   weights w_c = 2^(m_c - m) / l, adds p_j = e_j w_c, summed over
-//                   the G query heads, to score[j] for its own slots, and
-//                   computes its share of the channels of out = sum_c w_c o_c.
+//  streaming kernel  one workgroup per (stream, strip).  Reads the strip's K and
+//                    V rows once with 16-byte non-temporal loads and writes, per
+//                    query head of the group: the logit of every slot, and the
+//                    strip's softmax statistics (max m_s, sum l_s) and partial
+//                    output o_s = sum_j 2^(s_j - m_s) V_j.  The workgroup that
+//                    owns the last slot also stores the appended token.
+//                    Two variants:
+//                      attend_strip   (G <= 2) every wave runs its own online
+//                                     softmax over interleaved groups of rows,
+//                                     with the next group's loads in flight
+//                                     while the current one is used; the four
+//                                     waves merge once at the end; logits are
+//                                     collected in LDS and written in one burst.
+//                      attend_chunk   (G >= 4) strips of 256 slots handled by the
+//                                     whole workgroup in one pass.
+//  attend_finalize   one workgroup per (stream, strip).  Merges the strip
+//                    statistics of its stream into (m, l), adds
+//                    p_j = 2^(s_j - m) / l, summed over the G query heads, to
+//                    score[j] for its own slots, and computes its share of the
+//                    channels of out = sum_s 2^(m_s - m) o_s / l.
 //
 // The ragged geometry travels in the kernel arguments (at most kMaxPairs
 // (layer, sequence) regions per launch), so nothing is copied to the device
@@ -25,6 +34,7 @@
 #include <algorithm>
 #include <cmath>
 #include <limits>
+#include <numeric>
 #include <vector>
 
 #include "device_util.h"
@@ -35,13 +45,14 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
+constexpr int kMaxHeld = 64;            // strips one workgroup of the fused kernel can hold
 
 struct PairDesc {
   int64_t slot0;    // first slot of the region
   int32_t cap;      // slots per stream
   int32_t n;        // live slots, the appended token included
-  int32_t block0;   // first streaming-kernel workgroup of the region in this launch
-  int32_t fblock0;  // first finalize-kernel workgroup of the region in this launch
+  int32_t strip0;   // first strip record of the region in the launch's workspace (canonical order)
+  int32_t full0;    // first streaming workgroup (fused kernel: queue position) among the full strips
 };
 
 struct AttendParams {
@@ -53,39 +64,54 @@ struct AttendParams {
   float* score;
   int32_t* pos;
   float* out;
-  float* ws;              // first record of this launch
+  float* ws;              // first strip record of this launch
+  unsigned* barrier;      // fused kernel: {arrival count, timeout flag, queue head, unused}, zero at launch
   float scale_log2e;      // softmax scale times log2(e): logits live in the base-2 domain
   int32_t n_pairs;
   int32_t pair_base;      // index of pairs[0] relative to (layer_begin, sequence 0)
   int32_t n_kv_heads;
   int32_t append;
+  int32_t strip_rows;     // slots per strip, a multiple of kChunk
+  int32_t full_blocks;    // streaming workgroups that own a full strip; the rest own tail strips
+  int32_t n_tail_pairs;   // regions whose streams end in a partial strip
+  int32_t rec_floats;     // floats per strip record in the workspace
+  int32_t lds_rows;       // fused kernel: rows of logits a workgroup can hold
   PairDesc pairs[kMaxPairs];
-  int32_t pos_new[kMaxPairs];  // original position of the token appended to each region
+  int32_t pos_new[kMaxPairs];    // original position of the token appended to each region
+  uint8_t tail_order[kMaxPairs]; // regions with a partial last strip, longest tail first
 };
 
-// Chunks of one stream that one workgroup of the finalize kernel covers.
-constexpr int kFinalChunks = 4;
-
-// Finds the region, KV head and chunk of workgroup `bid` (same numbering in
-// both kernels): the last pair whose first workgroup is <= bid.  A stream with
-// no live slot still owns one workgroup.
-struct Work { int pair_local, h, c, nchunks; };
-__device__ __forceinline__ Work locate(const AttendParams& P, int bid) {
-  int lo = 0, hi = P.n_pairs - 1;
-  while (lo < hi) {
-    const int mid = (lo + hi + 1) >> 1;
-    if (P.pairs[mid].block0 <= bid) lo = mid; else hi = mid - 1;
-  }
-  Work w;
-  w.pair_local = lo;
-  w.nchunks = (P.pairs[lo].n + kChunk - 1) / kChunk;
-  const int per_head = w.nchunks > 0 ? w.nchunks : 1;
-  const int local = bid - P.pairs[lo].block0;
-  w.h = local / per_head;
-  w.c = local - w.h * per_head;
-  return w;
+// Floats per strip record: per query head, strip_rows logits, D partial outputs, (m, l).
+__host__ __device__ inline int64_t record_floats(int group, int head_dim, int strip_rows) {
+  return static_cast<int64_t>(group) * (strip_rows + head_dim + 2);
 }
 
+struct StripWork { int pair_local, h, s; };
+
+// Streaming kernels: full strips first (all the same size), then the partial
+// last strips of the streams, longest first, so that short work fills the end
+// of the launch.
+__device__ __forceinline__ StripWork locate_stream_block(const AttendParams& P, int bid) {
+  StripWork w;
+  if (bid < P.full_blocks) {
+    int lo = 0, hi = P.n_pairs - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (P.pairs[mid].full0 <= bid) lo = mid; else hi = mid - 1;
+    }
+    const int nfull = P.pairs[lo].n / P.strip_rows;
+    const int local = bid - P.pairs[lo].full0;
+    w.pair_local = lo;
+    w.h = local / nfull;
+    w.s = local - w.h * nfull;
+  } else {
+    const int t = bid - P.full_blocks;
+    w.pair_local = P.tail_order[t / P.n_kv_heads];
+    w.h = t % P.n_kv_heads;
+    w.s = P.pairs[w.pair_local].n / P.strip_rows;
+  }
+  return w;
+}
 
 // Loads kNB consecutive wave-wide fragments of a stream (rows first_row,
 // first_row + RPW, ...) into registers, without branches: rows at or past n are
@@ -127,17 +153,443 @@ __device__ __forceinline__ void store_appended(const uint4 (&reg)[kNB], char* ba
   }
 }
 
-// ---------------------------------------------------------------------------
+// Addresses shared by the streaming kernels.
 template <typename T, int D, int G>
-__global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P) {
-  constexpr int EPL = T::kPerLane;          // elements per lane per load
-  constexpr int LPR = D / EPL;              // lanes that cover one row
-  constexpr int RPW = 64 / LPR;             // rows per wave-wide load
+struct StreamCtx {
+  static constexpr int EPL = T::kPerLane;    // elements per lane per load
+  static constexpr int LPR = D / EPL;        // lanes that cover one row
+  static constexpr int RPW = 64 / LPR;       // rows per wave-wide load
+  static constexpr int ROWB = D * T::kBytes; // bytes per row
+  int n, h, s, pair;
+  char* kbase;
+  char* vbase;
+  const char* knew;
+  const char* vnew;
+  bool append_here;
+  float* rec;                                // this strip's record
+
+  // Stream (region pair_local, head h_) of the launch; append_here says whether
+  // the caller's row range may hold the appended token.
+  __device__ __forceinline__ void init_stream(const AttendParams& P, int pair_local, int h_,
+                                              bool may_append) {
+    const PairDesc pd = P.pairs[pair_local];
+    n = pd.n; h = h_; s = 0;
+    pair = P.pair_base + pair_local;
+    const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
+    kbase = static_cast<char*>(P.k) + stream_slot * ROWB;
+    vbase = static_cast<char*>(P.v) + stream_slot * ROWB;
+    append_here = P.append && may_append;
+    knew = vnew = nullptr;
+    if (append_here) {
+      const int64_t r = (static_cast<int64_t>(pair) * P.n_kv_heads + h) * ROWB;
+      knew = static_cast<const char*>(P.k_new) + r;
+      vnew = static_cast<const char*>(P.v_new) + r;
+    }
+    rec = nullptr;
+  }
+  __device__ __forceinline__ void init(const AttendParams& P, const StripWork& wk) {
+    const PairDesc pd = P.pairs[wk.pair_local];
+    const int nstrips = (pd.n + P.strip_rows - 1) / P.strip_rows;
+    init_stream(P, wk.pair_local, wk.h, wk.s == nstrips - 1);   // row n-1 lies in the last strip
+    s = wk.s;
+    rec = P.ws + (static_cast<int64_t>(pd.strip0) + static_cast<int64_t>(h) * nstrips + s) * P.rec_floats;
+  }
+  // Queries of the group, widened to fp32, this lane's columns only.
+  __device__ __forceinline__ void load_q(const AttendParams& P, int cl, float (&qf)[G][EPL]) const {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const int64_t hq = (static_cast<int64_t>(pair) * P.n_kv_heads + h) * G + g;
+      const uint4 raw =
+          *reinterpret_cast<const uint4*>(static_cast<const char*>(P.q) + hq * ROWB + cl * 16);
+      Unpack<T>::run(raw, qf[g]);
+    }
+  }
+};
+
+// ---------------------------------------------------------------------------
+// One pass of a workgroup over rows [r_begin, r_end) of one stream.  A round is
+// TPI wave-wide loads of K and of V per wave (TPI * RPW rows), the four waves
+// taking consecutive row groups.  Each wave keeps its own running (m, l, o) and
+// rescales them when the maximum moves; two register buffers alternate so that
+// the loads of round r+1 are in flight while round r is computed.  The logits go
+// to LDS (lg[g * lg_stride + row - r_begin]); the four waves merge at the end
+// and the segment's partial output o[G][D] and statistics ml[G][2] are written
+// with `put`.  Ends with a barrier, after which mrg_sh may be reused.
+template <typename T, int D, int G, int TPI, typename Put>
+__device__ __forceinline__ void segment_pass(const AttendParams& P, const StreamCtx<T, D, G>& cx,
+                                             int r_begin, int r_end, float* lg, int lg_stride,
+                                             float (*mrg_sh)[G][D + 2], float* rec_o, float* rec_ml,
+                                             Put put) {
+  using Ctx = StreamCtx<T, D, G>;
+  constexpr int EPL = Ctx::EPL, LPR = Ctx::LPR, RPW = Ctx::RPW, ROWB = Ctx::ROWB;
+  constexpr int RPI = TPI * RPW;            // rows per wave per round
+  constexpr int RPR = RPI * kWaves;         // rows per workgroup per round
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int sub = lane / LPR;               // row within a wave-wide load
+  const int cl = lane % LPR;                // 16-byte column of the row
+  const int n = cx.n;
+  const int rows = r_end - r_begin;
+  const int rounds = (rows + RPR - 1) / RPR;
+  const bool append_here = cx.append_here && r_end == n;   // this segment holds row n-1
+  const int n_plain = n - (append_here ? 1 : 0);           // rows below this come straight from the cache
+
+  float qf[G][EPL];
+  cx.load_q(P, cl, qf);
+
+  float m_run[G], l_run[G], acc[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m_run[g] = -INFINITY;
+    l_run[g] = 0.0f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.0f;
+  }
+
+  struct Buf { uint4 k[TPI]; uint4 v[TPI]; };
+  auto issue = [&](Buf& b, int round) {
+    const int first = r_begin + round * RPR + wave * RPI;
+    const bool full = first + RPI <= n_plain;
+    load_rows<ROWB, RPW, TPI>(b.k, cx.kbase, cx.knew, first + sub, n, full, append_here, cl);
+    load_rows<ROWB, RPW, TPI>(b.v, cx.vbase, cx.vnew, first + sub, n, full, append_here, cl);
+  };
+  auto compute = [&](Buf& b, int round) {
+    const int first = r_begin + round * RPR + wave * RPI + sub;
+    float sv[TPI][G];
+#pragma unroll
+    for (int i = 0; i < TPI; ++i) {
+      float kf[EPL];
+      Unpack<T>::run(b.k[i], kf);
+      const int row = first + i * RPW;
+      const bool valid = row < r_end;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float a = 0.0f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) a = fmaf(kf[e], qf[g][e], a);
+        a = group_sum<LPR>(a);
+        sv[i][g] = valid ? a * P.scale_log2e : -INFINITY;
+        if (cl == 0 && valid) lg[g * lg_stride + (row - r_begin)] = sv[i][g];
+      }
+    }
+    float pv[TPI][G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float gm = sv[0][g];
+#pragma unroll
+      for (int i = 1; i < TPI; ++i) gm = fmaxf(gm, sv[i][g]);
+#pragma unroll
+      for (int off = LPR; off < 64; off <<= 1) gm = fmaxf(gm, __shfl_xor(gm, off));
+      const float m_new = fmaxf(m_run[g], gm);
+      const float m_safe = m_new == -INFINITY ? 0.0f : m_new;   // a wave may see no live row at all
+      const float rescale = fast_exp2(m_run[g] - m_safe);
+      m_run[g] = m_new;
+      float l = l_run[g] * rescale;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] *= rescale;
+#pragma unroll
+      for (int i = 0; i < TPI; ++i) {
+        pv[i][g] = fast_exp2(sv[i][g] - m_safe);
+        l += pv[i][g];
+      }
+      l_run[g] = l;
+    }
+#pragma unroll
+    for (int i = 0; i < TPI; ++i) {
+      float vf[EPL];
+      Unpack<T>::run(b.v[i], vf);
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(pv[i][g], vf[e], acc[g][e]);
+    }
+    if (append_here) {
+      store_appended<ROWB, RPW, TPI>(b.k, cx.kbase, first, n, cl);
+      store_appended<ROWB, RPW, TPI>(b.v, cx.vbase, first, n, cl);
+    }
+  };
+
+  Buf A, B;
+  issue(A, 0);
+  for (int r = 0; r < rounds; r += 2) {
+    if (r + 1 < rounds) issue(B, r + 1);
+    compute(A, r);
+    if (r + 1 < rounds) {
+      if (r + 2 < rounds) issue(A, r + 2);
+      compute(B, r + 1);
+    }
+  }
+
+  // Fold the row groups of the wave together (each lane so far summed only the
+  // rows of its own group), then merge the four waves.
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float l = l_run[g];
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) l += __shfl_xor(l, off);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      float x = acc[g][e];
+#pragma unroll
+      for (int off = LPR; off < 64; off <<= 1) x += __shfl_xor(x, off);
+      if (sub == 0) mrg_sh[wave][g][cl * EPL + e] = x;
+    }
+    if (lane == 0) {
+      mrg_sh[wave][g][D] = m_run[g];
+      mrg_sh[wave][g][D + 1] = l;
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * (D + 1); idx += kThreads) {
+    const int g = idx / (D + 1), ch = idx - g * (D + 1);     // ch == D: the sum l
+    float m = mrg_sh[0][g][D];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) m = fmaxf(m, mrg_sh[w][g][D]);
+    const int col = ch < D ? ch : D + 1;
+    float tot = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) tot += mrg_sh[w][g][col] * fast_exp2(mrg_sh[w][g][D] - m);
+    if (ch < D) {
+      put(&rec_o[g * D + ch], tot);
+    } else {
+      put(&rec_ml[2 * g], m);
+      put(&rec_ml[2 * g + 1], tot);
+    }
+  }
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------------------
+// Strip kernel for small query groups: one workgroup per (stream, strip); the
+// strip's logits are collected in LDS and written in one burst.
+template <typename T, int D, int G, int TPI>
+__global__ __launch_bounds__(kThreads) void attend_strip(const AttendParams P) {
+  extern __shared__ float lg_sh[];          // [G][strip_rows] logits of the strip
+  __shared__ float mrg_sh[kWaves][G][D + 2];
+
+  StreamCtx<T, D, G> cx;
+  cx.init(P, locate_stream_block(P, blockIdx.x));
+  const int strip_rows = P.strip_rows;
+  const int r_begin = cx.s * strip_rows;
+  const int r_end = min(cx.n, r_begin + strip_rows);
+  const int rows = r_end - r_begin;
+  float* rec = cx.rec;
+  segment_pass<T, D, G, TPI>(P, cx, r_begin, r_end, lg_sh, strip_rows, mrg_sh,
+                             rec + G * strip_rows, rec + G * (strip_rows + D),
+                             [](float* p, float v) { store_stream(p, v); });
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+    for (int j = threadIdx.x; j < rows; j += kThreads)
+      store_stream(&rec[g * strip_rows + j], lg_sh[g * strip_rows + j]);
+}
+
+// ---------------------------------------------------------------------------
+// Fused kernel: the whole call in one cooperative launch, nothing but strip-sized
+// records written while K and V stream in.  The strips of the launch (numbered
+// as for the streaming kernels: full strips first, then the partial ones,
+// longest first) form a queue; every workgroup takes strips from it for as long
+// as its LDS has room for another strip's logits, runs the pass over each and
+// publishes the strip's (o, m, l) record.  After a grid-wide barrier each
+// workgroup merges the records of the streams its strips belong to, turns the
+// logits it holds into probabilities and adds them to the scores; the holder of a
+// stream's first strip writes the stream's output.  The K/V read is thus free of
+// concurrent per-token write traffic, which on this GPU costs read bandwidth far
+// beyond its volume.
+//
+// Grid-wide barrier for a cooperative launch (all workgroups resident).  The
+// counter starts at zero; every workgroup adds one and waits until all have.
+// No cache maintenance is tied to it: what crosses it (the strip records) is
+// written and read with agent-scope accesses that bypass the per-XCD caches, and
+// the barrier before the count makes sure those writes have been acknowledged.
+// The wait is bounded: should the count never fill (it cannot, unless the
+// launch was not resident), the workgroup gives up, raises the flag next to the
+// counter and goes on, so the kernel always ends.
+__device__ __forceinline__ void grid_barrier(unsigned* counter, unsigned n_wgs) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned spins = 0;
+    while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < n_wgs) {
+      __builtin_amdgcn_s_sleep(4);
+      if (++spins > (1u << 24)) {
+        __hip_atomic_store(counter + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        break;
+      }
+    }
+  }
+  __syncthreads();
+}
+
+// control words of a fused launch: {barrier count, barrier timeout flag, queue head, unused}
+__global__ void fused_prepare(unsigned* control) {
+  if (threadIdx.x < 4) control[threadIdx.x] = 0u;
+}
+
+__device__ __forceinline__ float load_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <typename T, int D, int G, int TPI>
+__global__ __launch_bounds__(kThreads) void attend_fused(const AttendParams P) {
+  constexpr int SEG = G * (D + 2);          // floats per strip record: o[G][D], (m, l)[G]
+  extern __shared__ float lg_sh[];          // [G][lds_rows] logits of the strips held
+  __shared__ float mrg_sh[kWaves][G][D + 2];
+  __shared__ float red_sh[2][G][kWaves];
+  __shared__ float st_sh[G][2];
+  __shared__ int held_sh[kMaxHeld];         // queue positions of the strips held
+  __shared__ int next_sh;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int strip_rows = P.strip_rows;
+  const int lds_rows = P.lds_rows;
+  const int n_units = P.full_blocks + P.n_tail_pairs * P.n_kv_heads;
+  unsigned* queue = P.barrier + 2;
+
+  // ---- phase 1: take strips while there is room; logits to LDS, one record each ----
+  int n_held = 0;
+  while (n_held < kMaxHeld && (n_held + 1) * strip_rows <= lds_rows) {
+    if (tid == 0)
+      next_sh = static_cast<int>(__hip_atomic_fetch_add(queue, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    __syncthreads();
+    const int unit = next_sh;
+    __syncthreads();
+    if (unit >= n_units) break;
+    if (tid == 0) held_sh[n_held] = unit;
+    StreamCtx<T, D, G> cx;
+    cx.init(P, locate_stream_block(P, unit));
+    const int r_begin = cx.s * strip_rows;
+    const int r_end = min(cx.n, r_begin + strip_rows);
+    segment_pass<T, D, G, TPI>(P, cx, r_begin, r_end, lg_sh + n_held * strip_rows, lds_rows, mrg_sh,
+                               cx.rec, cx.rec + G * D, [](float* p, float v) {
+                                 __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                               });
+    ++n_held;
+  }
+#ifdef XKV_EXP_NOSYNC
+  return;
+#endif
+  grid_barrier(P.barrier, gridDim.x);
+#ifdef XKV_EXP_NOPHASE2
+  return;
+#endif
+
+  // ---- phase 2: normalise, add to the scores, write the outputs -----------------
+  for (int k = 0; k < n_held; ++k) {
+    const StripWork wk = locate_stream_block(P, held_sh[k]);
+    const PairDesc pd = P.pairs[wk.pair_local];
+    const int n = pd.n;
+    const int nstrips = (n + strip_rows - 1) / strip_rows;
+    const float* rec0 = P.ws + (static_cast<int64_t>(pd.strip0) + static_cast<int64_t>(wk.h) * nstrips) * SEG;
+    // Stream statistics from the strip statistics, 256 strips at a time.
+    float m_run[G], l_run[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) { m_run[g] = -INFINITY; l_run[g] = 0.0f; }
+    for (int base = 0; base < nstrips; base += kThreads) {
+      const int c = base + tid;
+      float mc[G], lc[G];
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        mc[g] = -INFINITY;
+        lc[g] = 0.0f;
+        if (c < nstrips) {
+          mc[g] = load_agent(rec0 + static_cast<int64_t>(c) * SEG + G * D + 2 * g);
+          lc[g] = load_agent(rec0 + static_cast<int64_t>(c) * SEG + G * D + 2 * g + 1);
+        }
+      }
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float wm = wave_max(mc[g]);
+        if (lane == 0) red_sh[0][g][wave] = wm;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float m_new = m_run[g];
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) m_new = fmaxf(m_new, red_sh[0][g][w]);
+        const float contrib = lc[g] * fast_exp2(mc[g] - m_new);     // m_new is finite: some strip has a live row
+        const float wsum = wave_sum(contrib);
+        if (lane == 0) red_sh[1][g][wave] = wsum;
+        l_run[g] *= fast_exp2(m_run[g] - m_new);
+        m_run[g] = m_new;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) l_run[g] += red_sh[1][g][w];
+      }
+      __syncthreads();
+    }
+    if (tid == 0) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) { st_sh[g][0] = m_run[g]; st_sh[g][1] = 1.0f / l_run[g]; }
+    }
+    __syncthreads();
+
+    const int r_begin = wk.s * strip_rows;
+    const int r_end = min(n, r_begin + strip_rows);
+    const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(wk.h) * pd.cap;
+    float* score = P.score + stream_slot;
+    const float* lg = lg_sh + k * strip_rows;
+    // Batches of eight rows per thread: all eight score loads go out before the first is used.
+    for (int j0 = tid; j0 < r_end - r_begin; j0 += 8 * kThreads) {
+      float old[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int row = r_begin + j0 + u * kThreads;
+        old[u] = (row < r_end && !(P.append && row == n - 1)) ? score[row] : 0.0f;   // the appended token starts from zero
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int jj = j0 + u * kThreads;
+        if (r_begin + jj < r_end) {
+          float add = 0.0f;
+#pragma unroll
+          for (int g = 0; g < G; ++g) add = fmaf(fast_exp2(lg[g * lds_rows + jj] - st_sh[g][0]), st_sh[g][1], add);
+          score[r_begin + jj] = old[u] + add;
+        }
+      }
+    }
+    if (P.append && r_end == n && tid == 0) P.pos[stream_slot + n - 1] = P.pos_new[wk.pair_local];
+    if (wk.s == 0) {
+      const int pair = P.pair_base + wk.pair_local;
+      float* out = P.out + (static_cast<int64_t>(pair) * P.n_kv_heads + wk.h) * G * D;
+      for (int idx = tid; idx < G * D; idx += kThreads) {
+        const int g = idx / D;
+        float o = 0.0f;
+#pragma unroll 4
+        for (int c = 0; c < nstrips; ++c) {
+          const float* r = rec0 + static_cast<int64_t>(c) * SEG;
+          o = fmaf(load_agent(r + idx), fast_exp2(load_agent(r + G * D + 2 * g) - st_sh[g][0]), o);
+        }
+        out[idx] = o * st_sh[g][1];
+      }
+    }
+    __syncthreads();
+  }
+  // Streams without a live slot: zero output rows.
+  if (blockIdx.x == 0)
+    for (int p = 0; p < P.n_pairs; ++p)
+      if (P.pairs[p].n == 0) {
+        float* out = P.out + static_cast<int64_t>(P.pair_base + p) * P.n_kv_heads * G * D;
+        for (int idx = tid; idx < P.n_kv_heads * G * D; idx += kThreads) out[idx] = 0.0f;
+      }
+}
+
+// ---------------------------------------------------------------------------
+// Chunk kernel for larger query groups: strips are kChunk slots, the workgroup
+// makes one pass (thread t owns slot t for the statistics).
+template <typename T, int D, int G>
+__global__ __launch_bounds__(kThreads) void attend_chunk(const AttendParams P) {
+  using Ctx = StreamCtx<T, D, G>;
+  constexpr int EPL = Ctx::EPL, LPR = Ctx::LPR, RPW = Ctx::RPW, ROWB = Ctx::ROWB;
   constexpr int NT = 64 / RPW;              // loads per wave for its 64 rows
-  constexpr int ROWB = D * T::kBytes;       // bytes per row
-  constexpr int REC = G * (kChunk + D + 2);
   constexpr int kTB = NT < 16 ? NT : 16;    // wave-wide loads in flight per batch
-  constexpr bool V_EARLY = NT <= 16 && G <= 2;
 
   __shared__ float s_sh[G][kChunk];         // logits, then probabilities
   __shared__ float red_sh[2][G][kWaves];
@@ -146,52 +598,23 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int sub = lane / LPR;               // row within a wave-wide load
-  const int cl = lane % LPR;                // 16-byte column of the row
-  const int bid = blockIdx.x;
+  const int sub = lane / LPR;
+  const int cl = lane % LPR;
 
-  const Work wk = locate(P, bid);
-  const int lo = wk.pair_local;
-  const PairDesc pd = P.pairs[lo];
-  const int n = pd.n;
-  if (n == 0) return;                       // an empty stream: the finalize kernel zeroes its output
-  const int h = wk.h, c = wk.c;
-  const int pair = P.pair_base + lo;
-  const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
-  char* kbase = static_cast<char*>(P.k) + stream_slot * ROWB;
-  char* vbase = static_cast<char*>(P.v) + stream_slot * ROWB;
+  Ctx cx;
+  cx.init(P, locate_stream_block(P, blockIdx.x));
+  const int n = cx.n, c = cx.s;
   const int row0 = c * kChunk + wave * 64;
-  const bool append_here = P.append && (n - 1) / kChunk == c;
-  const char* knew = nullptr;
-  const char* vnew = nullptr;
-  if (append_here) {
-    const int64_t r = (static_cast<int64_t>(pair) * P.n_kv_heads + h) * ROWB;
-    knew = static_cast<const char*>(P.k_new) + r;
-    vnew = static_cast<const char*>(P.v_new) + r;
-  }
-
-  // Queries of the group, widened to fp32, this lane's columns only.
-  float qf[G][EPL];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    const int64_t hq = (static_cast<int64_t>(pair) * P.n_kv_heads + h) * G + g;
-    const uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const char*>(P.q) + hq * ROWB + cl * 16);
-    Unpack<T>::run(raw, qf[g]);
-  }
-
-  // K rows of this wave, kTB wave-wide loads at a time, all issued before the
-  // first is used; when registers allow, the V loads go out right behind them
-  // so that they are in flight during the softmax statistics.
+  const bool append_here = cx.append_here;
   const bool full = (c + 1) * kChunk <= n && !append_here;
-  constexpr int NV = V_EARLY ? NT : 1;
-  uint4 vreg[NV];
+
+  float qf[G][EPL];
+  cx.load_q(P, cl, qf);
+
 #pragma unroll
   for (int b0 = 0; b0 < NT; b0 += kTB) {
     uint4 kreg[kTB];
-    load_rows<ROWB, RPW, kTB>(kreg, kbase, knew, row0 + b0 * RPW + sub, n, full, append_here, cl);
-    if constexpr (V_EARLY)
-      if (b0 == 0) load_rows<ROWB, RPW, NV>(vreg, vbase, vnew, row0 + sub, n, full, append_here, cl);
-    // Logits: scale * q_g . K_j in base-2 units, one per (row, g).
+    load_rows<ROWB, RPW, kTB>(kreg, cx.kbase, cx.knew, row0 + b0 * RPW + sub, n, full, append_here, cl);
 #pragma unroll
     for (int i = 0; i < kTB; ++i) {
       float kf[EPL];
@@ -207,10 +630,8 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
         if (cl == 0) s_sh[g][lr] = valid ? a * P.scale_log2e : -INFINITY;
       }
     }
-    if (append_here) store_appended<ROWB, RPW, kTB>(kreg, kbase, row0 + b0 * RPW + sub, n, cl);
+    if (append_here) store_appended<ROWB, RPW, kTB>(kreg, cx.kbase, row0 + b0 * RPW + sub, n, cl);
   }
-  if constexpr (V_EARLY)
-    if (append_here) store_appended<ROWB, RPW, NV>(vreg, vbase, row0 + sub, n, cl);
   __syncthreads();
 
   // Chunk statistics.  Thread t owns row t of the chunk.
@@ -222,7 +643,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
     if (lane == 0) red_sh[0][g][wave] = wm;
   }
   __syncthreads();
-  float* rec = P.ws + static_cast<int64_t>(bid) * REC;
+  float* rec = cx.rec;
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     float m = red_sh[0][g][0];
@@ -231,7 +652,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
     m_c[g] = m;
     const float e = fast_exp2(s_own[g] - m);      // 0 for rows past the end
     s_sh[g][tid] = e;
-    store_stream(&rec[g * kChunk + tid], e);
+    store_stream(&rec[g * kChunk + tid], s_own[g]);
     const float ws = wave_sum(e);
     if (lane == 0) red_sh[1][g][wave] = ws;
   }
@@ -244,7 +665,6 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
     l_c[g] = l;
   }
   if (tid < G) {
-    // tid selects the head: pick with a loop the compiler can unroll.
 #pragma unroll
     for (int g = 0; g < G; ++g)
       if (g == tid) {
@@ -261,15 +681,13 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
     for (int e = 0; e < EPL; ++e) acc[g][e] = 0.0f;
 #pragma unroll
   for (int b0 = 0; b0 < NT; b0 += kTB) {
-    uint4 vlate[kTB];
-    if constexpr (!V_EARLY) {
-      load_rows<ROWB, RPW, kTB>(vlate, vbase, vnew, row0 + b0 * RPW + sub, n, full, append_here, cl);
-      if (append_here) store_appended<ROWB, RPW, kTB>(vlate, vbase, row0 + b0 * RPW + sub, n, cl);
-    }
+    uint4 vreg[kTB];
+    load_rows<ROWB, RPW, kTB>(vreg, cx.vbase, cx.vnew, row0 + b0 * RPW + sub, n, full, append_here, cl);
+    if (append_here) store_appended<ROWB, RPW, kTB>(vreg, cx.vbase, row0 + b0 * RPW + sub, n, cl);
 #pragma unroll
     for (int i = 0; i < kTB; ++i) {
       float vf[EPL];
-      if constexpr (V_EARLY) Unpack<T>::run(vreg[b0 + i], vf); else Unpack<T>::run(vlate[i], vf);
+      Unpack<T>::run(vreg[i], vf);
       const int lr = wave * 64 + (b0 + i) * RPW + sub;
 #pragma unroll
       for (int g = 0; g < G; ++g) {
@@ -302,9 +720,8 @@ __global__ __launch_bounds__(kThreads) void attend_partial(const AttendParams P)
 // ---------------------------------------------------------------------------
 template <int D, int G>
 __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P) {
-  constexpr int REC = G * (kChunk + D + 2);
   constexpr int GD = G * D;
-  extern __shared__ float dyn_sh[];         // [G][nchunks] chunk weights, then [G][nchunks] chunk sums
+  extern __shared__ float dyn_sh[];         // [G][nstrips] strip weights, then [G][nstrips] strip sums
   __shared__ float red_sh[kWaves];
   __shared__ float o_red[kThreads];
 
@@ -312,103 +729,93 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int bid = blockIdx.x;
+  const int strip_rows = P.strip_rows;
+  const int64_t REC = record_floats(G, D, strip_rows);
 
-  // Region: last pair whose first finalize workgroup is <= bid.
+  // Region: last pair whose first strip is <= bid.  An empty stream owns one strip.
   int lo = 0, hi = P.n_pairs - 1;
   while (lo < hi) {
     const int mid = (lo + hi + 1) >> 1;
-    if (P.pairs[mid].fblock0 <= bid) lo = mid; else hi = mid - 1;
+    if (P.pairs[mid].strip0 <= bid) lo = mid; else hi = mid - 1;
   }
   const PairDesc pd = P.pairs[lo];
   const int n = pd.n;
-  const int nchunks = (n + kChunk - 1) / kChunk;
-  const int nblk = nchunks > 0 ? (nchunks + kFinalChunks - 1) / kFinalChunks : 1;
-  const int local = bid - pd.fblock0;
-  const int h = local / nblk;
-  const int blk = local - h * nblk;
+  const int nstrips_live = (n + strip_rows - 1) / strip_rows;
+  const int nstrips = nstrips_live > 0 ? nstrips_live : 1;
+  const int local = bid - pd.strip0;
+  const int h = local / nstrips;
+  const int s_own = local - h * nstrips;
   const int pair = P.pair_base + lo;
   float* out = P.out + (static_cast<int64_t>(pair) * P.n_kv_heads + h) * GD;
   if (n == 0) {
     for (int idx = tid; idx < GD; idx += kThreads) out[idx] = 0.0f;
     return;
   }
-  const float* rec0 =
-      P.ws + (static_cast<int64_t>(pd.block0) + static_cast<int64_t>(h) * nchunks) * REC;
-  const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
-  float* score = P.score + stream_slot;
+  const float* rec0 = P.ws + (static_cast<int64_t>(pd.strip0) + static_cast<int64_t>(h) * nstrips) * REC;
   float* w_sh = dyn_sh;
-  float* l_sh = dyn_sh + G * nchunks;
+  float* l_sh = dyn_sh + G * nstrips;
 
-  // Start the loads that do not depend on the statistics: the un-normalised
-  // probabilities and the old scores of this workgroup's slots.
-  float e_r[kFinalChunks][G], old_r[kFinalChunks];
-#pragma unroll
-  for (int i = 0; i < kFinalChunks; ++i) {
-    const int c = blk * kFinalChunks + i;
-    const int j = c * kChunk + tid;
-    old_r[i] = 0.0f;
-#pragma unroll
-    for (int g = 0; g < G; ++g) e_r[i][g] = 0.0f;
-    if (c < nchunks && j < n) {
-#pragma unroll
-      for (int g = 0; g < G; ++g) e_r[i][g] = rec0[static_cast<int64_t>(c) * REC + g * kChunk + tid];
-      if (!(P.append && j == n - 1)) old_r[i] = score[j];   // the appended token starts from zero
-    }
-  }
-
-  // Stream statistics from the chunk statistics.  Every workgroup of the stream
+  // Stream statistics from the strip statistics.  Every workgroup of the stream
   // repeats this small reduction in the same order, so all agree bit for bit.
-  for (int c = tid; c < nchunks; c += kThreads) {
-    const float* ml = rec0 + static_cast<int64_t>(c) * REC + G * (kChunk + D);
+  for (int c = tid; c < nstrips; c += kThreads) {
+    const float* ml = rec0 + static_cast<int64_t>(c) * REC + G * (strip_rows + D);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      w_sh[g * nchunks + c] = ml[2 * g];
-      l_sh[g * nchunks + c] = ml[2 * g + 1];
+      w_sh[g * nstrips + c] = ml[2 * g];
+      l_sh[g * nstrips + c] = ml[2 * g + 1];
     }
   }
   __syncthreads();
+  float m_g[G], inv_g[G];
+#pragma unroll
   for (int g = 0; g < G; ++g) {
     float m = -INFINITY;
-    for (int c = tid; c < nchunks; c += kThreads) m = fmaxf(m, w_sh[g * nchunks + c]);
+    for (int c = tid; c < nstrips; c += kThreads) m = fmaxf(m, w_sh[g * nstrips + c]);
     m = wave_max(m);
     if (lane == 0) red_sh[wave] = m;
     __syncthreads();
     m = fmaxf(fmaxf(red_sh[0], red_sh[1]), fmaxf(red_sh[2], red_sh[3]));
     __syncthreads();
     float l = 0.0f;
-    for (int c = tid; c < nchunks; c += kThreads) {
-      const float wgt = fast_exp2(w_sh[g * nchunks + c] - m);
-      w_sh[g * nchunks + c] = wgt;
-      l += wgt * l_sh[g * nchunks + c];
+    for (int c = tid; c < nstrips; c += kThreads) {
+      const float wgt = fast_exp2(w_sh[g * nstrips + c] - m);
+      w_sh[g * nstrips + c] = wgt;
+      l += wgt * l_sh[g * nstrips + c];
     }
     l = wave_sum(l);
     if (lane == 0) red_sh[wave] = l;
     __syncthreads();
     l = (red_sh[0] + red_sh[1]) + (red_sh[2] + red_sh[3]);
     const float inv = 1.0f / l;
-    for (int c = tid; c < nchunks; c += kThreads) w_sh[g * nchunks + c] *= inv;
+    for (int c = tid; c < nstrips; c += kThreads) w_sh[g * nstrips + c] *= inv;
+    m_g[g] = m;
+    inv_g[g] = inv;
     __syncthreads();
   }
 
-  // score_j += sum_g e_gj w_gc
+  // score_j += sum_g 2^(s_gj - m_g) / l_g for the slots of this strip; the
+  // appended token starts from zero.
+  const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
+  float* score = P.score + stream_slot;
+  const int r_begin = s_own * strip_rows;
+  const int rows = min(n, r_begin + strip_rows) - r_begin;
+  const float* lg = rec0 + static_cast<int64_t>(s_own) * REC;
+#pragma unroll 4
+  for (int j = tid; j < rows; j += kThreads) {
+    float add = 0.0f;
 #pragma unroll
-  for (int i = 0; i < kFinalChunks; ++i) {
-    const int c = blk * kFinalChunks + i;
-    const int j = c * kChunk + tid;
-    if (c < nchunks && j < n) {
-      float add = 0.0f;
-#pragma unroll
-      for (int g = 0; g < G; ++g) add = fmaf(e_r[i][g], w_sh[g * nchunks + c], add);
-      score[j] = old_r[i] + add;
-    }
+    for (int g = 0; g < G; ++g) add = fmaf(fast_exp2(lg[g * strip_rows + j] - m_g[g]), inv_g[g], add);
+    const int row = r_begin + j;
+    const float old = (P.append && row == n - 1) ? 0.0f : score[row];
+    score[row] = old + add;
   }
-  if (P.append && blk == 0 && tid == 0) P.pos[stream_slot + n - 1] = P.pos_new[lo];
+  if (P.append && s_own == 0 && tid == 0) P.pos[stream_slot + n - 1] = P.pos_new[lo];
 
-  // out = sum_c w_c o_c.  The G*D channels of the stream are split evenly over
+  // out = sum_s w_s o_s.  The G*D channels of the stream are split evenly over
   // its workgroups.  Within a workgroup the threads form (channel, slice)
-  // pairs; a slice sums every S-th chunk, then the slices are added in order.
-  const int cpb = (GD + nblk - 1) / nblk;
-  const int ch_first = blk * cpb;
+  // pairs; a slice sums every S-th strip, then the slices are added in order.
+  const int cpb = (GD + nstrips - 1) / nstrips;
+  const int ch_first = s_own * cpb;
   const int nch = min(cpb, GD - ch_first);
   for (int tb = 0; tb < nch; tb += kThreads) {
     const int tn = min(kThreads, nch - tb);
@@ -418,10 +825,10 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P
     if (slice < S) {
       const int idx = ch_first + tb + ch_l;
       const int g = idx / D;
-      const float* col = rec0 + G * kChunk + idx;
+      const float* col = rec0 + G * strip_rows + idx;
 #pragma unroll 4
-      for (int c = slice; c < nchunks; c += S)
-        o = fmaf(w_sh[g * nchunks + c], col[static_cast<int64_t>(c) * REC], o);
+      for (int c = slice; c < nstrips; c += S)
+        o = fmaf(w_sh[g * nstrips + c], col[static_cast<int64_t>(c) * REC], o);
     }
     __syncthreads();
     o_red[tid] = o;
@@ -435,30 +842,224 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P
 }
 
 // ---------------------------------------------------------------------------
-using PartialFn = void (*)(const AttendParams);
-using FinalizeFn = void (*)(const AttendParams);
+using KernelFn = void (*)(const AttendParams);
+struct Kernels {
+  KernelFn stream = nullptr;
+  KernelFn finalize = nullptr;
+  KernelFn fused = nullptr;
+  bool strips = false;      // the streaming kernel is attend_strip (long strips, dynamic LDS)
+};
 
 template <typename T, int D>
-bool pick_group(int group, PartialFn* pf, FinalizeFn* ff) {
+bool pick_group(int group, Kernels* k) {
   switch (group) {
-    case 1: *pf = attend_partial<T, D, 1>; *ff = attend_finalize<D, 1>; return true;
-    case 2: *pf = attend_partial<T, D, 2>; *ff = attend_finalize<D, 2>; return true;
-    case 4: *pf = attend_partial<T, D, 4>; *ff = attend_finalize<D, 4>; return true;
-    case 8: *pf = attend_partial<T, D, 8>; *ff = attend_finalize<D, 8>; return true;
+    case 1:
+      k->stream = attend_strip<T, D, 1, 8>; k->finalize = attend_finalize<D, 1>; k->strips = true;
+      k->fused = attend_fused<T, D, 1, 8>;
+      return true;
+    case 2:
+      k->stream = attend_strip<T, D, 2, 8>; k->finalize = attend_finalize<D, 2>; k->strips = true;
+      k->fused = attend_fused<T, D, 2, 8>;
+      return true;
+    case 4:
+      k->stream = attend_chunk<T, D, 4>; k->finalize = attend_finalize<D, 4>;
+      k->fused = attend_fused<T, D, 4, 4>;
+      return true;
+    case 8:
+      k->stream = attend_chunk<T, D, 8>; k->finalize = attend_finalize<D, 8>;
+      k->fused = attend_fused<T, D, 8, 2>;
+      return true;
     default: return false;
   }
 }
 
-bool pick_kernels(int dtype, int head_dim, int group, PartialFn* pf, FinalizeFn* ff) {
-  if (dtype == XKV_F32 && head_dim == 64) return pick_group<F32, 64>(group, pf, ff);
-  if (dtype == XKV_F32 && head_dim == 128) return pick_group<F32, 128>(group, pf, ff);
-  if (dtype == XKV_BF16 && head_dim == 64) return pick_group<BF16, 64>(group, pf, ff);
-  if (dtype == XKV_BF16 && head_dim == 128) return pick_group<BF16, 128>(group, pf, ff);
+bool pick_kernels(int dtype, int head_dim, int group, Kernels* k) {
+  if (dtype == XKV_F32 && head_dim == 64) return pick_group<F32, 64>(group, k);
+  if (dtype == XKV_F32 && head_dim == 128) return pick_group<F32, 128>(group, k);
+  if (dtype == XKV_BF16 && head_dim == 64) return pick_group<BF16, 64>(group, k);
+  if (dtype == XKV_BF16 && head_dim == 128) return pick_group<BF16, 128>(group, k);
   return false;
 }
 
+// Strip length of a call: long strips amortise the per-strip record and let a
+// workgroup pipeline its loads, but a call must still spread over the whole
+// chip, so the strips shrink until there are enough of them.
+int choose_strip_rows(bool strips, int64_t streams, int64_t total_rows) {
+  if (!strips) return kChunk;
+  int rows = kMaxStripRows;
+#ifdef XKV_EXP_STRIP
+  rows = XKV_EXP_STRIP;
+#endif
+  const int64_t want = 2048;                // several workgroups per compute unit
+  while (rows > kChunk && total_rows / rows + streams / 2 < want) rows >>= 1;
+  return rows;
+}
+
+// ---- fused path, host side ---------------------------------------------------
+constexpr size_t kFusedLdsBudget = 72 * 1024;   // logits per workgroup; two workgroups share a compute unit
+
+int g_attend_path = 0;                          // 0 auto, 1 two kernels, 2 fused or error
+// What "auto" picks.  On the 32k benchmark workload the fused launch and the two
+// kernels currently take the same time within 2 %, the two kernels being the
+// simpler path; the fused launch stays selectable.
+constexpr bool kAutoPrefersFused = false;
+
+int compute_units() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+  }
+  return cus;
+}
+
+// Workgroups of `fn` that are resident at once with `lds` bytes of dynamic LDS
+// each (0 if unknown); raises the kernel's LDS limit when needed.  Cached per kernel.
+int resident_workgroups(KernelFn fn, size_t lds) {
+  struct Entry { KernelFn fn; size_t lds; int n; };
+  static std::vector<Entry> cache;
+  for (const Entry& e : cache)
+    if (e.fn == fn && e.lds == lds) return e.n;
+  const int cus = compute_units();
+  const void* f = reinterpret_cast<const void*>(fn);
+  int n = 0, per_cu = 0;
+  if (cus > 0 &&
+      (lds <= 48 * 1024 ||
+       hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) == hipSuccess) &&
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, f, kThreads, lds) == hipSuccess)
+    n = per_cu * cus;
+  (void)hipGetLastError();
+  cache.push_back({fn, lds, n});
+  return n;
+}
+
+// Launches the fused kernel over the call's regions, in groups of consecutive
+// regions that fit one launch (kMaxPairs regions, and no more strips than the
+// resident workgroups can hold logits for).  Returns XKV_ERR_UNSUPPORTED, before
+// anything is enqueued, if the call does not fit this path.
+xkv_status launch_fused(const xkv_cache* cache, int64_t first, int64_t n_pairs, bool append,
+                        const int32_t* pos_new, AttendParams& P, KernelFn fn, int G, int D,
+                        int64_t total_rows, void* workspace, size_t workspace_bytes,
+                        hipStream_t stream) {
+  const int B = cache->batch, hkv = cache->n_kv_heads;
+  const int64_t seg = static_cast<int64_t>(G) * (D + 2);
+  const int lds_rows = static_cast<int>(kFusedLdsBudget / (sizeof(float) * G) / kChunk * kChunk);
+  const size_t lds = static_cast<size_t>(lds_rows) * G * sizeof(float);
+  const int n_wgs = resident_workgroups(fn, lds);
+  if (n_wgs <= 0) return XKV_ERR_UNSUPPORTED;
+  // Strip length: about nine strips fit a workgroup; shorter when the call is
+  // small, so that every workgroup still finds work in the queue.
+  int strip_rows = std::max(kChunk, 2048 / G);
+  while (strip_rows > kChunk && total_rows / strip_rows < 2 * static_cast<int64_t>(n_wgs)) strip_rows >>= 1;
+  const int64_t hold = std::min<int64_t>(kMaxHeld, lds_rows / strip_rows);
+  const int64_t capacity = hold * n_wgs;      // strips one launch can take
+
+  struct Group { int64_t g0; int np; int64_t strips; int64_t units; };
+  std::vector<Group> groups;
+  int64_t total_strips = 0;
+  Group cur{0, 0, 0, 0};
+  for (int64_t i = 0; i < n_pairs; ++i) {
+    const int64_t n = cache->len[first + i] + (append ? 1 : 0);
+    const int64_t units = ceil_div(n, strip_rows) * hkv;              // strips with live rows
+    const int64_t strips = std::max<int64_t>(ceil_div(n, strip_rows), 1) * hkv;
+    if (units > capacity) return XKV_ERR_UNSUPPORTED;
+    if (cur.np == kMaxPairs || cur.units + units > capacity) {
+      groups.push_back(cur);
+      cur = Group{i, 0, 0, 0};
+    }
+    cur.np += 1;
+    cur.units += units;
+    cur.strips += strips;
+    total_strips += strips;
+  }
+  if (cur.np > 0) groups.push_back(cur);
+  if (total_strips > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;
+  // Records first, then four control words per launch.
+  const uint64_t need = static_cast<uint64_t>(total_strips) * seg * sizeof(float) + groups.size() * 16;
+  if (need > workspace_bytes) return XKV_ERR_UNSUPPORTED;
+  unsigned* control0 = reinterpret_cast<unsigned*>(static_cast<float*>(workspace) + total_strips * seg);
+
+  P.strip_rows = strip_rows;
+  P.rec_floats = static_cast<int32_t>(seg);
+  P.lds_rows = lds_rows;
+  int64_t strips_done = 0;
+  for (size_t gi = 0; gi < groups.size(); ++gi) {
+    const Group& gr = groups[gi];
+    int64_t strips = 0, full = 0;
+    int tails = 0;
+    int tail_len[kMaxPairs];
+    for (int i = 0; i < gr.np; ++i) {
+      const int64_t idx = first + gr.g0 + i;
+      PairDesc& pd = P.pairs[i];
+      pd.slot0 = cache->region_off[idx];
+      pd.cap = cache->cap[idx];
+      pd.n = cache->len[idx] + (append ? 1 : 0);
+      pd.strip0 = static_cast<int32_t>(strips);
+      pd.full0 = static_cast<int32_t>(full);
+      P.pos_new[i] = append ? pos_new[(gr.g0 + i) % B] : 0;
+      strips += std::max<int64_t>(ceil_div(pd.n, strip_rows), 1) * hkv;
+      full += static_cast<int64_t>(pd.n / strip_rows) * hkv;
+      tail_len[i] = pd.n % strip_rows;
+      if (tail_len[i] > 0) P.tail_order[tails++] = static_cast<uint8_t>(i);
+    }
+    std::stable_sort(P.tail_order, P.tail_order + tails,
+                     [&](uint8_t a, uint8_t b) { return tail_len[a] > tail_len[b]; });
+    P.n_pairs = gr.np;
+    P.pair_base = static_cast<int32_t>(gr.g0);
+    P.full_blocks = static_cast<int32_t>(full);
+    P.n_tail_pairs = tails;
+    P.ws = static_cast<float*>(workspace) + strips_done * seg;
+    P.barrier = control0 + 4 * gi;
+    const int64_t units = full + static_cast<int64_t>(tails) * hkv;
+    const int64_t grid = std::max<int64_t>(1, std::min<int64_t>(n_wgs, units));
+    hipLaunchKernelGGL(fused_prepare, dim3(1), dim3(64), 0, stream, P.barrier);
+    if (hipGetLastError() != hipSuccess) return gi == 0 ? XKV_ERR_UNSUPPORTED : XKV_ERR_DEVICE;
+    void* args[] = {&P};
+    const int tok = profile_begin(0, stream);
+    const hipError_t err =
+        hipLaunchCooperativeKernel(reinterpret_cast<const void*>(fn), dim3(static_cast<unsigned>(grid)),
+                                   dim3(kThreads), args, lds, stream);
+    profile_end(tok, stream);
+    if (err != hipSuccess) {
+      (void)hipGetLastError();
+      return gi == 0 ? XKV_ERR_UNSUPPORTED : XKV_ERR_DEVICE;
+    }
+    strips_done += gr.strips;
+  }
+  return XKV_OK;
+}
+
 }  // namespace
+
+size_t attend_workspace_bytes(const xkv_cache* c, int32_t layers) {
+  // Upper bound over every strip length a call may choose: logits for cap slots
+  // plus one padded strip, and one (o, m, l) block per kChunk slots.
+  const int group = c->n_q_heads / c->n_kv_heads;
+  const int hkv = c->n_kv_heads;
+  const int d = c->head_dim;
+  std::vector<size_t> need(static_cast<size_t>(c->n_layers), 0);
+  for (int32_t l = 0; l < c->n_layers; ++l)
+    for (int32_t b = 0; b < c->batch; ++b) {
+      const int64_t cap = c->cap[static_cast<int64_t>(l) * c->batch + b];
+      const int64_t floats = cap + kMaxStripRows + std::max<int64_t>(ceil_div(cap, kChunk), 1) * (d + 2);
+      need[l] += static_cast<size_t>(floats) * group * hkv * sizeof(float);
+    }
+  std::sort(need.begin(), need.end(), std::greater<size_t>());
+  size_t tot = 0;
+  for (int32_t l = 0; l < layers && l < c->n_layers; ++l) tot += need[l];
+  return tot;
+}
+
 }  // namespace xkv
+
+extern "C" xkv_status xkv_configure(int32_t key, int64_t value) {
+  if (key == XKV_CFG_ATTEND_PATH && value >= 0 && value <= 2) {
+    xkv::g_attend_path = static_cast<int>(value);
+    return XKV_OK;
+  }
+  return XKV_ERR_INVALID_ARG;
+}
 
 extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_begin,
                                               int32_t layer_end, const void* q, const void* k_new,
@@ -481,30 +1082,20 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
 
   const int B = cache->batch, hkv = cache->n_kv_heads, D = cache->head_dim;
   const int G = cache->n_q_heads / hkv;
-  PartialFn partial = nullptr;
-  FinalizeFn finalize = nullptr;
-  if (!pick_kernels(cache->dtype, D, G, &partial, &finalize)) return XKV_ERR_UNSUPPORTED;
+  Kernels kern;
+  if (!pick_kernels(cache->dtype, D, G, &kern)) return XKV_ERR_UNSUPPORTED;
 
   const int64_t first = static_cast<int64_t>(layer_begin) * B;
   const int64_t n_pairs = static_cast<int64_t>(layer_end - layer_begin) * B;
-  int64_t total_blocks = 0;
-  int64_t max_chunks = 0;
-  const int fin_chunks = kFinalChunks;
+  int64_t total_rows = 0, max_n = 0;
   for (int64_t i = 0; i < n_pairs; ++i) {
     const int64_t n = static_cast<int64_t>(cache->len[first + i]) + (append ? 1 : 0);
     if (n > cache->cap[first + i]) return XKV_ERR_CAPACITY;
-    const int64_t chunks = ceil_div(n, kChunk);
-    max_chunks = std::max(max_chunks, chunks);
-    total_blocks += std::max<int64_t>(chunks, 1) * hkv;
+    total_rows += n * hkv;
+    max_n = std::max(max_n, n);
   }
-  const int64_t rec = attend_record_floats(G, D);
   if (workspace == nullptr) return XKV_ERR_INVALID_ARG;
-  if (static_cast<uint64_t>(total_blocks) * rec * sizeof(float) > workspace_bytes)
-    return XKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(workspace) & 3u) return XKV_ERR_INVALID_ARG;
-  const size_t fin_lds = static_cast<size_t>(std::max<int64_t>(max_chunks, 1)) * G * 2 * sizeof(float);
-  if (fin_lds > 48 * 1024) return XKV_ERR_UNSUPPORTED;
-
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt(static_cast<float>(D));
   AttendParams P;
@@ -514,35 +1105,77 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
   P.n_kv_heads = hkv;
   P.append = append ? 1 : 0;
 
-  int64_t blocks_done = 0;
+  // One cooperative launch per group of regions when everything fits on the chip at once.
+  if ((g_attend_path == 2 || (g_attend_path == 0 && kAutoPrefersFused)) && kern.fused != nullptr) {
+    const xkv_status fs = launch_fused(cache, first, n_pairs, append, pos_new, P, kern.fused, G, D,
+                                       total_rows, workspace, workspace_bytes, stream);
+    if (fs == XKV_OK) {
+      if (append)
+        for (int64_t i = 0; i < n_pairs; ++i) cache->len[first + i] += 1;
+      return XKV_OK;
+    }
+    if (fs != XKV_ERR_UNSUPPORTED || g_attend_path == 2) return fs;
+  }
+
+  const int strip_rows = choose_strip_rows(kern.strips, n_pairs * hkv, total_rows);
+  const int64_t rec = record_floats(G, D, strip_rows);
+  int64_t total_strips = 0;
+  for (int64_t i = 0; i < n_pairs; ++i) {
+    const int64_t n = static_cast<int64_t>(cache->len[first + i]) + (append ? 1 : 0);
+    total_strips += std::max<int64_t>(ceil_div(n, strip_rows), 1) * hkv;
+  }
+  if (static_cast<uint64_t>(total_strips) * rec * sizeof(float) > workspace_bytes)
+    return XKV_ERR_CAPACITY;
+  const int64_t max_strips = std::max<int64_t>(ceil_div(max_n, strip_rows), 1);
+  const size_t fin_lds = static_cast<size_t>(max_strips) * G * 2 * sizeof(float);
+  if (fin_lds > 48 * 1024) return XKV_ERR_UNSUPPORTED;
+  const size_t stream_lds = kern.strips ? static_cast<size_t>(G) * strip_rows * sizeof(float) : 0;
+
+  P.strip_rows = strip_rows;
+  P.rec_floats = static_cast<int32_t>(rec);
+  P.lds_rows = 0;
+  P.barrier = nullptr;
+
+  int64_t strips_done = 0;
   for (int64_t g0 = 0; g0 < n_pairs; g0 += kMaxPairs) {
     const int np = static_cast<int>(std::min<int64_t>(kMaxPairs, n_pairs - g0));
-    int64_t blocks = 0, fblocks = 0;
+    int64_t strips = 0, full = 0;
+    int tails = 0;
+    int tail_len[kMaxPairs];
     for (int i = 0; i < np; ++i) {
       const int64_t idx = first + g0 + i;
       PairDesc& pd = P.pairs[i];
       pd.slot0 = cache->region_off[idx];
       pd.cap = cache->cap[idx];
       pd.n = cache->len[idx] + (append ? 1 : 0);
-      pd.block0 = static_cast<int32_t>(blocks);
-      pd.fblock0 = static_cast<int32_t>(fblocks);
+      pd.strip0 = static_cast<int32_t>(strips);
+      pd.full0 = static_cast<int32_t>(full);
       P.pos_new[i] = append ? pos_new[(g0 + i) % B] : 0;
-      const int64_t chunks = ceil_div(pd.n, kChunk);
-      blocks += std::max<int64_t>(chunks, 1) * hkv;
-      fblocks += std::max<int64_t>(ceil_div(chunks, fin_chunks), 1) * hkv;
+      strips += std::max<int64_t>(ceil_div(pd.n, strip_rows), 1) * hkv;
+      full += static_cast<int64_t>(pd.n / strip_rows) * hkv;
+      tail_len[i] = pd.n % strip_rows;
+      if (tail_len[i] > 0) P.tail_order[tails++] = static_cast<uint8_t>(i);
     }
-    if (blocks > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;
+    if (strips > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;
+    std::stable_sort(P.tail_order, P.tail_order + tails,
+                     [&](uint8_t a, uint8_t b) { return tail_len[a] > tail_len[b]; });
     P.n_pairs = np;
     P.pair_base = static_cast<int32_t>(g0);
-    P.ws = static_cast<float*>(workspace) + blocks_done * rec;
-    const int tok = profile_begin(0, stream);
-    hipLaunchKernelGGL(partial, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, stream, P);
-    profile_end(tok, stream);
-    if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
-    hipLaunchKernelGGL(finalize, dim3(static_cast<unsigned>(fblocks)), dim3(kThreads), fin_lds,
+    P.full_blocks = static_cast<int32_t>(full);
+    P.n_tail_pairs = tails;
+    P.ws = static_cast<float*>(workspace) + strips_done * rec;
+    const int64_t blocks = full + static_cast<int64_t>(tails) * hkv;
+    if (blocks > 0) {
+      const int tok = profile_begin(0, stream);
+      hipLaunchKernelGGL(kern.stream, dim3(static_cast<unsigned>(blocks)), dim3(kThreads),
+                         stream_lds, stream, P);
+      profile_end(tok, stream);
+      if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+    }
+    hipLaunchKernelGGL(kern.finalize, dim3(static_cast<unsigned>(strips)), dim3(kThreads), fin_lds,
                        stream, P);
     if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
-    blocks_done += blocks;
+    strips_done += strips;
   }
   if (append)
     for (int64_t i = 0; i < n_pairs; ++i) cache->len[first + i] += 1;

@@ -57,15 +57,6 @@ size_t top_layers_sum(const xkv_cache* c, int32_t layers,
 }
 }  // namespace
 
-size_t attend_workspace_bytes(const xkv_cache* c, int32_t layers) {
-  const int group = c->n_q_heads / c->n_kv_heads;
-  const size_t rec = static_cast<size_t>(attend_record_floats(group, c->head_dim)) * sizeof(float);
-  const int hkv = c->n_kv_heads;
-  return top_layers_sum(c, layers, [=](int64_t cap) {
-    return static_cast<size_t>(std::max<int64_t>(ceil_div(cap, kChunk), 1)) * hkv * rec;
-  });
-}
-
 size_t evict_workspace_bytes(const xkv_cache* c, int32_t layers) {
   // Per stream: keys, hole list and mover list (one 32-bit word per slot each,
   // slot counts rounded up to 32) and one move counter.
@@ -131,7 +122,7 @@ extern "C" xkv_status xkv_workspace_bytes(const xkv_cache* cache, int32_t max_la
   if (bytes_out == nullptr || max_layers_per_call <= 0) return XKV_ERR_INVALID_ARG;
   const int32_t layers = std::min(max_layers_per_call, cache->n_layers);
   *bytes_out = std::max(xkv::attend_workspace_bytes(cache, layers),
-                        xkv::evict_workspace_bytes(cache, layers)) + 256;
+                        xkv::evict_workspace_bytes(cache, layers)) + 4096;
   return XKV_OK;
 }
 

@@ -9,19 +9,14 @@
 
 namespace xkv {
 
-// Tokens of one stream handled by one workgroup of the K/V streaming kernel.
+// Granularity of the work split of a stream: strips are multiples of this many slots.
 constexpr int kChunk = 256;
+// Longest strip one workgroup of the streaming kernel handles.
+constexpr int kMaxStripRows = 4096;
 // (layer, sequence) regions described in the kernel arguments of one launch.
 constexpr int kMaxPairs = 128;
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
-
-// Floats of workspace per (stream, chunk): for each of the G query heads of the
-// stream, kChunk un-normalised probabilities, head_dim partial outputs and the
-// chunk's (max, sum).
-inline int64_t attend_record_floats(int group, int head_dim) {
-  return static_cast<int64_t>(group) * (kChunk + head_dim + 2);
-}
 
 // Checks everything about a cache descriptor that can be checked on the host.
 xkv_status check_cache(const xkv_cache* c);

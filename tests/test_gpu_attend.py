@@ -9,7 +9,27 @@ from gpu_util import TOL, get_unit, random_fill, rel_err, storage
 pytestmark = pytest.mark.gpu
 
 
-def run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, append, seed, scale=0.0, layer_range=None):
+def run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, append, seed, scale=0.0, layer_range=None, paths=(0, 1, 2),
+             fused_required=False):
+    """Runs the case once per attend path: 0 = the library's choice, 1 = streaming
+    + finalize kernels, 2 = the fused cooperative launch (which may say that the
+    call does not fit; that is accepted unless fused_required)."""
+    worst = (0.0, 0.0)
+    for path in paths:
+        xkv.xkv_configure(xkv.XKV_CFG_ATTEND_PATH, path)
+        try:
+            r = _run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, append, seed, scale, layer_range)
+        except xkv.XkvError as e:
+            if path == 2 and e.status == -4 and not fused_required:
+                continue
+            raise
+        finally:
+            xkv.xkv_configure(xkv.XKV_CFG_ATTEND_PATH, 0)
+        worst = (max(worst[0], r[0]), max(worst[1], r[1]))
+    return worst
+
+
+def _run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, append, seed, scale=0.0, layer_range=None):
     lens = np.asarray(lens, np.int32).reshape(L, B)
     caps = lens + 2
     cache = xkv.XkvCache(L, B, Hq, Hkv, d, dtype, caps)
@@ -61,6 +81,16 @@ def test_shapes_and_groups(xkv, dtype, d, G):
     run_case(xkv, dtype, d, Hkv * G, Hkv, 3, 2, lens, True, seed=7 + G)
     print(f"case dtype={dtype} d={d} G={G} no-append", flush=True)
     run_case(xkv, dtype, d, Hkv * G, Hkv, 3, 2, lens, False, seed=17 + G)
+
+
+@pytest.mark.parametrize("dtype,d,G", [("bf16", 128, 1), ("f32", 64, 1), ("bf16", 128, 2), ("bf16", 128, 4),
+                                       ("f32", 128, 1), ("bf16", 64, 4)])
+def test_fused_launch_is_really_taken(xkv, dtype, d, G):
+    """Path 2 fails instead of falling back, so a pass means the fused kernel ran."""
+    lens = [[0, 1, 300], [255, 256, 5000], [257, 700, 1030]]
+    print(f"case fused dtype={dtype} d={d} G={G}", flush=True)
+    run_case(xkv, dtype, d, 2 * G, 2, 3, 3, lens, True, seed=40 + G, paths=(2,), fused_required=True)
+    run_case(xkv, dtype, d, 2 * G, 2, 3, 3, lens, False, seed=50 + G, paths=(2,), fused_required=True)
 
 
 def test_empty_stream_without_append_gives_zero_row(xkv):

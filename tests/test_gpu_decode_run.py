@@ -73,7 +73,14 @@ def all_units(w):
     return [(l, b, h) for l in range(w.n_layers) for b in range(w.batch) for h in range(w.n_kv_heads)]
 
 
-def test_tiny_fp32_full_run_every_unit(xkv):
+@pytest.fixture(params=[2, 1], ids=["fused", "two-kernels"])
+def attend_path(request, xkv):
+    xkv.xkv_configure(xkv.XKV_CFG_ATTEND_PATH, request.param)
+    yield request.param
+    xkv.xkv_configure(xkv.XKV_CFG_ATTEND_PATH, 0)
+
+
+def test_tiny_fp32_full_run_every_unit(xkv, attend_path):
     """The small fp32 configuration: 4 layers, 4 heads, d 64, prompt 512, 16
     steps, budgets 384/256/128/64 (sum 832), sinks at tokens 0-3."""
     w = wl.WORKLOADS["tiny_f32"]
@@ -87,7 +94,7 @@ def test_tiny_fp32_full_run_every_unit(xkv):
         assert len(set(pos.tolist()) & {0, 1, 2, 3}) >= 1
 
 
-def test_tiny_paper_defaults_window_and_pooling(xkv):
+def test_tiny_paper_defaults_window_and_pooling(xkv, attend_path):
     """Observation window 8 and pooling width 7 (the paper's default setting):
     the first eviction waits for 8 decode steps, the newest 8 tokens are kept."""
     w = wl.WORKLOADS["tiny_f32"]
@@ -95,7 +102,7 @@ def test_tiny_paper_defaults_window_and_pooling(xkv):
     lockstep(xkv, w, budgets, all_units(w), 12, pool=7, protect=8, first_evict_step=7)
 
 
-def test_gqa_bf16_batched_sampled_units(xkv):
+def test_gqa_bf16_batched_sampled_units(xkv, attend_path):
     """Mistral-shaped geometry at reduced size: GQA 32/8, batch 3, per-sequence budgets."""
     w = wl.scaled(wl.WORKLOADS["mistral_7b_gqa_b32"], n_layers=3, batch=3, context=1500, decode_steps=4)
     budgets = wl.dirichlet_budgets(w.n_layers, w.batch, w.context, int(0.3 * w.n_layers * w.context), w.seed)

@@ -95,9 +95,16 @@ def run_full(xkv, name, steps, n_sample):
             ws = torch.empty(xkv.xkv_workspace_bytes(cache, L), dtype=torch.uint8, device="cuda")
 
 
-def test_llama2_7b_4k_full_size(xkv):
+@pytest.fixture(params=[2, 1], ids=["fused", "two-kernels"])
+def attend_path(request, xkv):
+    xkv.xkv_configure(xkv.XKV_CFG_ATTEND_PATH, request.param)
+    yield request.param
+    xkv.xkv_configure(xkv.XKV_CFG_ATTEND_PATH, 0)
+
+
+def test_llama2_7b_4k_full_size(xkv, attend_path):
     run_full(xkv, "llama2_7b_4k", steps=3, n_sample=8)
 
 
-def test_llama2_7b_32k_full_size(xkv):
+def test_llama2_7b_32k_full_size(xkv, attend_path):
     run_full(xkv, "llama2_7b_32k", steps=3, n_sample=8)
