@@ -469,13 +469,7 @@ __global__ __launch_bounds__(kThreads) void attend_fused(const AttendParams P) {
                                });
     ++n_held;
   }
-#ifdef XKV_EXP_NOSYNC
-  return;
-#endif
   grid_barrier(P.barrier, gridDim.x);
-#ifdef XKV_EXP_NOPHASE2
-  return;
-#endif
 
   // ---- phase 2: normalise, add to the scores, write the outputs -----------------
   for (int k = 0; k < n_held; ++k) {
@@ -887,9 +881,6 @@ bool pick_kernels(int dtype, int head_dim, int group, Kernels* k) {
 int choose_strip_rows(bool strips, int64_t streams, int64_t total_rows) {
   if (!strips) return kChunk;
   int rows = kMaxStripRows;
-#ifdef XKV_EXP_STRIP
-  rows = XKV_EXP_STRIP;
-#endif
   const int64_t want = 2048;                // several workgroups per compute unit
   while (rows > kChunk && total_rows / rows + streams / 2 < want) rows >>= 1;
   return rows;
