@@ -231,16 +231,36 @@ def main():
         bytes_per_launch = alg_bytes_step / launches_per_step
         achieved = bytes_per_launch / (total_ms / launches * 1e-3) / 1e9
         traffic = None
-        tfile = os.path.join(ROOT, "profiles", f"attend_partial_{w.name}_hbm_traffic.txt")
+        tfile = os.path.join(ROOT, "profiles", f"attend_strip_{w.name}_hbm_traffic.txt")
         if os.path.exists(tfile):
             for line in open(tfile):
                 if line.startswith("traffic_bytes_per_launch:"):
                     traffic = float(line.split(":")[1])
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                    "kernel": "attend_partial", "avg_launch_ms": total_ms / launches,
+                    "kernel": "attend_strip (K/V streaming kernel of xkv_decode_attend_score)", "avg_launch_ms": total_ms / launches,
                     "launches_per_step": launches_per_step, "algorithmic_bytes_per_launch": bytes_per_launch,
                     "evict_select_avg_ms": (sel_ms / sel_launches) if sel_launches else None}
+
+    # What a read-only kernel of the same shape reaches on this machine (context for the roofline fraction).
+    ceiling = None
+    if not args.no_roofline_pass:
+        buf = cache.k
+        per_wg = 128 * 1024
+        nbytes = buf.numel() * buf.element_size() // per_wg * per_wg
+        sink = torch.empty((nbytes // per_wg) * 386, dtype=torch.float32, device="cuda")
+        ceiling = {"bytes_per_launch": nbytes}
+        for tag, nt, st in (("non_temporal_GBs", True, 0), ("ordinary_loads_GBs", False, 0),
+                            ("non_temporal_with_1544B_record_store_per_128KiB_GBs", True, 386)):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            xkv.xkv_probe_stream_read(buf, nt, st, sink, stream=stream)
+            e0.record(stream)
+            for _ in range(20):
+                xkv.xkv_probe_stream_read(buf, nt, st, sink, stream=stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ceiling[tag] = nbytes * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del sink
 
     cpu = None
     if args.cpu_seconds > 0:
@@ -273,7 +293,7 @@ def main():
         "step0_ms": step0_ms,
         "algorithmic_bytes_per_step": alg_bytes_timed / K,
         "step_hbm_gbs": step_gbs, "step_hbm_frac": step_gbs / HBM_PEAK_GBS,
-        "roofline": roofline, "cpu_baseline": cpu, "allocator": allocator,
+        "roofline": roofline, "stream_read_ceiling": ceiling, "cpu_baseline": cpu, "allocator": allocator,
     }
     print(json.dumps(line))
 

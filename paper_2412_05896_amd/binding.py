@@ -16,7 +16,7 @@ XKV_ALLOC_TOTAL_SIZE, XKV_ALLOC_TARGET_RAVG = 0, 1
 EXPORTS = (
     "xkv_status_string", "xkv_allocate_budgets", "xkv_workspace_bytes",
     "xkv_decode_attend_score", "xkv_evict_compact", "xkv_profile_enable", "xkv_profile_read",
-    "xkv_configure",
+    "xkv_configure", "xkv_probe_stream_read",
 )
 XKV_CFG_ATTEND_PATH = 1
 
@@ -71,6 +71,8 @@ def load():
         C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.xkv_configure.restype = C.c_int32
     lib.xkv_configure.argtypes = [C.c_int32, C.c_int64]
+    lib.xkv_probe_stream_read.restype = C.c_int32
+    lib.xkv_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.xkv_profile_enable.restype = C.c_int32
     lib.xkv_profile_enable.argtypes = [C.c_int32]
     lib.xkv_profile_read.restype = C.c_int32
@@ -227,6 +229,14 @@ def xkv_evict_compact(cache: XkvCache, layer_begin, layer_end, budgets, workspac
 
 def xkv_configure(key: int, value: int):
     _check(load().xkv_configure(int(key), int(value)), "xkv_configure")
+
+
+def xkv_probe_stream_read(buffer, non_temporal: bool, store_floats_per_workgroup: int = 0, sink=None,
+                          stream=None):
+    """One launch of the read-only streaming kernel over a torch device tensor."""
+    _check(load().xkv_probe_stream_read(_ptr(buffer), buffer.numel() * buffer.element_size(),
+                                        1 if non_temporal else 0, int(store_floats_per_workgroup),
+                                        _ptr(sink), _stream_handle(stream)), "xkv_probe_stream_read")
 
 
 def xkv_profile_enable(on: bool):
