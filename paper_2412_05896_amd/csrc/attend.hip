@@ -19,7 +19,9 @@
 //                                     waves merge once at the end; logits are
 //                                     collected in LDS and written in one burst.
 //                      attend_chunk   (G >= 4) strips of 256 slots handled by the
-//                                     whole workgroup in one pass.
+//                                     whole workgroup in one pass; for bf16
+//                                     the logits come from bf16 MFMA (the
+//                                     query group is a real matrix operand).
 //  attend_finalize   one workgroup per (stream, strip).  Merges the strip
 //                    statistics of its stream into (m, l), adds
 //                    p_j = 2^(s_j - m) / l, summed over the G query heads, to
@@ -35,6 +37,7 @@
 #include <cmath>
 #include <limits>
 #include <numeric>
+#include <type_traits>
 #include <vector>
 
 #include "device_util.h"
@@ -45,6 +48,9 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kMaxHeld = 64;            // strips one workgroup of the fused kernel can hold
 
 struct PairDesc {
@@ -602,29 +608,90 @@ __global__ __launch_bounds__(kThreads) void attend_chunk(const AttendParams P) {
   const bool append_here = cx.append_here;
   const bool full = (c + 1) * kChunk <= n && !append_here;
 
-  float qf[G][EPL];
-  cx.load_q(P, cl, qf);
-
+  // V rows: issued together with the K rows so that they arrive during the
+  // logit and statistics phases.
+  uint4 vreg[NT];
+  if constexpr (std::is_same<T, BF16>::value) {
+    // Logits on the matrix cores: S[g][t] = sum_c Q[g][c] K[t][c] as D = A * B with
+    // A = the query group (rows g < G, zero rows up to 16) and B = 16 K rows.  In
+    // both operands lane (j, x) = (lane / 16, lane % 16) holds 8 consecutive
+    // channels 32 s + 8 j .. of row x for contraction slice s, so a K operand is a
+    // 16-byte load straight from the cache row: no staging.  The result has
+    // S[4 j + i][t = lane % 16] in register i of lane (j, t).
+    constexpr int NS = D / 32;              // contraction slices of 32 channels
+    const int x16 = lane & 15, j4 = lane >> 4;
+    bf16x8 qa[NS];
 #pragma unroll
-  for (int b0 = 0; b0 < NT; b0 += kTB) {
-    uint4 kreg[kTB];
-    load_rows<ROWB, RPW, kTB>(kreg, cx.kbase, cx.knew, row0 + b0 * RPW + sub, n, full, append_here, cl);
-#pragma unroll
-    for (int i = 0; i < kTB; ++i) {
-      float kf[EPL];
-      Unpack<T>::run(kreg[i], kf);
-      const int lr = wave * 64 + (b0 + i) * RPW + sub;   // row within the chunk
-      const bool valid = c * kChunk + lr < n;
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float a = 0.0f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) a = fmaf(kf[e], qf[g][e], a);
-        a = group_sum<LPR>(a);
-        if (cl == 0) s_sh[g][lr] = valid ? a * P.scale_log2e : -INFINITY;
+    for (int sl = 0; sl < NS; ++sl) {
+      uint4 raw = make_uint4(0, 0, 0, 0);
+      if (x16 < G) {
+        const int64_t hq = (static_cast<int64_t>(cx.pair) * P.n_kv_heads + cx.h) * G + x16;
+        raw = *reinterpret_cast<const uint4*>(static_cast<const char*>(P.q) + hq * ROWB + sl * 64 + j4 * 16);
       }
+      qa[sl] = __builtin_bit_cast(bf16x8, raw);
     }
-    if (append_here) store_appended<ROWB, RPW, kTB>(kreg, cx.kbase, row0 + b0 * RPW + sub, n, cl);
+    load_rows<ROWB, RPW, NT>(vreg, cx.vbase, cx.vnew, row0 + sub, n, full, append_here, cl);
+    // The wave's 64 rows are 4 groups of 16; two groups of K operands are in flight at a time.
+#pragma unroll
+    for (int g0 = 0; g0 < 4; g0 += 2) {
+      uint4 kb[2][NS];
+#pragma unroll
+      for (int gi = 0; gi < 2; ++gi) {
+        const int r = row0 + (g0 + gi) * 16 + x16;
+        const int rc = r < n ? r : n - 1;
+        const char* src = cx.kbase + static_cast<int64_t>(rc) * ROWB + j4 * 16;
+        if (append_here && r == n - 1) src = cx.knew + j4 * 16;
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) kb[gi][sl] = load_stream16(src + sl * 64);
+      }
+#pragma unroll
+      for (int gi = 0; gi < 2; ++gi) {
+        floatx4 acc4 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl)
+          acc4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[sl], __builtin_bit_cast(bf16x8, kb[gi][sl]), acc4, 0, 0, 0);
+        const int lr = wave * 64 + (g0 + gi) * 16 + x16;
+        const int r = c * kChunk + lr;
+        const bool valid = r < n;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int g = 4 * j4 + i;
+          if (g < G) s_sh[g][lr] = valid ? acc4[i] * P.scale_log2e : -INFINITY;
+        }
+        if (append_here && r == n - 1) {    // the append itself, K part
+#pragma unroll
+          for (int sl = 0; sl < NS; ++sl)
+            *reinterpret_cast<uint4*>(cx.kbase + static_cast<int64_t>(r) * ROWB + sl * 64 + j4 * 16) = kb[gi][sl];
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  } else {
+    float qf[G][EPL];
+    cx.load_q(P, cl, qf);
+#pragma unroll
+    for (int b0 = 0; b0 < NT; b0 += kTB) {
+      uint4 kreg[kTB];
+      load_rows<ROWB, RPW, kTB>(kreg, cx.kbase, cx.knew, row0 + b0 * RPW + sub, n, full, append_here, cl);
+      if (b0 + kTB >= NT)
+        load_rows<ROWB, RPW, NT>(vreg, cx.vbase, cx.vnew, row0 + sub, n, full, append_here, cl);
+#pragma unroll
+      for (int i = 0; i < kTB; ++i) {
+        float kf[EPL];
+        Unpack<T>::run(kreg[i], kf);
+        const int lr = wave * 64 + (b0 + i) * RPW + sub;   // row within the chunk
+        const bool valid = c * kChunk + lr < n;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float a = 0.0f;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) a = fmaf(kf[e], qf[g][e], a);
+          a = group_sum<LPR>(a);
+          if (cl == 0) s_sh[g][lr] = valid ? a * P.scale_log2e : -INFINITY;
+        }
+      }
+      if (append_here) store_appended<ROWB, RPW, kTB>(kreg, cx.kbase, row0 + b0 * RPW + sub, n, cl);
+    }
   }
   __syncthreads();
 
@@ -667,40 +734,46 @@ __global__ __launch_bounds__(kThreads) void attend_chunk(const AttendParams P) {
       }
   }
 
-  // Partial output: sum over this wave's rows of e_j V_j.
-  float acc[G][EPL];
+  // Partial output: sum over this wave's rows of e_j V_j, at most four query
+  // heads at a time (the V registers are reused), which keeps the accumulators
+  // small enough for several waves per SIMD.
+  constexpr int GP = G > 4 ? 4 : G;
+  if (append_here) store_appended<ROWB, RPW, NT>(vreg, cx.vbase, row0 + sub, n, cl);
 #pragma unroll
-  for (int g = 0; g < G; ++g)
+  for (int gp = 0; gp < G; gp += GP) {
+    float acc[GP][EPL];
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.0f;
+    for (int g = 0; g < GP; ++g)
 #pragma unroll
-  for (int b0 = 0; b0 < NT; b0 += kTB) {
-    uint4 vreg[kTB];
-    load_rows<ROWB, RPW, kTB>(vreg, cx.vbase, cx.vnew, row0 + b0 * RPW + sub, n, full, append_here, cl);
-    if (append_here) store_appended<ROWB, RPW, kTB>(vreg, cx.vbase, row0 + b0 * RPW + sub, n, cl);
+      for (int e = 0; e < EPL; ++e) acc[g][e] = 0.0f;
 #pragma unroll
-    for (int i = 0; i < kTB; ++i) {
+    for (int i = 0; i < NT; ++i) {
       float vf[EPL];
       Unpack<T>::run(vreg[i], vf);
-      const int lr = wave * 64 + (b0 + i) * RPW + sub;
+      const int lr = wave * 64 + i * RPW + sub;
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const float p = s_sh[g][lr];
+      for (int g = 0; g < GP; ++g) {
+        const float p = s_sh[gp + g][lr];
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vf[e], acc[g][e]);
       }
+      // Keeps the compiler from gathering the probability reads of all rows first
+      // (it would interchange the loops and hold them all in registers).
+      asm volatile("" ::: "memory");
     }
+    // Rows of a wave-wide load sit LPR lanes apart: fold them together.
+#pragma unroll
+    for (int g = 0; g < GP; ++g) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        float x = acc[g][e];
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) x += __shfl_xor(x, off);
+        if (sub == 0) o_sh[wave][gp + g][cl * EPL + e] = x;
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
-  // Rows of a wave-wide load sit LPR lanes apart: fold them together.
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-      float x = acc[g][e];
-#pragma unroll
-      for (int off = LPR; off < 64; off <<= 1) x += __shfl_xor(x, off);
-      if (sub == 0) o_sh[wave][g][cl * EPL + e] = x;
-    }
   __syncthreads();
   for (int idx = tid; idx < G * D; idx += kThreads) {
     const int g = idx / D, ch = idx - g * D;
