@@ -16,7 +16,8 @@
  *   - Pointers marked HOST are ordinary host memory, pointers marked DEVICE
  *     are device memory of the current HIP device.  All are owned by the
  *     caller; the library allocates no device memory and frees nothing.
- *     Scratch comes in through `workspace` (xkv_workspace_bytes).
+ *     Scratch comes in through `workspace` (xkv_workspace_bytes), a DEVICE
+ *     buffer aligned to 256 bytes.
  *   - Device work is enqueued on `hip_stream` (a hipStream_t, NULL = default
  *     stream) and the call returns without waiting.  The host `len` table is
  *     updated at enqueue time: lengths never depend on data.

@@ -18,12 +18,16 @@
 //                                     while the current one is used; the four
 //                                     waves merge once at the end; logits are
 //                                     collected in LDS and written in one burst.
-//                      attend_chunk   (G >= 4) strips of 256 slots handled by the
-//                                     whole workgroup in one pass; for bf16
-//                                     the logits come from bf16 MFMA (the
-//                                     query group is a real matrix operand).
-//  attend_finalize   one workgroup per (stream, strip).  Merges the strip
-//                    statistics of its stream into (m, l), adds
+//                      attend_gqa     (G >= 4, bf16, 128 channels) logits and
+//                                     output on the matrix cores (bf16 MFMA,
+//                                     fp32 result); each wave runs its own
+//                                     online softmax over tiles of 32 rows; a
+//                                     tile's logits leave as one aligned block.
+//                      attend_chunk   (other G >= 4 cases) strips of 256 slots
+//                                     handled by the whole workgroup in one
+//                                     pass; bf16 logits from MFMA.
+//  attend_finalize   one workgroup per (stream, up to 4096 slots).  Merges the
+//                    strip statistics of its stream into (m, l), adds
 //                    p_j = 2^(s_j - m) / l, summed over the G query heads, to
 //                    score[j] for its own slots, and computes its share of the
 //                    channels of out = sum_s 2^(m_s - m) o_s / l.
@@ -52,13 +56,15 @@ constexpr int kWaves = kThreads / 64;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kMaxHeld = 64;            // strips one workgroup of the fused kernel can hold
+constexpr int kGqaStripRows = 512;      // strip length of attend_gqa (measured best among 256 .. 4096)
 
 struct PairDesc {
   int64_t slot0;    // first slot of the region
   int32_t cap;      // slots per stream
   int32_t n;        // live slots, the appended token included
   int32_t strip0;   // first strip record of the region in the launch's workspace (canonical order)
-  int32_t full0;    // first streaming workgroup (fused kernel: queue position) among the full strips
+  int32_t full0;    // first streaming workgroup (fused kernel: queue position) among the full strips;
+                    // in the finalize launch: first finalize workgroup of the region
 };
 
 struct AttendParams {
@@ -82,14 +88,16 @@ struct AttendParams {
   int32_t n_tail_pairs;   // regions whose streams end in a partial strip
   int32_t rec_floats;     // floats per strip record in the workspace
   int32_t lds_rows;       // fused kernel: rows of logits a workgroup can hold
+  int32_t fin_strips;     // finalize kernel: strips per workgroup
   PairDesc pairs[kMaxPairs];
   int32_t pos_new[kMaxPairs];    // original position of the token appended to each region
   uint8_t tail_order[kMaxPairs]; // regions with a partial last strip, longest tail first
 };
 
-// Floats per strip record: per query head, strip_rows logits, D partial outputs, (m, l).
+// Floats per strip record: per query head, strip_rows logits, D partial outputs,
+// (m, l); padded so that every record starts on a 128-byte line.
 __host__ __device__ inline int64_t record_floats(int group, int head_dim, int strip_rows) {
-  return static_cast<int64_t>(group) * (strip_rows + head_dim + 2);
+  return (static_cast<int64_t>(group) * (strip_rows + head_dim + 2) + 31) / 32 * 32;
 }
 
 struct StripWork { int pair_local, h, s; };
@@ -785,11 +793,264 @@ __global__ __launch_bounds__(kThreads) void attend_chunk(const AttendParams P) {
 }
 
 // ---------------------------------------------------------------------------
-template <int D, int G>
+// Streaming kernel for query groups of 4 and 8 over bf16 rows of 128 channels:
+// both contractions run on the matrix cores (16x16x32 bf16 MFMA, fp32 result),
+// the VALUs only do the softmax.  One workgroup per (stream, strip); its waves
+// take the strip's tiles of 32 rows in turn and each keeps its own running
+// (m, l, o); the four waves merge at the end.
+//
+// Lane (j, x) = (lane / 16, lane % 16).  An MFMA operand holds, per lane, 8
+// consecutive contraction indices 8 j .. 8 j + 7 of row (A) or column (B) x, and
+// the result has element (4 j + i, x) in register i.
+//   logits   S^T = K Q^T per 16 rows: A = K rows (a 16-byte load straight from the
+//            cache row), B = the query group (columns g >= G are zero).  Lane
+//            (j, g) receives the logits of head g for rows 4 j .. 4 j + 3.
+//   output   O += P V per 32 rows: the probabilities a lane holds after two
+//            logit MFMAs (rows 4 j + i and 16 + 4 j + i) are exactly one A operand,
+//            so P never changes lanes.  The matching B operand needs, per lane, 8
+//            rows of one channel: the lane loads 16 bytes (channels 8 x .. 8 x + 7)
+//            of each of its 8 rows and transposes the 8 x 8 block in registers
+//            with byte permutes; MFMA c then produces channels 8 x + c.
+// A probability enters the MFMA as the sum of two bf16 numbers (the rounded
+// value and the rounded remainder), which keeps its relative error below 2^-16.
+template <int G>
+__global__ __launch_bounds__(kThreads) void attend_gqa(const AttendParams P) {
+  constexpr int D = 128, ROWB = 256, NS = D / 32, kTile = 32;
+  typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+  __shared__ float o_sh[kWaves][G][D];
+  __shared__ float ml_sh[kWaves][G][2];
+  __shared__ __attribute__((aligned(16))) float lg_sh[kWaves][kTile * G];   // a tile's logits, [row][head]
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int x = lane & 15, j = lane >> 4;
+
+  StreamCtx<BF16, D, G> cx;
+  cx.init(P, locate_stream_block(P, blockIdx.x));
+  const int n = cx.n;
+  const int strip_rows = P.strip_rows;
+  const int r_begin = cx.s * strip_rows;
+  const int r_end = min(n, r_begin + strip_rows);
+  const int tiles = (r_end - r_begin + kTile - 1) / kTile;
+  const bool append_here = cx.append_here;
+  const int n_plain = n - (append_here ? 1 : 0);   // rows below this come straight from the cache
+  float* rec = cx.rec;
+
+  bf16x8 qb[NS];
+#pragma unroll
+  for (int sl = 0; sl < NS; ++sl) {
+    uint4 raw = make_uint4(0, 0, 0, 0);
+    if (x < G) {
+      const int64_t hq = (static_cast<int64_t>(cx.pair) * P.n_kv_heads + cx.h) * G + x;
+      raw = *reinterpret_cast<const uint4*>(static_cast<const char*>(P.q) + hq * ROWB + sl * 64 + j * 16);
+    }
+    qb[sl] = __builtin_bit_cast(bf16x8, raw);
+  }
+
+  floatx4 acc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+  float m_run = -INFINITY;                  // head x, all rows of this wave so far
+  float l_run = 0.0f;                       // head x, this lane's rows only
+
+  auto dword = [](const uint4& u, int k) { return k == 0 ? u.x : k == 1 ? u.y : k == 2 ? u.z : u.w; };
+  // Row of V load i of this lane within a tile.
+  auto vrow = [&](int i) { return (i < 4 ? 0 : 12) + 4 * j + i; };
+  // Rows at or past n are clamped to row n-1 (their logits are masked); the
+  // lanes of an appended row n-1 read the new token instead of the empty slot.
+  auto issue_k = [&](uint4 (&kb)[2][NS], int t) {
+    const int row0 = r_begin + t * kTile;
+    if (row0 + kTile <= n_plain) {
+      const char* ks = cx.kbase + static_cast<int64_t>(row0 + x) * ROWB + j * 16;
+#pragma unroll
+      for (int grp = 0; grp < 2; ++grp)
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) kb[grp][sl] = load_stream16(ks + grp * 16 * ROWB + sl * 64);
+    } else {
+#pragma unroll
+      for (int grp = 0; grp < 2; ++grp) {
+        const int r = row0 + grp * 16 + x;
+        const int rc = r < n ? r : n - 1;
+        const char* src = cx.kbase + static_cast<int64_t>(rc) * ROWB + j * 16;
+        if (append_here && rc == n - 1) src = cx.knew + j * 16;
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) kb[grp][sl] = load_stream16(src + sl * 64);
+      }
+    }
+  };
+  auto issue_v = [&](uint4 (&vb)[8], int t) {
+    const int row0 = r_begin + t * kTile;
+    if (row0 + kTile <= n_plain) {
+      const char* vs = cx.vbase + static_cast<int64_t>(row0 + 4 * j) * ROWB + x * 16;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) vb[i] = load_stream16(vs + ((i < 4 ? 0 : 12) + i) * ROWB);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int r = row0 + vrow(i);
+        const int rc = r < n ? r : n - 1;
+        const char* src = cx.vbase + static_cast<int64_t>(rc) * ROWB + x * 16;
+        if (append_here && rc == n - 1) src = cx.vnew + x * 16;
+        vb[i] = load_stream16(src);
+      }
+    }
+  };
+
+  // The wave's tiles are wave, wave + 4, ...  K and V have one register buffer
+  // each; the K rows of the next tile are requested as soon as the logit MFMAs
+  // have consumed the current ones, the V rows after the output MFMAs, so each
+  // request has half a tile of work (and the other resident waves) to hide behind.
+  uint4 kb[2][NS], vb[8];
+  if (wave < tiles) {
+    issue_k(kb, wave);
+    issue_v(vb, wave);
+  }
+  for (int t = wave; t < tiles; t += kWaves) {
+    const int row0 = r_begin + t * kTile;
+    const bool more = t + kWaves < tiles;
+    const bool last_tile = append_here && row0 + kTile >= n;   // holds the appended row n-1
+    float sv[8];
+#pragma unroll
+    for (int grp = 0; grp < 2; ++grp) {
+      floatx4 a = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int sl = 0; sl < NS; ++sl)
+        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[grp][sl]), qb[sl], a, 0, 0, 0);
+      const int r = row0 + grp * 16 + 4 * j;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        sv[grp * 4 + i] = r + i < r_end ? a[i] * P.scale_log2e : -INFINITY;
+        if (x < G) lg_sh[wave][(grp * 16 + 4 * j + i) * G + x] = sv[grp * 4 + i];
+      }
+    }
+    if (last_tile) {                          // the append itself, K part
+#pragma unroll
+      for (int grp = 0; grp < 2; ++grp)
+        if (row0 + grp * 16 + x == n - 1) {
+#pragma unroll
+          for (int sl = 0; sl < NS; ++sl)
+            *reinterpret_cast<uint4*>(cx.kbase + static_cast<int64_t>(n - 1) * ROWB + sl * 64 + j * 16) = kb[grp][sl];
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) issue_k(kb, t + kWaves);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // Online softmax for head x: the tile's first row is live, so the maximum is finite.
+    float tm = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
+                     fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+    tm = fmaxf(tm, __shfl_xor(tm, 16));
+    tm = fmaxf(tm, __shfl_xor(tm, 32));
+    const float m_new = fmaxf(m_run, tm);
+    const float alpha = fast_exp2(m_run - m_new);
+    const bool moved = m_new > m_run;
+    m_run = m_new;
+    float pv[8];
+    float ls = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      pv[i] = fast_exp2(sv[i] - m_new);
+      ls += pv[i];
+    }
+    l_run = fmaf(l_run, alpha, ls);
+    if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+      // Accumulator register i of lane (j, .) belongs to head 4 j + i.
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float a_i = __shfl(alpha, 4 * j + i);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[c][i] *= a_i;
+      }
+    }
+    bf16x8 p_hi, p_lo;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      p_hi[i] = static_cast<__bf16>(pv[i]);
+      p_lo[i] = static_cast<__bf16>(pv[i] - static_cast<float>(p_hi[i]));
+    }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const unsigned sel = (c & 1) ? 0x07060302u : 0x05040100u;
+      uintx4 vt;
+#pragma unroll
+      for (int rp = 0; rp < 4; ++rp)
+        vt[rp] = __builtin_amdgcn_perm(dword(vb[2 * rp + 1], c >> 1), dword(vb[2 * rp], c >> 1), sel);
+      const bf16x8 vop = __builtin_bit_cast(bf16x8, vt);
+      acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(p_hi, vop, acc[c], 0, 0, 0);
+      acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(p_lo, vop, acc[c], 0, 0, 0);
+    }
+    if (last_tile) {                          // the append itself, V part
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (row0 + vrow(i) == n - 1)
+          *reinterpret_cast<uint4*>(cx.vbase + static_cast<int64_t>(n - 1) * ROWB + x * 16) = vb[i];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) issue_v(vb, t + kWaves);
+    __builtin_amdgcn_sched_barrier(0);
+    // The tile's logits leave as one contiguous, line-aligned block [row][head]
+    // (the wave's own LDS staging turns them; LDS keeps a wave's accesses in
+    // order).  The store comes after the requests for the next tile: the waits
+    // for those then do not include it.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (4 * lane < kTile * G) {
+      const floatx4 lg = *reinterpret_cast<const floatx4*>(&lg_sh[wave][4 * lane]);
+      __builtin_nontemporal_store(
+          lg, reinterpret_cast<floatx4*>(rec + static_cast<int64_t>(row0 - r_begin) * G + 4 * lane));
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  // Merge the four waves.
+  float l = l_run;
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+  if (j == 0 && x < G) {
+    ml_sh[wave][x][0] = m_run;
+    ml_sh[wave][x][1] = l;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int g = 4 * j + i;
+    if (g < G) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) o_sh[wave][g][8 * x + c] = acc[c][i];
+    }
+  }
+  __syncthreads();
+  float* rec_o = rec + G * strip_rows;
+  float* rec_ml = rec + G * (strip_rows + D);
+  for (int idx = tid; idx < G * (D + 1); idx += kThreads) {
+    const int g = idx / (D + 1), ch = idx - g * (D + 1);     // ch == D: the sum l
+    float m = ml_sh[0][g][0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) m = fmaxf(m, ml_sh[w][g][0]);
+    float tot = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float part = ch < D ? o_sh[w][g][ch] : ml_sh[w][g][1];
+      tot += part * fast_exp2(ml_sh[w][g][0] - m);
+    }
+    if (ch < D) {
+      store_stream(&rec_o[g * D + ch], tot);
+    } else {
+      store_stream(&rec_ml[2 * g], m);
+      store_stream(&rec_ml[2 * g + 1], tot);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// kByRow: the record's logits are stored [slot][head] (attend_gqa) instead of [head][slot].
+template <int D, int G, bool kByRow = false>
 __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P) {
   constexpr int GD = G * D;
-  extern __shared__ float dyn_sh[];         // [G][nstrips] strip weights, then [G][nstrips] strip sums
-  __shared__ float red_sh[kWaves];
+  extern __shared__ float w_sh[];           // [G][nstrips] strip weights 2^(m_s - m) / l
+  __shared__ float m_sh[G], inv_sh[G];
   __shared__ float o_red[kThreads];
 
   const int tid = threadIdx.x;
@@ -797,21 +1058,24 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P
   const int wave = tid >> 6;
   const int bid = blockIdx.x;
   const int strip_rows = P.strip_rows;
+  const int F = P.fin_strips;
   const int64_t REC = record_floats(G, D, strip_rows);
 
-  // Region: last pair whose first strip is <= bid.  An empty stream owns one strip.
+  // Region: last pair whose first finalize workgroup is <= bid (in this launch
+  // full0 holds that number).  An empty stream owns one strip and one workgroup.
   int lo = 0, hi = P.n_pairs - 1;
   while (lo < hi) {
     const int mid = (lo + hi + 1) >> 1;
-    if (P.pairs[mid].strip0 <= bid) lo = mid; else hi = mid - 1;
+    if (P.pairs[mid].full0 <= bid) lo = mid; else hi = mid - 1;
   }
   const PairDesc pd = P.pairs[lo];
   const int n = pd.n;
   const int nstrips_live = (n + strip_rows - 1) / strip_rows;
   const int nstrips = nstrips_live > 0 ? nstrips_live : 1;
-  const int local = bid - pd.strip0;
-  const int h = local / nstrips;
-  const int s_own = local - h * nstrips;
+  const int nfin = (nstrips + F - 1) / F;
+  const int local = bid - pd.full0;
+  const int h = local / nfin;
+  const int f_own = local - h * nfin;
   const int pair = P.pair_base + lo;
   float* out = P.out + (static_cast<int64_t>(pair) * P.n_kv_heads + h) * GD;
   if (n == 0) {
@@ -819,70 +1083,68 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P
     return;
   }
   const float* rec0 = P.ws + (static_cast<int64_t>(pd.strip0) + static_cast<int64_t>(h) * nstrips) * REC;
-  float* w_sh = dyn_sh;
-  float* l_sh = dyn_sh + G * nstrips;
 
-  // Stream statistics from the strip statistics.  Every workgroup of the stream
-  // repeats this small reduction in the same order, so all agree bit for bit.
-  for (int c = tid; c < nstrips; c += kThreads) {
-    const float* ml = rec0 + static_cast<int64_t>(c) * REC + G * (strip_rows + D);
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      w_sh[g * nstrips + c] = ml[2 * g];
-      l_sh[g * nstrips + c] = ml[2 * g + 1];
+  // Stream statistics from the strip statistics, one wave per query head.  Every
+  // workgroup of the stream repeats this small reduction in the same order, so
+  // all agree bit for bit.
+  for (int g = wave; g < G; g += kWaves) {
+    const float* ml = rec0 + G * (strip_rows + D) + 2 * g;
+    float m = -INFINITY;
+    for (int c = lane; c < nstrips; c += 64) m = fmaxf(m, ml[static_cast<int64_t>(c) * REC]);
+    m = wave_max(m);
+    float l = 0.0f;
+    for (int c = lane; c < nstrips; c += 64) {
+      const float wgt = fast_exp2(ml[static_cast<int64_t>(c) * REC] - m);
+      w_sh[g * nstrips + c] = wgt;
+      l = fmaf(wgt, ml[static_cast<int64_t>(c) * REC + 1], l);
     }
+    l = wave_sum(l);
+    const float inv = 1.0f / l;
+    for (int c = lane; c < nstrips; c += 64) w_sh[g * nstrips + c] *= inv;
+    if (lane == 0) { m_sh[g] = m; inv_sh[g] = inv; }
   }
   __syncthreads();
   float m_g[G], inv_g[G];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float m = -INFINITY;
-    for (int c = tid; c < nstrips; c += kThreads) m = fmaxf(m, w_sh[g * nstrips + c]);
-    m = wave_max(m);
-    if (lane == 0) red_sh[wave] = m;
-    __syncthreads();
-    m = fmaxf(fmaxf(red_sh[0], red_sh[1]), fmaxf(red_sh[2], red_sh[3]));
-    __syncthreads();
-    float l = 0.0f;
-    for (int c = tid; c < nstrips; c += kThreads) {
-      const float wgt = fast_exp2(w_sh[g * nstrips + c] - m);
-      w_sh[g * nstrips + c] = wgt;
-      l += wgt * l_sh[g * nstrips + c];
-    }
-    l = wave_sum(l);
-    if (lane == 0) red_sh[wave] = l;
-    __syncthreads();
-    l = (red_sh[0] + red_sh[1]) + (red_sh[2] + red_sh[3]);
-    const float inv = 1.0f / l;
-    for (int c = tid; c < nstrips; c += kThreads) w_sh[g * nstrips + c] *= inv;
-    m_g[g] = m;
-    inv_g[g] = inv;
-    __syncthreads();
-  }
+  for (int g = 0; g < G; ++g) { m_g[g] = m_sh[g]; inv_g[g] = inv_sh[g]; }
 
-  // score_j += sum_g 2^(s_gj - m_g) / l_g for the slots of this strip; the
-  // appended token starts from zero.
+  // score_j += sum_g 2^(s_gj - m_g) / l_g for the slots of this workgroup's
+  // strips; the appended token starts from zero.
   const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
   float* score = P.score + stream_slot;
-  const int r_begin = s_own * strip_rows;
-  const int rows = min(n, r_begin + strip_rows) - r_begin;
-  const float* lg = rec0 + static_cast<int64_t>(s_own) * REC;
+  const int shift = __ffs(strip_rows) - 1;  // strip lengths are powers of two
+  const int s_begin = f_own * F;
+  const int r_begin = s_begin << shift;
+  const int rows = min(n, (s_begin + F) << shift) - r_begin;
+  const float* lg0 = rec0 + static_cast<int64_t>(s_begin) * REC;
 #pragma unroll 4
   for (int j = tid; j < rows; j += kThreads) {
+    const int js = j & (strip_rows - 1);
+    const float* lg = lg0 + static_cast<int64_t>(j >> shift) * REC + (kByRow ? js * G : js);
     float add = 0.0f;
+    if constexpr (kByRow) {
+      static_assert(!kByRow || G % 4 == 0, "");
 #pragma unroll
-    for (int g = 0; g < G; ++g) add = fmaf(fast_exp2(lg[g * strip_rows + j] - m_g[g]), inv_g[g], add);
+      for (int g4 = 0; g4 < G / 4; ++g4) {
+        const floatx4 v = *reinterpret_cast<const floatx4*>(lg + 4 * g4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) add = fmaf(fast_exp2(v[i] - m_g[4 * g4 + i]), inv_g[4 * g4 + i], add);
+      }
+    } else {
+#pragma unroll
+      for (int g = 0; g < G; ++g) add = fmaf(fast_exp2(lg[g * strip_rows] - m_g[g]), inv_g[g], add);
+    }
     const int row = r_begin + j;
     const float old = (P.append && row == n - 1) ? 0.0f : score[row];
     score[row] = old + add;
   }
-  if (P.append && s_own == 0 && tid == 0) P.pos[stream_slot + n - 1] = P.pos_new[lo];
+  if (P.append && f_own == 0 && tid == 0) P.pos[stream_slot + n - 1] = P.pos_new[lo];
 
   // out = sum_s w_s o_s.  The G*D channels of the stream are split evenly over
   // its workgroups.  Within a workgroup the threads form (channel, slice)
   // pairs; a slice sums every S-th strip, then the slices are added in order.
-  const int cpb = (GD + nstrips - 1) / nstrips;
-  const int ch_first = s_own * cpb;
+  const int cpb = (GD + nfin - 1) / nfin;
+  const int ch_first = f_own * cpb;
   const int nch = min(cpb, GD - ch_first);
   for (int tb = 0; tb < nch; tb += kThreads) {
     const int tn = min(kThreads, nch - tb);
@@ -914,27 +1176,36 @@ struct Kernels {
   KernelFn stream = nullptr;
   KernelFn finalize = nullptr;
   KernelFn fused = nullptr;
-  bool strips = false;      // the streaming kernel is attend_strip (long strips, dynamic LDS)
+  int max_strip_rows = kChunk;  // longest strip the streaming kernel is given (a power of two)
+  bool lds_logits = false;      // the streaming kernel collects the strip's logits in dynamic LDS
 };
 
 template <typename T, int D>
 bool pick_group(int group, Kernels* k) {
   switch (group) {
     case 1:
-      k->stream = attend_strip<T, D, 1, 8>; k->finalize = attend_finalize<D, 1>; k->strips = true;
+      k->stream = attend_strip<T, D, 1, 8>; k->finalize = attend_finalize<D, 1>;
+      k->max_strip_rows = kMaxStripRows; k->lds_logits = true;
       k->fused = attend_fused<T, D, 1, 8>;
       return true;
     case 2:
-      k->stream = attend_strip<T, D, 2, 8>; k->finalize = attend_finalize<D, 2>; k->strips = true;
+      k->stream = attend_strip<T, D, 2, 8>; k->finalize = attend_finalize<D, 2>;
+      k->max_strip_rows = kMaxStripRows; k->lds_logits = true;
       k->fused = attend_fused<T, D, 2, 8>;
       return true;
     case 4:
       k->stream = attend_chunk<T, D, 4>; k->finalize = attend_finalize<D, 4>;
       k->fused = attend_fused<T, D, 4, 4>;
+      if constexpr (std::is_same<T, BF16>::value && D == 128) {
+        k->stream = attend_gqa<4>; k->finalize = attend_finalize<D, 4, true>; k->max_strip_rows = kGqaStripRows;
+      }
       return true;
     case 8:
       k->stream = attend_chunk<T, D, 8>; k->finalize = attend_finalize<D, 8>;
       k->fused = attend_fused<T, D, 8, 2>;
+      if constexpr (std::is_same<T, BF16>::value && D == 128) {
+        k->stream = attend_gqa<8>; k->finalize = attend_finalize<D, 8, true>; k->max_strip_rows = kGqaStripRows;
+      }
       return true;
     default: return false;
   }
@@ -951,9 +1222,8 @@ bool pick_kernels(int dtype, int head_dim, int group, Kernels* k) {
 // Strip length of a call: long strips amortise the per-strip record and let a
 // workgroup pipeline its loads, but a call must still spread over the whole
 // chip, so the strips shrink until there are enough of them.
-int choose_strip_rows(bool strips, int64_t streams, int64_t total_rows) {
-  if (!strips) return kChunk;
-  int rows = kMaxStripRows;
+int choose_strip_rows(int max_rows, int64_t streams, int64_t total_rows) {
+  int rows = max_rows;
   const int64_t want = 2048;                // several workgroups per compute unit
   while (rows > kChunk && total_rows / rows + streams / 2 < want) rows >>= 1;
   return rows;
@@ -1047,6 +1317,7 @@ xkv_status launch_fused(const xkv_cache* cache, int64_t first, int64_t n_pairs, 
   P.strip_rows = strip_rows;
   P.rec_floats = static_cast<int32_t>(seg);
   P.lds_rows = lds_rows;
+  P.fin_strips = 1;
   int64_t strips_done = 0;
   for (size_t gi = 0; gi < groups.size(); ++gi) {
     const Group& gr = groups[gi];
@@ -1106,8 +1377,9 @@ size_t attend_workspace_bytes(const xkv_cache* c, int32_t layers) {
   for (int32_t l = 0; l < c->n_layers; ++l)
     for (int32_t b = 0; b < c->batch; ++b) {
       const int64_t cap = c->cap[static_cast<int64_t>(l) * c->batch + b];
-      const int64_t floats = cap + kMaxStripRows + std::max<int64_t>(ceil_div(cap, kChunk), 1) * (d + 2);
-      need[l] += static_cast<size_t>(floats) * group * hkv * sizeof(float);
+      const int64_t floats = (cap + kMaxStripRows) * group +
+                             std::max<int64_t>(ceil_div(cap, kChunk), 1) * ((d + 2) * group + 32);
+      need[l] += static_cast<size_t>(floats) * hkv * sizeof(float);
     }
   std::sort(need.begin(), need.end(), std::greater<size_t>());
   size_t tot = 0;
@@ -1159,7 +1431,7 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
     max_n = std::max(max_n, n);
   }
   if (workspace == nullptr) return XKV_ERR_INVALID_ARG;
-  if (reinterpret_cast<uintptr_t>(workspace) & 3u) return XKV_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return XKV_ERR_INVALID_ARG;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt(static_cast<float>(D));
   AttendParams P;
@@ -1181,7 +1453,7 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
     if (fs != XKV_ERR_UNSUPPORTED || g_attend_path == 2) return fs;
   }
 
-  const int strip_rows = choose_strip_rows(kern.strips, n_pairs * hkv, total_rows);
+  const int strip_rows = choose_strip_rows(kern.max_strip_rows, n_pairs * hkv, total_rows);
   const int64_t rec = record_floats(G, D, strip_rows);
   int64_t total_strips = 0;
   for (int64_t i = 0; i < n_pairs; ++i) {
@@ -1191,13 +1463,18 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
   if (static_cast<uint64_t>(total_strips) * rec * sizeof(float) > workspace_bytes)
     return XKV_ERR_CAPACITY;
   const int64_t max_strips = std::max<int64_t>(ceil_div(max_n, strip_rows), 1);
-  const size_t fin_lds = static_cast<size_t>(max_strips) * G * 2 * sizeof(float);
+  const size_t fin_lds = static_cast<size_t>(max_strips) * G * sizeof(float);
+  // A finalize workgroup covers up to kMaxStripRows slots, fewer when the call
+  // is small and would otherwise leave compute units without one.
+  int fin_strips = std::max(1, kMaxStripRows / strip_rows);
+  while (fin_strips > 1 && total_strips / fin_strips < 1024) fin_strips >>= 1;
   if (fin_lds > 48 * 1024) return XKV_ERR_UNSUPPORTED;
-  const size_t stream_lds = kern.strips ? static_cast<size_t>(G) * strip_rows * sizeof(float) : 0;
+  const size_t stream_lds = kern.lds_logits ? static_cast<size_t>(G) * strip_rows * sizeof(float) : 0;
 
   P.strip_rows = strip_rows;
   P.rec_floats = static_cast<int32_t>(rec);
   P.lds_rows = 0;
+  P.fin_strips = fin_strips;
   P.barrier = nullptr;
 
   int64_t strips_done = 0;
@@ -1236,7 +1513,13 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
       profile_end(tok, stream);
       if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     }
-    hipLaunchKernelGGL(kern.finalize, dim3(static_cast<unsigned>(strips)), dim3(kThreads), fin_lds,
+    int64_t fin_blocks = 0;
+    for (int i = 0; i < np; ++i) {
+      PairDesc& pd = P.pairs[i];
+      pd.full0 = static_cast<int32_t>(fin_blocks);
+      fin_blocks += ceil_div(std::max<int64_t>(ceil_div(pd.n, strip_rows), 1), fin_strips) * hkv;
+    }
+    hipLaunchKernelGGL(kern.finalize, dim3(static_cast<unsigned>(fin_blocks)), dim3(kThreads), fin_lds,
                        stream, P);
     if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     strips_done += strips;

@@ -372,7 +372,7 @@ extern "C" xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, i
   const int64_t units = n_pairs * hkv;
   const uint64_t need_bytes = static_cast<uint64_t>(words) * 12 + static_cast<uint64_t>(units) * 4;
   if (workspace == nullptr || need_bytes > workspace_bytes) return XKV_ERR_CAPACITY;
-  if (reinterpret_cast<uintptr_t>(workspace) & 3u) return XKV_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return XKV_ERR_INVALID_ARG;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (any_work || kept_idx_out != nullptr) {

@@ -155,3 +155,15 @@ def test_mass_conservation_on_device(xkv):
             for h in range(2):
                 _, _, sc, _ = get_unit(cache, 0, b, h)
                 assert abs(float(sc.astype(np.float64).sum()) - 4.0 * (step + 1)) < 1e-3
+
+
+@pytest.mark.parametrize("G", [4, 8])
+def test_gqa_call_large_enough_for_full_length_strips(xkv, G):
+    """Over a million slots in one call: the matrix-core kernel gets its longest
+    strips (several tiles per wave) and a finalize workgroup covers several strips;
+    streams end in ragged tails of every tile phase."""
+    lens = [[90001 + G, 45003]]
+    o, s = run_case(xkv, "bf16", 128, 8 * G, 8, 1, 2, lens, True, seed=60 + G, paths=(0,))
+    print(f"gqa G={G} long strips rel err out {o:.2e} score {s:.2e}", flush=True)
+    # far inside the bf16-input tolerance: probabilities enter the MFMA as bf16 pairs
+    assert o < 1e-4 and s < 1e-4
