@@ -802,9 +802,11 @@ __global__ __launch_bounds__(kThreads) void attend_chunk(const AttendParams P) {
 // Lane (j, x) = (lane / 16, lane % 16).  An MFMA operand holds, per lane, 8
 // consecutive contraction indices 8 j .. 8 j + 7 of row (A) or column (B) x, and
 // the result has element (4 j + i, x) in register i.
-//   logits   S^T = K Q^T per 16 rows: A = K rows (a 16-byte load straight from the
-//            cache row), B = the query group (columns g >= G are zero).  Lane
-//            (j, g) receives the logits of head g for rows 4 j .. 4 j + 3.
+//   logits   S^T = K Q^T per 16 rows: A = K rows, B = the query group (columns
+//            g >= G are zero).  Lane (j, g) receives the logits of head g for
+//            rows 4 j .. 4 j + 3.  An A operand read straight from the cache would
+//            take 64 bytes of each of 16 rows per instruction; reading whole rows
+//            and turning the tile in LDS measured 10 % faster on short streams.
 //   output   O += P V per 32 rows: the probabilities a lane holds after two
 //            logit MFMAs (rows 4 j + i and 16 + 4 j + i) are exactly one A operand,
 //            so P never changes lanes.  The matching B operand needs, per lane, 8
@@ -820,6 +822,8 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const AttendParams P) {
   __shared__ float o_sh[kWaves][G][D];
   __shared__ float ml_sh[kWaves][G][2];
   __shared__ __attribute__((aligned(16))) float lg_sh[kWaves][kTile * G];   // a tile's logits, [row][head]
+  constexpr int kPitch = ROWB + 16;         // staged K rows, padded against bank conflicts
+  __shared__ __attribute__((aligned(16))) char kt_sh[kWaves][kTile * kPitch];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -859,49 +863,34 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const AttendParams P) {
   auto vrow = [&](int i) { return (i < 4 ? 0 : 12) + 4 * j + i; };
   // Rows at or past n are clamped to row n-1 (their logits are masked); the
   // lanes of an appended row n-1 read the new token instead of the empty slot.
-  auto issue_k = [&](uint4 (&kb)[2][NS], int t) {
+  // One tile of K or V: load i of lane (j, x) is the 16 bytes at column x of row
+  // vrow(i), so that every instruction reads whole 256-byte rows.
+  auto issue = [&](uint4 (&rb)[8], int t, const char* base, const char* newrow) {
     const int row0 = r_begin + t * kTile;
     if (row0 + kTile <= n_plain) {
-      const char* ks = cx.kbase + static_cast<int64_t>(row0 + x) * ROWB + j * 16;
+      const char* src = base + static_cast<int64_t>(row0 + 4 * j) * ROWB + x * 16;
 #pragma unroll
-      for (int grp = 0; grp < 2; ++grp)
-#pragma unroll
-        for (int sl = 0; sl < NS; ++sl) kb[grp][sl] = load_stream16(ks + grp * 16 * ROWB + sl * 64);
-    } else {
-#pragma unroll
-      for (int grp = 0; grp < 2; ++grp) {
-        const int r = row0 + grp * 16 + x;
-        const int rc = r < n ? r : n - 1;
-        const char* src = cx.kbase + static_cast<int64_t>(rc) * ROWB + j * 16;
-        if (append_here && rc == n - 1) src = cx.knew + j * 16;
-#pragma unroll
-        for (int sl = 0; sl < NS; ++sl) kb[grp][sl] = load_stream16(src + sl * 64);
-      }
-    }
-  };
-  auto issue_v = [&](uint4 (&vb)[8], int t) {
-    const int row0 = r_begin + t * kTile;
-    if (row0 + kTile <= n_plain) {
-      const char* vs = cx.vbase + static_cast<int64_t>(row0 + 4 * j) * ROWB + x * 16;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) vb[i] = load_stream16(vs + ((i < 4 ? 0 : 12) + i) * ROWB);
+      for (int i = 0; i < 8; ++i) rb[i] = load_stream16(src + ((i < 4 ? 0 : 12) + i) * ROWB);
     } else {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int r = row0 + vrow(i);
         const int rc = r < n ? r : n - 1;
-        const char* src = cx.vbase + static_cast<int64_t>(rc) * ROWB + x * 16;
-        if (append_here && rc == n - 1) src = cx.vnew + x * 16;
-        vb[i] = load_stream16(src);
+        const char* src = base + static_cast<int64_t>(rc) * ROWB + x * 16;
+        if (append_here && rc == n - 1) src = newrow + x * 16;
+        rb[i] = load_stream16(src);
       }
     }
   };
+  auto issue_k = [&](uint4 (&rb)[8], int t) { issue(rb, t, cx.kbase, cx.knew); };
+  auto issue_v = [&](uint4 (&rb)[8], int t) { issue(rb, t, cx.vbase, cx.vnew); };
 
   // The wave's tiles are wave, wave + 4, ...  K and V have one register buffer
-  // each; the K rows of the next tile are requested as soon as the logit MFMAs
-  // have consumed the current ones, the V rows after the output MFMAs, so each
-  // request has half a tile of work (and the other resident waves) to hide behind.
-  uint4 kb[2][NS], vb[8];
+  // each; the K rows of the next tile are requested as soon as the current ones
+  // sit in LDS, the V rows after the output MFMAs, so each request has most of a
+  // tile's work (and the other resident waves) to hide behind.
+  uint4 kb[8], vb[8];
+  char* kt = kt_sh[wave];
   if (wave < tiles) {
     issue_k(kb, wave);
     issue_v(vb, wave);
@@ -910,13 +899,31 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const AttendParams P) {
     const int row0 = r_begin + t * kTile;
     const bool more = t + kWaves < tiles;
     const bool last_tile = append_here && row0 + kTile >= n;   // holds the appended row n-1
+    // The K tile passes through the wave's LDS staging area to reach the MFMA
+    // operand layout (row x of each 16-row group, 16 bytes at column 4 sl + j).
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      *reinterpret_cast<uint4*>(kt + vrow(i) * kPitch + x * 16) = kb[i];
+    if (last_tile) {                          // the append itself, K part
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (row0 + vrow(i) == n - 1)
+          *reinterpret_cast<uint4*>(cx.kbase + static_cast<int64_t>(n - 1) * ROWB + x * 16) = kb[i];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) issue_k(kb, t + kWaves);
+    __builtin_amdgcn_sched_barrier(0);
     float sv[8];
 #pragma unroll
     for (int grp = 0; grp < 2; ++grp) {
       floatx4 a = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-      for (int sl = 0; sl < NS; ++sl)
-        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[grp][sl]), qb[sl], a, 0, 0, 0);
+      for (int sl = 0; sl < NS; ++sl) {
+        const uint4 ka = *reinterpret_cast<const uint4*>(kt + (grp * 16 + x) * kPitch + sl * 64 + j * 16);
+        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), qb[sl], a, 0, 0, 0);
+      }
       const int r = row0 + grp * 16 + 4 * j;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -924,18 +931,8 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const AttendParams P) {
         if (x < G) lg_sh[wave][(grp * 16 + 4 * j + i) * G + x] = sv[grp * 4 + i];
       }
     }
-    if (last_tile) {                          // the append itself, K part
-#pragma unroll
-      for (int grp = 0; grp < 2; ++grp)
-        if (row0 + grp * 16 + x == n - 1) {
-#pragma unroll
-          for (int sl = 0; sl < NS; ++sl)
-            *reinterpret_cast<uint4*>(cx.kbase + static_cast<int64_t>(n - 1) * ROWB + sl * 64 + j * 16) = kb[grp][sl];
-        }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    if (more) issue_k(kb, t + kWaves);
-    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 
     // Online softmax for head x: the tile's first row is live, so the maximum is finite.
     float tm = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
