@@ -18,6 +18,12 @@ What follows which passage of the paper (arXiv 2412.05896):
 * ``pooled_keys``       Alg. 2 step 4 (Pooling) as described with the attention
                         processing module in Sec. 4.1.
 * ``evict_compact``     Alg. 2 steps 5-7 (TopK, EvictByIndex on K and V).
+* ``window_attention_mass``  Alg. 2 steps 1-3 for the prefill phase: W_attn of the
+                        observation window (Eq. 2, causal), Select and Merge as
+                        in the attention processing module of Sec. 4.1 (Eq. 3).
+* ``prefill_select``, ``prefill_evict``  Alg. 2 steps 4-7 on a dense prompt:
+                        Pooling over the candidate vector, TopK, EvictByIndex as
+                        an ordered gather.
 * ``retention_ratio``   Eq. 4 (R_i), as a fraction.
 * ``allocate_budgets``  Alg. 1 (allocation list + wait list greedy) for the
                         two problems of Eq. 17 and Eq. 18.
@@ -38,6 +44,9 @@ __all__ = [
     "pooled_keys",
     "select_keep",
     "evict_compact",
+    "window_attention_mass",
+    "prefill_select",
+    "prefill_evict",
     "retention_ratio",
     "allocate_budgets",
     "OracleUnit",
@@ -178,6 +187,84 @@ def evict_compact(K, V, score, pos, budget: int, pool_size: int = 1, n_protect: 
         kept_idx[hslot] = mslot
     return (K[kept_idx].copy(), V[kept_idx].copy(), score[kept_idx].copy(),
             pos[kept_idx].copy(), kept_idx)
+
+
+# --------------------------------------------------------------------------
+# Alg. 2 as written, for the prefill phase (Sec. 4.1, attention processing)
+# --------------------------------------------------------------------------
+def window_attention_mass(q_win, K, scale=None) -> np.ndarray:
+    """Attention mass that the observation window puts on every prompt token.
+
+    q_win  [G, ows, d]  queries of the last ``ows`` prompt positions, for the G
+                        query heads that share this KV head
+    K      [t, d]       keys of the whole prompt (t >= ows)
+
+    Window row r is prompt position t - ows + r and, the attention being
+    causal, sees positions 0 .. t - ows + r; its softmax (Eq. 2) runs over
+    exactly those.  Returns w [t] in float64 with
+    w[j] = sum over g and r of W_attn[g][t - ows + r][j].  Its first t - ows
+    entries are the Select block merged over the window rows and the heads
+    (sum; the paper's mean is this divided by the constant ows); the last ows
+    entries are the mass the window puts on itself.  sum(w) = G * ows.
+    """
+    q_win = as_f64(q_win)
+    K = as_f64(K)
+    G, ows, d = q_win.shape
+    t = K.shape[0]
+    if ows < 1 or ows > t:
+        raise ValueError("need 1 <= ows <= t")
+    if scale is None:
+        scale = 1.0 / np.sqrt(float(d))
+    scale = float(scale)
+    w = np.zeros(t, dtype=np.float64)
+    for g in range(G):
+        for r in range(ows):
+            last = t - ows + r                # the row's own position
+            s = scale * (K[:last + 1] @ q_win[g, r])
+            e = np.exp(s - np.max(s))
+            w[:last + 1] += e / np.sum(e)
+    return w
+
+
+def prefill_select(w, ows: int, budget: int, pool_size: int = 1) -> np.ndarray:
+    """Prompt positions kept by Alg. 2 steps 4-5, ascending.
+
+    w [t] is the fp32 mass vector.  The candidates are the first t - ows
+    positions; their keys are the pooled candidate vector (``pooled_keys`` of
+    w[:t - ows]: nothing of the window enters a key).  The window's ows
+    positions are always kept and count towards the budget, so
+    min(budget, t) - ows candidates are kept: the largest keys, equal keys by
+    lower position.
+    """
+    w = np.asarray(w, dtype=np.float32)
+    t = w.shape[0]
+    kk = min(int(budget), t)
+    if kk < ows:
+        raise ValueError("the budget must cover the observation window")
+    tc = t - ows
+    key = pooled_keys(w[:tc], pool_size)
+    order = np.argsort(-key.astype(np.float64), kind="stable")
+    cand = np.sort(order[:kk - ows])
+    return np.concatenate([cand, np.arange(tc, t)]).astype(np.int64)
+
+
+def prefill_evict(q_win, K, V, budget: int, ows: int, pool_size: int = 1, scale=None, w=None):
+    """Alg. 2 on one unit of a dense prompt.
+
+    Returns (K', V', score', pos', w): the kept tokens in ascending position
+    order, score' = their fp32 mass (not pooled), pos' = their positions, and
+    the fp32 mass vector the selection was taken on.  If ``w`` is given (fp32),
+    the selection uses it instead of this function's own: a decision that
+    floating point takes must be taken on the same bits by both sides of a
+    parity test.
+    """
+    K = np.asarray(K)
+    V = np.asarray(V)
+    if w is None:
+        w = window_attention_mass(q_win, K, scale).astype(np.float32)
+    w = np.asarray(w, dtype=np.float32)
+    keep = prefill_select(w, ows, budget, pool_size)
+    return K[keep].copy(), V[keep].copy(), w[keep].copy(), keep.astype(np.int32), w
 
 
 # --------------------------------------------------------------------------
