@@ -11,6 +11,9 @@
  *                               attention probability into its importance
  *   - xkv_evict_compact         keep the top-budget tokens per (layer, KV
  *                               head) and compact K, V, score, pos in place
+ *   - xkv_prefill_evict         fill the cache from a dense prompt, keeping per
+ *                               (layer, KV head) the tokens the observation
+ *                               window attends to most
  *
  * Conventions for every call
  *   - Pointers marked HOST are ordinary host memory, pointers marked DEVICE
@@ -178,6 +181,47 @@ xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, int32_t laye
                              void* hip_stream);
 
 /*
+ * Eviction of the prefill phase for layers [layer_begin, layer_end): Alg. 2 as
+ * written (attention weights of the observation window, Select, Merge, Pooling,
+ * TopK, EvictByIndex; Eq. 3 and the attention processing module of Sec. 4.1),
+ * from a dense prompt into the ragged cache.
+ *
+ * For every (l, b, h), with tc = t - ows candidates and k' = min(budget, t):
+ *   window row r (prompt position tc + r) of each of the G query heads of KV
+ *     head h attends causally to positions 0 .. tc + r:
+ *     p_rj = softmax_j( scale * q_r . K_j ) over those positions;
+ *   w_j = sum over the G heads and the ows rows of p_rj (fp32), for all j < t:
+ *     the mean the paper merges with, times the constant ows;
+ *   key_j, j < tc = w_j, or for pool_size > 1 the fp32 sum, added left to right,
+ *     of w over the window of pool_size candidates centred on j (zeros outside
+ *     [0, tc): nothing of the observation window enters a key);
+ *   kept = the k' - ows candidates with the largest key (equal keys by lower
+ *     position) and the ows window positions;
+ *   slot s < k' of the stream receives the s-th kept position j, in ascending
+ *     order: its K and V rows, score = w_j (not pooled), pos = j.  len becomes
+ *     k'; what the region held before is overwritten.
+ *
+ *   q_win    DEVICE [layers][batch][n_q_heads][ows][head_dim], cache dtype
+ *   k_src, v_src  DEVICE [layers][batch][n_kv_heads][t][head_dim], cache dtype;
+ *            must not overlap the cache
+ *   t        prompt length, the same for every sequence; 1 <= ows <= t
+ *   budgets  HOST [layers][batch], each >= ows
+ *   softmax_scale  0 = 1/sqrt(head_dim)
+ *   w_out    DEVICE [layers][batch][n_kv_heads][t] fp32 or NULL: receives w
+ *   workspace  at least xkv_prefill_workspace_bytes
+ *
+ * Supported: ows * G <= 64.  Errors: INVALID_ARG, UNSUPPORTED, CAPACITY (k' > cap
+ * or the workspace is too small), DEVICE.  Bit-reproducible.
+ */
+xkv_status xkv_prefill_workspace_bytes(const xkv_cache* cache, int32_t max_layers_per_call,
+                                       int32_t t, int32_t ows, size_t* bytes_out);
+xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                             const void* q_win, const void* k_src, const void* v_src, int32_t t,
+                             int32_t ows, int32_t pool_size, const int32_t* budgets,
+                             float softmax_scale, float* w_out, void* workspace,
+                             size_t workspace_bytes, void* hip_stream);
+
+/*
  * Process-wide options, for tests and benchmarks.
  *   XKV_CFG_ATTEND_PATH  how xkv_decode_attend_score runs: 0 = the library's
  *       choice (default; at present the two kernels); 1 = a streaming kernel plus
@@ -189,10 +233,11 @@ enum { XKV_CFG_ATTEND_PATH = 1 };
 xkv_status xkv_configure(int32_t key, int64_t value);
 
 /*
- * Per-kernel timing for benchmarks.  While enabled, the two calls above record
+ * Per-kernel timing for benchmarks.  While enabled, the device calls above record
  * HIP events around their dominant kernel (the K/V streaming kernel of
- * xkv_decode_attend_score, kernel index 0, and the selection kernel of
- * xkv_evict_compact, kernel index 1) on the stream they launch on.
+ * xkv_decode_attend_score, kernel index 0, the selection kernel of
+ * xkv_evict_compact, kernel index 1, and the first K pass of xkv_prefill_evict,
+ * kernel index 2) on the stream they launch on.
  * xkv_profile_read waits for those events, returns the number of launches and
  * their summed duration in milliseconds since the last xkv_profile_enable(1),
  * and keeps them until the next enable.  Off by default; not for use under

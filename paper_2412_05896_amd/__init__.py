@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     xkv_configure,
     xkv_decode_attend_score,
     xkv_evict_compact,
+    xkv_prefill_evict,
+    xkv_prefill_workspace_bytes,
     xkv_probe_stream_read,
     xkv_profile_enable,
     xkv_profile_read,

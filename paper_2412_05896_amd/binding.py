@@ -16,7 +16,7 @@ XKV_ALLOC_TOTAL_SIZE, XKV_ALLOC_TARGET_RAVG = 0, 1
 EXPORTS = (
     "xkv_status_string", "xkv_allocate_budgets", "xkv_workspace_bytes",
     "xkv_decode_attend_score", "xkv_evict_compact", "xkv_profile_enable", "xkv_profile_read",
-    "xkv_configure", "xkv_probe_stream_read",
+    "xkv_configure", "xkv_probe_stream_read", "xkv_prefill_workspace_bytes", "xkv_prefill_evict",
 )
 XKV_CFG_ATTEND_PATH = 1
 
@@ -69,6 +69,13 @@ def load():
     lib.xkv_evict_compact.argtypes = [
         C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
         C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.xkv_prefill_workspace_bytes.restype = C.c_int32
+    lib.xkv_prefill_workspace_bytes.argtypes = [C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_int32,
+                                                C.POINTER(C.c_size_t)]
+    lib.xkv_prefill_evict.restype = C.c_int32
+    lib.xkv_prefill_evict.argtypes = [
+        C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+        C.c_int32, C.c_int32, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.xkv_configure.restype = C.c_int32
     lib.xkv_configure.argtypes = [C.c_int32, C.c_int64]
     lib.xkv_probe_stream_read.restype = C.c_int32
@@ -225,6 +232,26 @@ def xkv_evict_compact(cache: XkvCache, layer_begin, layer_end, budgets, workspac
         int(n_protect), _ptr(kept_idx_out), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     _check(st, "xkv_evict_compact")
+
+
+def xkv_prefill_workspace_bytes(cache: XkvCache, max_layers_per_call: int, t: int, ows: int) -> int:
+    out = C.c_size_t(0)
+    _check(load().xkv_prefill_workspace_bytes(C.byref(cache.struct), int(max_layers_per_call), int(t),
+                                              int(ows), C.byref(out)), "xkv_prefill_workspace_bytes")
+    return out.value
+
+
+def xkv_prefill_evict(cache: XkvCache, layer_begin, layer_end, q_win, k_src, v_src, t: int, ows: int,
+                      budgets, workspace, pool_size: int = 1, softmax_scale: float = 0.0, w_out=None,
+                      stream=None):
+    """q_win [layers, B, Hq, ows, d], k_src / v_src [layers, B, Hkv, t, d]: device tensors of the
+    cache dtype; budgets: int32 host array [layers, B]; w_out: device fp32 [layers, B, Hkv, t] or None."""
+    bud = None if budgets is None else np.ascontiguousarray(budgets, dtype=np.int32)
+    st = load().xkv_prefill_evict(
+        C.byref(cache.struct), int(layer_begin), int(layer_end), _ptr(q_win), _ptr(k_src), _ptr(v_src),
+        int(t), int(ows), int(pool_size), _ptr(bud), float(softmax_scale), _ptr(w_out), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    _check(st, "xkv_prefill_evict")
 
 
 def xkv_configure(key: int, value: int):

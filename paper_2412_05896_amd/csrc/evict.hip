@@ -21,13 +21,12 @@
 #include <limits>
 
 #include "device_util.h"
+#include "select_util.h"
 #include "xkv_internal.h"
 
 namespace xkv {
 namespace {
 
-constexpr int kSelThreads = 512;
-constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kMoveThreads = 256;
 constexpr int kFuseMax = 64;     // moves the selecting workgroup does itself
 constexpr int kSmallE = 8;       // evictions per stream found by repeated minimum search
@@ -85,17 +84,10 @@ __device__ __forceinline__ void move_row(const EvictParams& P, int64_t stream_sl
   }
 }
 
-// Number of set bits of a wave-wide vote below this lane.
-__device__ __forceinline__ int rank_in_wave(unsigned long long vote) {
-  return __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(vote >> 32),
-                                   __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(vote), 0));
-}
-
 __global__ __launch_bounds__(kSelThreads) void evict_select(const EvictParams P) {
-  __shared__ unsigned hist[256];
+  __shared__ RadixShared radix_sh;
   __shared__ int scan_sh[kSelWaves];
   __shared__ int cnt_sh[3][kSelWaves];
-  __shared__ unsigned sel_bin, sel_need;
   __shared__ int hole_l[kFuseMax], mover_l[kFuseMax];
   __shared__ unsigned long long best_sh[kSelWaves];
   __shared__ int ev_sh[kSmallE];
@@ -226,44 +218,8 @@ __global__ __launch_bounds__(kSelThreads) void evict_select(const EvictParams P)
   }
 
   // ---- radix select: the kk-th largest key -----------------------------------
-  unsigned prefix = 0, mask = 0, need = static_cast<unsigned>(kk);
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
-    for (int j = tid; j < n; j += kSelThreads) {
-      const unsigned key = key_at(j);
-      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
-    }
-    __syncthreads();
-    // Thread t < 256 takes bin 255 - t; an inclusive scan over t finds the bin
-    // in which the running count, from the top, reaches `need`.
-    unsigned cnt = 0, incl = 0;
-    if (tid < 256) {
-      cnt = hist[255 - tid];
-      incl = cnt;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const unsigned y = __shfl_up(incl, off);
-        if (lane >= off) incl += y;
-      }
-      if (lane == 63) scan_sh[wave] = static_cast<int>(incl);
-    }
-    __syncthreads();
-    if (tid < 256) {
-      for (int w = 0; w < wave; ++w) incl += static_cast<unsigned>(scan_sh[w]);
-      const unsigned before = incl - cnt;
-      if (before < need && need <= incl) {
-        sel_bin = 255u - static_cast<unsigned>(tid);
-        sel_need = need - before;
-      }
-    }
-    __syncthreads();
-    prefix |= sel_bin << shift;
-    mask |= 255u << shift;
-    need = sel_need;
-    __syncthreads();
-  }
-  const unsigned thr = prefix;              // keys above are kept, `need` of the equal ones too
+  unsigned thr, need;                       // keys above thr are kept, `need` of the equal ones too
+  radix_select(key_at, n, kk, radix_sh, thr, need);
 
   // ---- walk the slots in order ---------------------------------------------
   int carry_eq = 0, carry_h = 0, carry_m = 0;

@@ -1,0 +1,550 @@
+// xkv_prefill_evict: the eviction of the prefill phase, Alg. 2 of the paper as
+// written, from a dense prompt into the ragged cache.
+//
+//   step 1-3  W_attn of the observation window (Eq. 2, causal), Select, Merge:
+//             w[j] = sum over the G query heads and the ows window rows of the
+//             probability that row gives to prompt position j  (Eq. 3, Sec. 4.1)
+//   step 4    Pooling over the candidate vector w[0 .. t - ows)
+//   step 5    TopK: the budget - ows best candidates; the window is always kept
+//   step 6-7  EvictByIndex: the kept rows of K and V, in prompt order, are
+//             gathered into the stream's slots, with score = w and pos = position
+//
+// The window's queries against the prompt's keys are a dense contraction with
+// Nq = ows * G query rows per KV head: it runs on the matrix cores (bf16
+// 16x16x32 MFMA, or the fp32 16x16x4 MFMA for fp32 caches).  The softmax needs
+// each query row's maximum and sum before any probability is final, so K is read
+// twice: window_stats reduces (max, sum) per (stream, strip, query row),
+// window_merge folds the strips, window_mass recomputes the logits and writes w.
+// Storing the Nq logits per token instead would write and read 4 Nq bytes per
+// token next to a K row of 256.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <limits>
+#include <type_traits>
+
+#include "device_util.h"
+#include "select_util.h"
+#include "xkv_internal.h"
+
+namespace xkv {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kMaxNq = 64;                 // query rows (ows * G) per KV head
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+struct WindowParams {
+  const void* q_win;      // [pairs][Hq][ows][D]
+  const void* k_src;      // [pairs][Hkv][t][D]
+  float* stats;           // [streams][nstrips][nq_pad][2]  (max, sum) in the base-2 domain
+  float* fin;             // [streams][nq_pad][2]           (max, 1 / sum)
+  float* w;               // [streams][t]
+  float scale_log2e;
+  int32_t t, ows, group, n_kv_heads;
+  int32_t strip_rows, nstrips, nq_pad;
+};
+
+// One MFMA step over the 16 bytes that lane (j, x) holds of row x of A and of
+// column x of B, at byte offset 64 sl + 16 j of both: 8 bf16 channels, or 4 fp32
+// channels taken one at a time.  Which channels a step contracts does not
+// matter as long as both operands agree and all are visited.
+template <typename T>
+__device__ __forceinline__ floatx4 mma16(const uint4& a, const uint4& b, floatx4 c) {
+  if constexpr (std::is_same<T, BF16>::value) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  } else {
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+    return c;
+  }
+}
+
+// (max, sum) of two parts of a softmax row, base-2 domain; an empty part has max -inf.
+__device__ __forceinline__ void merge_ml(float& m, float& l, float m2, float l2) {
+  const float mn = fmaxf(m, m2);
+  const float ms = mn == -INFINITY ? 0.0f : mn;
+  l = l * fast_exp2(m - ms) + l2 * fast_exp2(m2 - ms);
+  m = mn;
+}
+
+// Logits of 16 prompt rows against the NB blocks of 16 query rows.
+//   kPhase 0  window_stats: per-strip (max, sum) of every query row
+//   kPhase 1  window_mass:  w[j] = sum over query rows of 2^(s - max) / sum
+// Workgroup = (stream, strip); its waves take the strip's groups of 16 rows in
+// turn.  Lane (j, x): operand loads are 16 bytes at offset 64 sl + 16 j of K row
+// x of the group and of query row 16 nb + x; the result has the logit of
+// (row 4 j + i, query row 16 nb + x) in register i.
+template <typename T, int D, int NB, int kPhase>
+__global__ __launch_bounds__(kThreads) void window_pass(const WindowParams P) {
+  constexpr int ROWB = D * T::kBytes;
+  constexpr int NSL = ROWB / 64;
+  __shared__ float ml_sh[kWaves][NB * 16][2];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int x = lane & 15, j = lane >> 4;
+  const int u = blockIdx.x / P.nstrips;             // stream = (pair, KV head)
+  const int s = blockIdx.x - u * P.nstrips;
+  const int pair = u / P.n_kv_heads;
+  const int h = u - pair * P.n_kv_heads;
+  const int t = P.t, ows = P.ows;
+  const int nq = ows * P.group;
+  const int r_begin = s * P.strip_rows;
+  const int r_end = min(t, r_begin + P.strip_rows);
+  const char* kbase = static_cast<const char*>(P.k_src) + static_cast<int64_t>(u) * t * ROWB;
+
+  // Query operands; query row qi = g * ows + r is head g, window row r.
+  uint4 qreg[NB][NSL];
+  int last_col[NB];                                 // last position the lane's query row sees
+  float m_fin[NB] = {}, inv_fin[NB] = {};
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int qi = nb * 16 + x;
+    const bool live = qi < nq;
+    const int g = live ? qi / ows : 0;
+    const int r = live ? qi - g * ows : 0;
+    last_col[nb] = live ? t - ows + r : -1;
+    const int64_t qrow = (static_cast<int64_t>(pair) * P.n_kv_heads * P.group + h * P.group + g) * ows + r;
+#pragma unroll
+    for (int sl = 0; sl < NSL; ++sl) {
+      uint4 raw = make_uint4(0, 0, 0, 0);
+      if (live) raw = *reinterpret_cast<const uint4*>(static_cast<const char*>(P.q_win) + qrow * ROWB + sl * 64 + j * 16);
+      qreg[nb][sl] = raw;
+    }
+    if (kPhase == 1) {
+      const float* f = P.fin + (static_cast<int64_t>(u) * P.nq_pad + qi) * 2;
+      m_fin[nb] = f[0];
+      inv_fin[nb] = f[1];
+    }
+  }
+
+  float m_run[NB], l_run[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) { m_run[nb] = -INFINITY; l_run[nb] = 0.0f; }
+
+  const int groups = (r_end - r_begin + 15) / 16;
+  for (int gi = wave; gi < groups; gi += kWaves) {
+    const int g0 = r_begin + gi * 16;
+    const int row = g0 + x;
+    const int rc = row < t ? row : t - 1;           // rows past the end repeat the last one, masked below
+    const char* src = kbase + static_cast<int64_t>(rc) * ROWB + j * 16;
+    uint4 kreg[NSL];
+#pragma unroll
+    for (int sl = 0; sl < NSL; ++sl) kreg[sl] = load_stream16(src + sl * 64);
+    float wsum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      floatx4 a = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int sl = 0; sl < NSL; ++sl) a = mma16<T>(kreg[sl], qreg[nb][sl], a);
+      if (kPhase == 0) {
+        float sv[4];
+        float gm = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          sv[i] = g0 + 4 * j + i <= last_col[nb] ? a[i] * P.scale_log2e : -INFINITY;   // causal
+          gm = fmaxf(gm, sv[i]);
+        }
+        const float m_new = fmaxf(m_run[nb], gm);
+        const float m_safe = m_new == -INFINITY ? 0.0f : m_new;
+        float l = l_run[nb] * fast_exp2(m_run[nb] - m_safe);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) l += fast_exp2(sv[i] - m_safe);
+        m_run[nb] = m_new;
+        l_run[nb] = l;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool seen = g0 + 4 * j + i <= last_col[nb];
+          wsum[i] += seen ? fast_exp2(a[i] * P.scale_log2e - m_fin[nb]) * inv_fin[nb] : 0.0f;
+        }
+      }
+    }
+    if (kPhase == 1) {
+      // Sum over the 16 query rows that share a lane row, then lane x < 4 of row j
+      // stores position g0 + 4 j + x.
+      float mine = 0.0f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float tot = group_sum<16>(wsum[i]);
+        if (x == i) mine = tot;
+      }
+      const int pos = g0 + 4 * j + x;
+      if (x < 4 && pos < t) P.w[static_cast<int64_t>(u) * t + pos] = mine;
+    }
+  }
+
+  if (kPhase == 0) {
+    // Fold the four row quarters of the wave, then the waves.
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+      for (int off = 16; off < 64; off <<= 1) {
+        const float m2 = __shfl_xor(m_run[nb], off);
+        const float l2 = __shfl_xor(l_run[nb], off);
+        merge_ml(m_run[nb], l_run[nb], m2, l2);
+      }
+      if (j == 0) {
+        ml_sh[wave][nb * 16 + x][0] = m_run[nb];
+        ml_sh[wave][nb * 16 + x][1] = l_run[nb];
+      }
+    }
+    __syncthreads();
+    if (tid < NB * 16) {
+      float m = ml_sh[0][tid][0], l = ml_sh[0][tid][1];
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w) merge_ml(m, l, ml_sh[w][tid][0], ml_sh[w][tid][1]);
+      float* st = P.stats + ((static_cast<int64_t>(u) * P.nstrips + s) * P.nq_pad + tid) * 2;
+      st[0] = m;
+      st[1] = l;
+    }
+  }
+}
+
+// One workgroup of 64 threads per stream: thread qi folds the strips of query row qi.
+__global__ __launch_bounds__(64) void window_merge(const WindowParams P) {
+  const int u = blockIdx.x;
+  const int qi = threadIdx.x;
+  if (qi >= P.nq_pad) return;
+  float m = -INFINITY, l = 0.0f;
+  for (int s = 0; s < P.nstrips; ++s) {
+    const float* st = P.stats + ((static_cast<int64_t>(u) * P.nstrips + s) * P.nq_pad + qi) * 2;
+    merge_ml(m, l, st[0], st[1]);
+  }
+  float* f = P.fin + (static_cast<int64_t>(u) * P.nq_pad + qi) * 2;
+  f[0] = m == -INFINITY ? 0.0f : m;           // padding rows: any finite value, they are never seen
+  f[1] = l > 0.0f ? 1.0f / l : 0.0f;
+}
+
+// ---- selection and gather ---------------------------------------------------
+struct GatherPair {
+  int64_t slot0;   // first slot of the region
+  int32_t cap;     // slots per stream
+  int32_t k;       // tokens kept: min(budget, t)
+};
+
+struct GatherParams {
+  const void* k_src;
+  const void* v_src;
+  void* k;
+  void* v;
+  float* score;
+  int32_t* pos;
+  const float* w;        // [streams][t]
+  uint32_t* keys;        // [streams][t] pooled keys (only used when pool > 1)
+  int32_t* idx;          // [streams][t] kept positions, ascending
+  int32_t t, ows, pool, n_kv_heads, row_bytes;
+  int32_t stream0;       // index of this launch's first stream within the call
+  GatherPair pairs[kMaxPairs];
+};
+
+// One workgroup per stream: pooled keys of the candidates, the threshold of
+// the top kc = k - ows of them by radix select, then a walk in prompt order that
+// numbers the kept candidates (equal keys: lower position first); the window's
+// positions follow.
+__global__ __launch_bounds__(kSelThreads) void prefill_select(const GatherParams P) {
+  __shared__ RadixShared radix_sh;
+  __shared__ int cnt_sh[2][kSelWaves];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int ul = blockIdx.x;                        // stream within the launch
+  const GatherPair pd = P.pairs[ul / P.n_kv_heads];
+  const int64_t u = static_cast<int64_t>(P.stream0) + ul;
+  const int t = P.t, tc = P.t - P.ows;
+  const int kc = pd.k - P.ows;                      // candidates to keep
+  const float* w = P.w + u * t;
+  uint32_t* keys = P.keys + u * t;
+  int32_t* idx = P.idx + u * t;
+
+  for (int r = tid; r < P.ows; r += kSelThreads) idx[kc + r] = tc + r;
+  if (kc >= tc) {                                   // every candidate stays
+    for (int jx = tid; jx < tc; jx += kSelThreads) idx[jx] = jx;
+    return;
+  }
+  if (kc == 0) return;
+
+  const bool pooled = P.pool > 1;
+  if (pooled) {
+    const int half = P.pool >> 1;
+    for (int jx = tid; jx < tc; jx += kSelThreads) {
+      // window sum, fp32, left to right, zeros outside the candidate vector
+      int c = jx - half;
+      float acc = (c >= 0 && c < tc) ? w[c] : 0.0f;
+      for (int q = 1; q < P.pool; ++q) {
+        ++c;
+        const float term = (c >= 0 && c < tc) ? w[c] : 0.0f;
+        acc = acc + term;
+      }
+      keys[jx] = __float_as_uint(acc);
+    }
+    __syncthreads();
+  }
+  auto key_at = [&](int jx) -> unsigned { return pooled ? keys[jx] : __float_as_uint(w[jx]); };
+
+  unsigned thr, need;
+  radix_select(key_at, tc, kc, radix_sh, thr, need);
+
+  int carry_eq = 0, carry_k = 0;
+  for (int base = 0; base < tc; base += kSelThreads) {
+    const int jx = base + tid;
+    const bool live = jx < tc;
+    const unsigned key = live ? key_at(jx) : 0u;
+    const bool is_eq = live && key == thr;
+    const unsigned long long v_eq = __ballot(is_eq);
+    if (lane == 0) cnt_sh[0][wave] = __popcll(v_eq);
+    __syncthreads();
+    int eq_rank = carry_eq + rank_in_wave(v_eq), eq_tot = 0;
+#pragma unroll
+    for (int wv = 0; wv < kSelWaves; ++wv) {
+      const int cw = cnt_sh[0][wv];
+      if (wv < wave) eq_rank += cw;
+      eq_tot += cw;
+    }
+    carry_eq += eq_tot;
+    const bool keep = live && (key > thr || (is_eq && eq_rank < static_cast<int>(need)));
+    const unsigned long long v_k = __ballot(keep);
+    if (lane == 0) cnt_sh[1][wave] = __popcll(v_k);
+    __syncthreads();
+    int k_rank = carry_k + rank_in_wave(v_k), k_tot = 0;
+#pragma unroll
+    for (int wv = 0; wv < kSelWaves; ++wv) {
+      const int cw = cnt_sh[1][wv];
+      if (wv < wave) k_rank += cw;
+      k_tot += cw;
+    }
+    carry_k += k_tot;
+    if (keep) idx[k_rank] = jx;
+    __syncthreads();                                // cnt_sh is reused by the next round
+  }
+}
+
+// EvictByIndex as a gather: workgroup (chunk, stream) copies kept tokens
+// [256 chunk, 256 chunk + 256) of the stream; a wave moves four rows of up to
+// 256 bytes per instruction.
+__global__ __launch_bounds__(kThreads) void prefill_gather(const GatherParams P) {
+  const int tid = threadIdx.x;
+  const int ul = blockIdx.y;
+  const int pl = ul / P.n_kv_heads;
+  const int h = ul - pl * P.n_kv_heads;
+  const GatherPair pd = P.pairs[pl];
+  const int first = blockIdx.x * kThreads;
+  if (first >= pd.k) return;
+  const int64_t u = static_cast<int64_t>(P.stream0) + ul;
+  const int t = P.t;
+  const int32_t* idx = P.idx + u * t;
+  const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
+  const int last = min(pd.k, first + kThreads);
+
+  const int sdst = first + tid;
+  if (sdst < last) {
+    const int src = idx[sdst];
+    P.score[stream_slot + sdst] = P.w[u * t + src];
+    P.pos[stream_slot + sdst] = src;
+  }
+  const int frags = P.row_bytes >> 4;               // 16-byte pieces per row: 8, 16 or 32
+  const int rows_per_pass = kThreads / frags;
+  const int fr = tid % frags;
+  const char* ks = static_cast<const char*>(P.k_src) + u * t * P.row_bytes;
+  const char* vs = static_cast<const char*>(P.v_src) + u * t * P.row_bytes;
+  char* kd = static_cast<char*>(P.k) + stream_slot * P.row_bytes;
+  char* vd = static_cast<char*>(P.v) + stream_slot * P.row_bytes;
+  for (int s = first + tid / frags; s < last; s += rows_per_pass) {
+    const int src = idx[s];
+    const int64_t so = static_cast<int64_t>(src) * P.row_bytes + fr * 16;
+    const int64_t dof = static_cast<int64_t>(s) * P.row_bytes + fr * 16;
+    const uint4 a = load_stream16(ks + so);
+    const uint4 b = load_stream16(vs + so);
+    *reinterpret_cast<uint4*>(kd + dof) = a;
+    *reinterpret_cast<uint4*>(vd + dof) = b;
+  }
+}
+
+using WindowFn = void (*)(const WindowParams);
+
+template <typename T, int D>
+bool pick_window_nb(int nb, WindowFn* stats, WindowFn* mass) {
+  switch (nb) {
+    case 1: *stats = window_pass<T, D, 1, 0>; *mass = window_pass<T, D, 1, 1>; return true;
+    case 2: *stats = window_pass<T, D, 2, 0>; *mass = window_pass<T, D, 2, 1>; return true;
+    case 3: *stats = window_pass<T, D, 3, 0>; *mass = window_pass<T, D, 3, 1>; return true;
+    case 4: *stats = window_pass<T, D, 4, 0>; *mass = window_pass<T, D, 4, 1>; return true;
+    default: return false;
+  }
+}
+
+bool pick_window(int dtype, int head_dim, int nb, WindowFn* stats, WindowFn* mass) {
+  if (dtype == XKV_F32 && head_dim == 64) return pick_window_nb<F32, 64>(nb, stats, mass);
+  if (dtype == XKV_F32 && head_dim == 128) return pick_window_nb<F32, 128>(nb, stats, mass);
+  if (dtype == XKV_BF16 && head_dim == 64) return pick_window_nb<BF16, 64>(nb, stats, mass);
+  if (dtype == XKV_BF16 && head_dim == 128) return pick_window_nb<BF16, 128>(nb, stats, mass);
+  return false;
+}
+
+// Workspace layout for `streams` streams of t tokens; every part starts on a
+// 256-byte boundary.  Returns the total; the offsets are in bytes.
+struct PrefillLayout { size_t stats, fin, w, keys, idx, total; };
+
+size_t round256(size_t b) { return (b + 255) / 256 * 256; }
+
+int prefill_strip_rows(int64_t streams, int t) {
+  int rows = 1024;
+  while (rows > 64 && streams * ceil_div(t, rows) < 2048) rows >>= 1;
+  return rows;
+}
+
+PrefillLayout prefill_layout(int64_t streams, int t, int nq_pad, bool own_w, bool pooled) {
+  // The strip length depends on the call; 64 rows is the shortest, so this bounds the statistics.
+  PrefillLayout L;
+  const int64_t max_strips = ceil_div(t, prefill_strip_rows(streams, t));
+  size_t off = 0;
+  L.stats = off; off += round256(static_cast<size_t>(streams) * max_strips * nq_pad * 2 * sizeof(float));
+  L.fin = off;   off += round256(static_cast<size_t>(streams) * nq_pad * 2 * sizeof(float));
+  L.w = off;     off += own_w ? round256(static_cast<size_t>(streams) * t * sizeof(float)) : 0;
+  L.keys = off;  off += pooled ? round256(static_cast<size_t>(streams) * t * sizeof(uint32_t)) : 0;
+  L.idx = off;   off += round256(static_cast<size_t>(streams) * t * sizeof(int32_t));
+  L.total = off;
+  return L;
+}
+
+xkv_status check_prefill_shape(const xkv_cache* cache, int32_t t, int32_t ows, int* nb_out) {
+  if (t < 1 || ows < 1 || ows > t) return XKV_ERR_INVALID_ARG;
+  const int nq = ows * (cache->n_q_heads / cache->n_kv_heads);
+  if (nq > kMaxNq) return XKV_ERR_UNSUPPORTED;
+  *nb_out = (nq + 15) / 16;
+  return XKV_OK;
+}
+
+}  // namespace
+}  // namespace xkv
+
+extern "C" xkv_status xkv_prefill_workspace_bytes(const xkv_cache* cache, int32_t max_layers_per_call,
+                                                  int32_t t, int32_t ows, size_t* bytes_out) {
+  using namespace xkv;
+  xkv_status st = check_cache(cache);
+  if (st != XKV_OK) return st;
+  if (bytes_out == nullptr || max_layers_per_call <= 0) return XKV_ERR_INVALID_ARG;
+  int nb = 0;
+  st = check_prefill_shape(cache, t, ows, &nb);
+  if (st != XKV_OK) return st;
+  const int64_t layers = std::min<int64_t>(max_layers_per_call, cache->n_layers);
+  // A call on fewer layers has fewer streams and may pick shorter strips: take
+  // the largest need over the possible layer counts' strip lengths.
+  size_t worst = 0;
+  for (int64_t l = 1; l <= layers; ++l) {
+    const int64_t streams = l * cache->batch * cache->n_kv_heads;
+    worst = std::max(worst, prefill_layout(streams, t, nb * 16, true, true).total);
+  }
+  *bytes_out = worst;
+  return XKV_OK;
+}
+
+extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                        const void* q_win, const void* k_src, const void* v_src,
+                                        int32_t t, int32_t ows, int32_t pool_size,
+                                        const int32_t* budgets, float softmax_scale, float* w_out,
+                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+  using namespace xkv;
+  xkv_status st = check_cache(cache);
+  if (st != XKV_OK) return st;
+  st = check_layers(cache, layer_begin, layer_end);
+  if (st != XKV_OK) return st;
+  if (q_win == nullptr || k_src == nullptr || v_src == nullptr || budgets == nullptr)
+    return XKV_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(q_win) & 15u) || (reinterpret_cast<uintptr_t>(k_src) & 15u) ||
+      (reinterpret_cast<uintptr_t>(v_src) & 15u) || (reinterpret_cast<uintptr_t>(w_out) & 3u))
+    return XKV_ERR_INVALID_ARG;
+  if (pool_size < 1 || (pool_size & 1) == 0) return XKV_ERR_INVALID_ARG;
+  if (!(softmax_scale >= 0.0f) || std::isinf(softmax_scale)) return XKV_ERR_INVALID_ARG;
+  int nb = 0;
+  st = check_prefill_shape(cache, t, ows, &nb);
+  if (st != XKV_OK) return st;
+
+  const int B = cache->batch, hkv = cache->n_kv_heads, D = cache->head_dim;
+  const int G = cache->n_q_heads / hkv;
+  const int64_t first = static_cast<int64_t>(layer_begin) * B;
+  const int64_t n_pairs = static_cast<int64_t>(layer_end - layer_begin) * B;
+  const int64_t streams = n_pairs * hkv;
+  int64_t max_k = 0;
+  for (int64_t i = 0; i < n_pairs; ++i) {
+    if (budgets[i] < ows) return XKV_ERR_INVALID_ARG;
+    const int64_t kk = std::min<int64_t>(budgets[i], t);
+    if (kk > cache->cap[first + i]) return XKV_ERR_CAPACITY;
+    max_k = std::max(max_k, kk);
+  }
+  WindowFn stats_fn = nullptr, mass_fn = nullptr;
+  if (!pick_window(cache->dtype, D, nb, &stats_fn, &mass_fn)) return XKV_ERR_UNSUPPORTED;
+  const int strip_rows = prefill_strip_rows(streams, t);
+  const int64_t nstrips = ceil_div(t, strip_rows);
+  if (streams * nstrips > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;
+  const bool pooled = pool_size > 1;
+  const PrefillLayout L = prefill_layout(streams, t, nb * 16, w_out == nullptr, pooled);
+  if (workspace == nullptr || L.total > workspace_bytes) return XKV_ERR_CAPACITY;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return XKV_ERR_INVALID_ARG;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  WindowParams W;
+  W.q_win = q_win;
+  W.k_src = k_src;
+  W.stats = reinterpret_cast<float*>(ws + L.stats);
+  W.fin = reinterpret_cast<float*>(ws + L.fin);
+  W.w = w_out != nullptr ? w_out : reinterpret_cast<float*>(ws + L.w);
+  const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt(static_cast<float>(D));
+  W.scale_log2e = scale * 1.44269504088896340736f;
+  W.t = t; W.ows = ows; W.group = G; W.n_kv_heads = hkv;
+  W.strip_rows = strip_rows;
+  W.nstrips = static_cast<int32_t>(nstrips);
+  W.nq_pad = nb * 16;
+  const unsigned grid = static_cast<unsigned>(streams * nstrips);
+  const int tok = profile_begin(2, stream);
+  hipLaunchKernelGGL(stats_fn, dim3(grid), dim3(kThreads), 0, stream, W);
+  profile_end(tok, stream);
+  if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+  hipLaunchKernelGGL(window_merge, dim3(static_cast<unsigned>(streams)), dim3(64), 0, stream, W);
+  if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+  hipLaunchKernelGGL(mass_fn, dim3(grid), dim3(kThreads), 0, stream, W);
+  if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+
+  GatherParams Gp;
+  Gp.k_src = k_src; Gp.v_src = v_src;
+  Gp.k = cache->k; Gp.v = cache->v; Gp.score = cache->score; Gp.pos = cache->pos;
+  Gp.w = W.w;
+  Gp.keys = reinterpret_cast<uint32_t*>(ws + L.keys);
+  Gp.idx = reinterpret_cast<int32_t*>(ws + L.idx);
+  Gp.t = t; Gp.ows = ows; Gp.pool = pool_size; Gp.n_kv_heads = hkv;
+  Gp.row_bytes = D * (cache->dtype == XKV_F32 ? 4 : 2);
+  for (int64_t g0 = 0; g0 < n_pairs; g0 += kMaxPairs) {
+    const int np = static_cast<int>(std::min<int64_t>(kMaxPairs, n_pairs - g0));
+    int64_t kmax = 0;
+    for (int i = 0; i < np; ++i) {
+      const int64_t idx = first + g0 + i;
+      GatherPair& pd = Gp.pairs[i];
+      pd.slot0 = cache->region_off[idx];
+      pd.cap = cache->cap[idx];
+      pd.k = static_cast<int32_t>(std::min<int64_t>(budgets[g0 + i], t));
+      kmax = std::max<int64_t>(kmax, pd.k);
+    }
+    Gp.stream0 = static_cast<int32_t>(g0 * hkv);
+    hipLaunchKernelGGL(prefill_select, dim3(static_cast<unsigned>(np * hkv)), dim3(kSelThreads), 0,
+                       stream, Gp);
+    if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+    hipLaunchKernelGGL(prefill_gather,
+                       dim3(static_cast<unsigned>(ceil_div(kmax, kThreads)), static_cast<unsigned>(np * hkv)),
+                       dim3(kThreads), 0, stream, Gp);
+    if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+  }
+  for (int64_t i = 0; i < n_pairs; ++i)
+    cache->len[first + i] = static_cast<int32_t>(std::min<int64_t>(budgets[i], t));
+  return XKV_OK;
+}

@@ -1,0 +1,151 @@
+"""GPU parity: xkv_prefill_evict against the oracle's Alg. 2, unit by unit.
+
+The attention mass w is compared within the floating-point tolerance; the
+selection is an integer decision taken on w, so the oracle repeats it on the
+device's own fp32 w and everything after it (kept positions, gathered rows,
+scores) must then match bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import xkv_oracle as orc
+from gpu_util import TOL, get_unit, rel_err, storage
+
+pytestmark = pytest.mark.gpu
+
+
+def run_prefill(xkv, dtype, d, Hq, Hkv, L, B, t, ows, ps, budgets, seed, scale=0.0, layer_range=None,
+                heavy=True, with_w=True, check_units=None):
+    budgets = np.asarray(budgets, np.int32).reshape(L, B)
+    caps = np.minimum(budgets, t) + 3
+    cache = xkv.XkvCache(L, B, Hq, Hkv, d, dtype, caps)
+    G = Hq // Hkv
+    l0, l1 = layer_range or (0, L)
+    nl = l1 - l0
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    tdt = cache.torch_dtype
+    k_src = torch.randn((nl, B, Hkv, t, d), generator=g)
+    if heavy:                                   # a few dominant tokens, as in the paper's heat map
+        hot = torch.randperm(t, generator=g)[:max(1, t // 50)]
+        k_src[:, :, :, hot, :] *= 3.0
+    k_src = k_src.to(tdt).cuda()
+    v_src = torch.randn((nl, B, Hkv, t, d), generator=g).to(tdt).cuda()
+    q_win = torch.randn((nl, B, Hq, ows, d), generator=g).to(tdt).cuda()
+    ws = torch.empty(xkv.xkv_prefill_workspace_bytes(cache, L, t, ows), dtype=torch.uint8, device="cuda")
+    w_out = torch.full((nl, B, Hkv, t), float("nan"), dtype=torch.float32, device="cuda") if with_w else None
+    cache.len[:] = 1                            # whatever was there is overwritten
+    xkv.xkv_prefill_evict(cache, l0, l1, q_win, k_src, v_src, t, ows, budgets[l0:l1], ws, pool_size=ps,
+                          softmax_scale=scale, w_out=w_out)
+    torch.cuda.synchronize()
+    w_dev = w_out.cpu().numpy() if with_w else None
+    worst = 0.0
+    for l in range(L):
+        for b in range(B):
+            if not (l0 <= l < l1):
+                assert cache.length(l, b) == 1
+                continue
+            kk = min(int(budgets[l, b]), t)
+            assert cache.length(l, b) == kk
+            for h in range(Hkv):
+                if check_units is not None and (l, b, h) not in check_units:
+                    continue
+                K = storage(k_src[l - l0, b, h])
+                V = storage(v_src[l - l0, b, h])
+                q = storage(q_win[l - l0, b, h * G:(h + 1) * G])
+                w_ref = orc.window_attention_mass(q, K, None if scale == 0.0 else scale)
+                K2, V2, s2, p2 = get_unit(cache, l, b, h)
+                if with_w:
+                    wd = w_dev[l - l0, b, h]
+                    assert np.all(np.isfinite(wd))
+                    worst = max(worst, rel_err(wd, w_ref))
+                    assert abs(float(wd.astype(np.float64).sum()) - G * ows) < 1e-3 * G * ows
+                    Ko, Vo, so, po, _ = orc.prefill_evict(q, K, V, kk, ows, ps, w=wd)
+                    assert np.array_equal(p2, po), f"kept positions differ in unit {(l, b, h)}"
+                    assert np.array_equal(K2, Ko) and np.array_equal(V2, Vo) and np.array_equal(s2, so)
+                else:
+                    # without w_out: what is unique is checked (the window, order, rows, scores
+                    # within tolerance) and the kept set is valid for scores within tolerance
+                    assert np.all(np.diff(p2) > 0) and np.array_equal(p2[kk - ows:], np.arange(t - ows, t))
+                    assert np.array_equal(K2, K[p2]) and np.array_equal(V2, V[p2])
+                    worst = max(worst, rel_err(s2, w_ref[p2]))
+    assert worst <= TOL[dtype], f"w rel err {worst}"
+    return worst
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128), ("bf16", 64), ("f32", 128)])
+@pytest.mark.parametrize("G", [1, 2, 4, 8])
+def test_shapes_groups_and_ragged_prompts(xkv, dtype, d, G):
+    """Prompt lengths that end inside a 16-row group; budgets from window-only to everything."""
+    Hkv = 2
+    for t, ows, ps in [(300, 8, 7), (257, 5, 1), (64, 8, 3)]:
+        if ows * G > 64:
+            ows = 64 // G
+        budgets = [[ows, t + 5], [t // 3, t - 1]]
+        print(f"case dtype={dtype} d={d} G={G} t={t} ows={ows} ps={ps}", flush=True)
+        run_prefill(xkv, dtype, d, Hkv * G, Hkv, 2, 2, t, ows, ps, budgets, seed=100 + G + t)
+
+
+def test_window_covers_whole_prompt_and_single_row_window(xkv):
+    run_prefill(xkv, "f32", 64, 2, 2, 1, 1, 8, 8, 1, [[8]], seed=1)        # no candidate at all
+    run_prefill(xkv, "bf16", 128, 4, 2, 1, 2, 500, 1, 7, [[100, 1]], seed=2)   # ows = 1: a decode query
+
+
+def test_ties_go_to_the_lower_position(xkv):
+    """Identical keys for all tokens: uniform attention, so candidates tie in
+    bulk and the kept ones must be the first."""
+    L, B, Hkv, t, ows, d = 1, 1, 1, 700, 4, 64
+    cache = xkv.XkvCache(L, B, 1, Hkv, d, "f32", [[300]])
+    k_src = torch.ones((1, 1, 1, t, d), device="cuda")
+    v_src = torch.randn((1, 1, 1, t, d), device="cuda")
+    q_win = torch.randn((1, 1, 1, ows, d), device="cuda")
+    ws = torch.empty(xkv.xkv_prefill_workspace_bytes(cache, 1, t, ows), dtype=torch.uint8, device="cuda")
+    xkv.xkv_prefill_evict(cache, 0, 1, q_win, k_src, v_src, t, ows, np.array([[200]], np.int32), ws)
+    torch.cuda.synchronize()
+    _, _, s2, p2 = get_unit(cache, 0, 0, 0)
+    assert p2.tolist() == list(range(196)) + list(range(696, 700))
+    expect = sum(1.0 / (t - ows + r + 1) for r in range(ows))
+    assert abs(float(s2[0]) - expect) < 1e-6
+
+
+def test_layer_subrange_scale_and_no_w_out(xkv):
+    run_prefill(xkv, "bf16", 128, 8, 2, 3, 2, 1000, 8, 7, [[100, 200], [300, 50], [999, 1000]], seed=5,
+                scale=0.11, layer_range=(1, 3))
+    run_prefill(xkv, "f32", 64, 4, 4, 2, 1, 400, 8, 7, [[100], [37]], seed=6, with_w=False)
+
+
+def test_long_prompt_many_strips_and_launch_groups(xkv):
+    """A 20k-token prompt (several strips per stream) and more regions than one launch describes."""
+    o = run_prefill(xkv, "bf16", 128, 8, 2, 1, 2, 20011, 8, 7, [[4000, 6001]], seed=7)
+    print("long prompt w rel err", o, flush=True)
+    r = np.random.default_rng(0)
+    budgets = r.integers(8, 300, size=(3, 50))
+    run_prefill(xkv, "bf16", 128, 2, 1, 3, 50, 333, 8, 7, budgets, seed=8)
+
+
+def test_decode_continues_on_a_prefilled_cache(xkv):
+    """The decode step runs on what the prefill call left: scores keep accumulating."""
+    L, B, Hq, Hkv, d, t, ows = 2, 1, 4, 2, 128, 600, 8
+    budgets = np.array([[150], [90]], np.int32)
+    cache = xkv.XkvCache(L, B, Hq, Hkv, d, "bf16", budgets + 2)
+    g = torch.Generator(device="cpu").manual_seed(3)
+    k_src = torch.randn((L, B, Hkv, t, d), generator=g).bfloat16().cuda()
+    v_src = torch.randn((L, B, Hkv, t, d), generator=g).bfloat16().cuda()
+    q_win = torch.randn((L, B, Hq, ows, d), generator=g).bfloat16().cuda()
+    ws = torch.empty(max(xkv.xkv_prefill_workspace_bytes(cache, L, t, ows), xkv.xkv_workspace_bytes(cache, L)),
+                     dtype=torch.uint8, device="cuda")
+    xkv.xkv_prefill_evict(cache, 0, L, q_win, k_src, v_src, t, ows, budgets, ws, pool_size=7)
+    torch.cuda.synchronize()
+    units = {(l, h): orc.OracleUnit(*get_unit(cache, l, 0, h)) for l in range(L) for h in range(Hkv)}
+    q = torch.randn((L, B, Hq, d), generator=g).bfloat16().cuda()
+    kn = torch.randn((L, B, Hkv, d), generator=g).bfloat16().cuda()
+    vn = torch.randn((L, B, Hkv, d), generator=g).bfloat16().cuda()
+    out = torch.empty((L, B, Hq, d), dtype=torch.float32, device="cuda")
+    xkv.xkv_decode_attend_score(cache, 0, L, q, kn, vn, np.array([t], np.int32), out, ws)
+    xkv.xkv_evict_compact(cache, 0, L, budgets, ws, n_protect=ows)
+    torch.cuda.synchronize()
+    for (l, h), u in units.items():
+        u.append(storage(kn[l, 0, h]), storage(vn[l, 0, h]), t)
+        o, _ = u.attend(storage(q[l, 0, h * 2:(h + 1) * 2]))
+        K2, V2, s2, p2 = get_unit(cache, l, 0, h)
+        assert rel_err(out[l, 0, h * 2:(h + 1) * 2].cpu().numpy(), o) <= TOL["bf16"]
+        assert len(p2) == budgets[l, 0] and t in p2.tolist()

@@ -170,6 +170,39 @@ def test_attend_and_evict_argument_errors_leave_state_untouched():
     assert keep["len"].tolist() == [10, 20, 30, 100]
 
 
+def test_prefill_argument_errors_leave_state_untouched():
+    lib = xkv.load()
+    s, keep = _fake_cache()                      # G = 2, caps 100
+    p = 0x2000
+    big = 1 << 30
+    bud = np.array([50, 50, 50, 50], np.int32)
+    out = C.c_size_t(0)
+    assert lib.xkv_prefill_workspace_bytes(C.byref(s), 2, 300, 8, C.byref(out)) == 0 and out.value > 0
+    assert lib.xkv_prefill_workspace_bytes(C.byref(s), 2, 300, 0, C.byref(out)) == -1    # empty window
+    assert lib.xkv_prefill_workspace_bytes(C.byref(s), 2, 4, 8, C.byref(out)) == -1      # window > prompt
+    assert lib.xkv_prefill_workspace_bytes(C.byref(s), 2, 300, 40, C.byref(out)) == -4   # ows * G > 64
+    call = lambda *a: lib.xkv_prefill_evict(C.byref(s), *a)
+    ok_args = lambda **o: [o.get("l0", 0), o.get("l1", 2), o.get("q", p), o.get("k", p), o.get("v", p),
+                           o.get("t", 300), o.get("ows", 8), o.get("ps", 7),
+                           o.get("bud", bud.ctypes.data), o.get("scale", 0.0), None, o.get("ws", p),
+                           o.get("wsb", big), None]
+    assert call(*ok_args(l1=3)) == -1
+    assert call(*ok_args(q=None)) == -1
+    assert call(*ok_args(k=0x2008)) == -1                                # misaligned source
+    assert call(*ok_args(ps=4)) == -1                                    # even pooling width
+    assert call(*ok_args(ows=0)) == -1
+    assert call(*ok_args(ows=40)) == -4
+    assert call(*ok_args(scale=-1.0)) == -1
+    assert call(*ok_args(bud=None)) == -1
+    small = np.array([50, 7, 50, 50], np.int32)                          # budget below the window
+    assert call(*ok_args(bud=small.ctypes.data)) == -1
+    large = np.array([50, 101, 50, 50], np.int32)                        # more than the stream holds
+    assert call(*ok_args(bud=large.ctypes.data)) == -3
+    assert call(*ok_args(wsb=64)) == -3
+    assert call(*ok_args(ws=0x2010)) == -1                               # misaligned workspace
+    assert keep["len"].tolist() == [10, 20, 30, 100]
+
+
 def test_workload_generators_are_seeded_and_consistent():
     w = wl.WORKLOADS["mistral_7b_gqa_b32"]
     b1 = wl.dirichlet_budgets(w.n_layers, 4, w.context, w.total_budget, w.seed)
