@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--no-roofline-pass", action="store_true")
     ap.add_argument("--keep-prompt-arena", action="store_true",
                     help="stay in the prompt-sized arena after the first eviction instead of moving to one sized by the budgets")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the prefill-phase eviction leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of 1 GiB x 10 (reference point for HBM byte counters)")
     return ap.parse_args()
@@ -238,7 +239,9 @@ def main():
                     traffic = float(line.split(":")[1])
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                    "kernel": "attend_strip (K/V streaming kernel of xkv_decode_attend_score)", "avg_launch_ms": total_ms / launches,
+                    "kernel": ("attend_strip" if w.group <= 2 else "attend_gqa") +
+                              " (K/V streaming kernel of xkv_decode_attend_score)",
+                    "avg_launch_ms": total_ms / launches,
                     "launches_per_step": launches_per_step, "algorithmic_bytes_per_launch": bytes_per_launch,
                     "evict_select_avg_ms": (sel_ms / sel_launches) if sel_launches else None}
 
@@ -261,6 +264,42 @@ def main():
             torch.cuda.synchronize()
             ceiling[tag] = nbytes * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e9
         del sink
+
+    # Prefill-phase eviction (Alg. 2 as written, ows = 8, ps = 7), layer by layer as a
+    # prefill would call it: one dense layer of the prompt at a time into a budget-sized cache.
+    prefill = None
+    if not args.no_prefill:
+        ows, ps = 8, 7
+        bud_p = np.maximum(budgets, ows)
+        caps_p = ((np.minimum(bud_p, w.context).astype(np.int64) + 7) // 8 * 8).astype(np.int32)
+        dst = xkv.XkvCache(L, B, w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, caps_p)
+        ws_p = torch.empty(xkv.xkv_prefill_workspace_bytes(dst, 1, w.context, ows), dtype=torch.uint8, device="cuda")
+        q_win, k_src, v_src = wl.dense_prompt_layer(w, 0, ows, device="cuda")
+        xkv.xkv_prefill_evict(dst, 0, 1, q_win, k_src, v_src, w.context, ows, bud_p[0:1], ws_p, pool_size=ps,
+                              stream=stream)                                 # warm-up
+        torch.cuda.synchronize()
+        xkv.xkv_profile_enable(True)
+        t0 = time.perf_counter()
+        for l in range(L):
+            xkv.xkv_prefill_evict(dst, l, l + 1, q_win, k_src, v_src, w.context, ows, bud_p[l:l + 1], ws_p,
+                                  pool_size=ps, stream=stream)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        n_stats, ms_stats = xkv.xkv_profile_read(2)
+        xkv.xkv_profile_enable(False)
+        row = w.head_dim * w.elem_bytes
+        kept = np.minimum(bud_p, w.context).astype(np.int64)
+        # K of the prompt read once, kept K and V rows read and written, score and pos written
+        pre_bytes = int(L * B * w.n_kv_heads * w.context * row + kept.sum() * w.n_kv_heads * (4 * row + 8))
+        k_pass_bytes = B * w.n_kv_heads * w.context * row
+        prefill = {"ows": ows, "pool_size": ps, "ms_per_layer": dt / L * 1e3, "layers_per_s": L / dt,
+                   "algorithmic_bytes_per_layer": pre_bytes / L, "hbm_gbs": pre_bytes / dt / 1e9,
+                   "hbm_frac": pre_bytes / dt / 1e9 / HBM_PEAK_GBS,
+                   "window_stats_avg_ms": ms_stats / n_stats if n_stats else None,
+                   "window_stats_hbm_frac": (k_pass_bytes / (ms_stats / n_stats * 1e-3) / 1e9 / HBM_PEAK_GBS)
+                   if n_stats else None,
+                   "note": "the same dense layer is the source for every layer; budgets differ per layer"}
+        del dst, ws_p, q_win, k_src, v_src
 
     cpu = None
     if args.cpu_seconds > 0:
@@ -293,7 +332,8 @@ def main():
         "step0_ms": step0_ms,
         "algorithmic_bytes_per_step": alg_bytes_timed / K,
         "step_hbm_gbs": step_gbs, "step_hbm_frac": step_gbs / HBM_PEAK_GBS,
-        "roofline": roofline, "stream_read_ceiling": ceiling, "cpu_baseline": cpu, "allocator": allocator,
+        "roofline": roofline, "stream_read_ceiling": ceiling, "prefill_evict": prefill, "cpu_baseline": cpu,
+        "allocator": allocator,
     }
     print(json.dumps(line))
 

@@ -210,8 +210,8 @@ xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, int32_t laye
  *   w_out    DEVICE [layers][batch][n_kv_heads][t] fp32 or NULL: receives w
  *   workspace  at least xkv_prefill_workspace_bytes
  *
- * Supported: ows * G <= 64.  Errors: INVALID_ARG, UNSUPPORTED, CAPACITY (k' > cap
- * or the workspace is too small), DEVICE.  Bit-reproducible.
+ * Supported: ows * G <= 64, t - ows <= 262144.  Errors: INVALID_ARG, UNSUPPORTED,
+ * CAPACITY (k' > cap or the workspace is too small), DEVICE.  Bit-reproducible.
  */
 xkv_status xkv_prefill_workspace_bytes(const xkv_cache* cache, int32_t max_layers_per_call,
                                        int32_t t, int32_t ows, size_t* bytes_out);

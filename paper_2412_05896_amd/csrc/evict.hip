@@ -27,6 +27,8 @@
 namespace xkv {
 namespace {
 
+constexpr int kSelThreads = 512;
+constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kMoveThreads = 256;
 constexpr int kFuseMax = 64;     // moves the selecting workgroup does itself
 constexpr int kSmallE = 8;       // evictions per stream found by repeated minimum search
@@ -219,7 +221,8 @@ __global__ __launch_bounds__(kSelThreads) void evict_select(const EvictParams P)
 
   // ---- radix select: the kk-th largest key -----------------------------------
   unsigned thr, need;                       // keys above thr are kept, `need` of the equal ones too
-  radix_select(key_at, n, kk, radix_sh, thr, need);
+  radix_select([&](auto&& fn) { for (int j = tid; j < n; j += kSelThreads) fn(key_at(j)); }, kk, radix_sh,
+               thr, need);
 
   // ---- walk the slots in order ---------------------------------------------
   int carry_eq = 0, carry_h = 0, carry_m = 0;

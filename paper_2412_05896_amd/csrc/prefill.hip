@@ -33,7 +33,11 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
+constexpr int kSelThreads = 1024;          // prefill_select: one large workgroup per stream
+constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kMaxNq = 64;                 // query rows (ows * G) per KV head
+constexpr int kMaxKeyRegs = 32;            // prefill_select: keys a thread keeps in registers
+constexpr int kMaxWalkRows = 256;          // prefill_select without register keys: rows of candidates
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -210,19 +214,30 @@ __global__ __launch_bounds__(kThreads) void window_pass(const WindowParams P) {
   }
 }
 
-// One workgroup of 64 threads per stream: thread qi folds the strips of query row qi.
-__global__ __launch_bounds__(64) void window_merge(const WindowParams P) {
+// One workgroup per stream: thread (slice, qi) folds every S-th strip of query
+// row qi, then the slices are folded in order.
+__global__ __launch_bounds__(kThreads) void window_merge(const WindowParams P) {
+  __shared__ float part_sh[kThreads][2];
   const int u = blockIdx.x;
-  const int qi = threadIdx.x;
-  if (qi >= P.nq_pad) return;
+  const int tid = threadIdx.x;
+  const int nq = P.nq_pad;                    // 16, 32, 48 or 64
+  const int S = kThreads / nq;
+  const int qi = tid % nq, slice = tid / nq;
   float m = -INFINITY, l = 0.0f;
-  for (int s = 0; s < P.nstrips; ++s) {
-    const float* st = P.stats + ((static_cast<int64_t>(u) * P.nstrips + s) * P.nq_pad + qi) * 2;
-    merge_ml(m, l, st[0], st[1]);
+  if (slice < S)
+    for (int s = slice; s < P.nstrips; s += S) {
+      const float* st = P.stats + ((static_cast<int64_t>(u) * P.nstrips + s) * nq + qi) * 2;
+      merge_ml(m, l, st[0], st[1]);
+    }
+  part_sh[tid][0] = m;
+  part_sh[tid][1] = l;
+  __syncthreads();
+  if (tid < nq) {
+    for (int sl = 1; sl < S; ++sl) merge_ml(m, l, part_sh[sl * nq + tid][0], part_sh[sl * nq + tid][1]);
+    float* f = P.fin + (static_cast<int64_t>(u) * nq + tid) * 2;
+    f[0] = m == -INFINITY ? 0.0f : m;         // padding rows: any finite value, they are never seen
+    f[1] = l > 0.0f ? 1.0f / l : 0.0f;
   }
-  float* f = P.fin + (static_cast<int64_t>(u) * P.nq_pad + qi) * 2;
-  f[0] = m == -INFINITY ? 0.0f : m;           // padding rows: any finite value, they are never seen
-  f[1] = l > 0.0f ? 1.0f / l : 0.0f;
 }
 
 // ---- selection and gather ---------------------------------------------------
@@ -250,10 +265,16 @@ struct GatherParams {
 // One workgroup per stream: pooled keys of the candidates, the threshold of
 // the top kc = k - ows of them by radix select, then a walk in prompt order that
 // numbers the kept candidates (equal keys: lower position first); the window's
-// positions follow.
+// positions follow.  Thread `tid` owns candidates tid, tid + 1024, ...; with
+// KPT > 0 it keeps their keys in KPT registers (tc <= 1024 KPT), otherwise they
+// go through the workspace.
+template <int KPT>
 __global__ __launch_bounds__(kSelThreads) void prefill_select(const GatherParams P) {
+  extern __shared__ float wpad_sh[];                // staged candidates, see below
   __shared__ RadixShared radix_sh;
-  __shared__ int cnt_sh[2][kSelWaves];
+  constexpr int kMaxRows = KPT > 0 ? KPT : kMaxWalkRows;
+  __shared__ int eq_sh[kMaxRows * kSelWaves], keep_sh[kMaxRows * kSelWaves];
+  __shared__ int tot_sh[kSelWaves + 1];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -274,59 +295,100 @@ __global__ __launch_bounds__(kSelThreads) void prefill_select(const GatherParams
   }
   if (kc == 0) return;
 
-  const bool pooled = P.pool > 1;
-  if (pooled) {
-    const int half = P.pool >> 1;
-    for (int jx = tid; jx < tc; jx += kSelThreads) {
-      // window sum, fp32, left to right, zeros outside the candidate vector
+  // With pooling and register-resident keys the candidate vector is staged in
+  // LDS (zeros on both sides), so that the window sums read it from there.
+  const int half = P.pool >> 1;
+  const bool staged = KPT > 0 && P.pool > 1;
+  if (staged) {
+    for (int c = tid; c < tc + 2 * half; c += kSelThreads)
+      wpad_sh[c] = (c >= half && c < tc + half) ? w[c - half] : 0.0f;
+    __syncthreads();
+  }
+  auto make_key = [&](int jx) -> unsigned {
+    if (P.pool == 1) return __float_as_uint(w[jx]);
+    // window sum, fp32, left to right, zeros outside the candidate vector
+    float acc;
+    if (staged) {
+      acc = wpad_sh[jx];                              // candidate jx - half
+      for (int q = 1; q < P.pool; ++q) acc = acc + wpad_sh[jx + q];
+    } else {
       int c = jx - half;
-      float acc = (c >= 0 && c < tc) ? w[c] : 0.0f;
+      acc = (c >= 0 && c < tc) ? w[c] : 0.0f;
       for (int q = 1; q < P.pool; ++q) {
         ++c;
         const float term = (c >= 0 && c < tc) ? w[c] : 0.0f;
         acc = acc + term;
       }
-      keys[jx] = __float_as_uint(acc);
     }
+    return __float_as_uint(acc);
+  };
+  constexpr int NK = KPT > 0 ? KPT : 1;
+  unsigned kreg[NK];
+  const bool stored = KPT == 0 && P.pool > 1;
+  if (KPT > 0) {
+#pragma unroll
+    for (int i = 0; i < NK; ++i) {
+      const int jx = i * kSelThreads + tid;
+      kreg[i] = jx < tc ? make_key(jx) : 0u;
+    }
+  } else if (stored) {
+    for (int jx = tid; jx < tc; jx += kSelThreads) keys[jx] = make_key(jx);
     __syncthreads();
   }
-  auto key_at = [&](int jx) -> unsigned { return pooled ? keys[jx] : __float_as_uint(w[jx]); };
+  auto key_at = [&](int jx) -> unsigned { return stored ? keys[jx] : __float_as_uint(w[jx]); };
+  auto for_each_key = [&](auto&& fn) {
+    if (KPT > 0) {
+#pragma unroll
+      for (int i = 0; i < NK; ++i)
+        if (i * kSelThreads + tid < tc) fn(kreg[i]);
+    } else {
+      for (int jx = tid; jx < tc; jx += kSelThreads) fn(key_at(jx));
+    }
+  };
 
   unsigned thr, need;
-  radix_select(key_at, tc, kc, radix_sh, thr, need);
+  radix_select(for_each_key, kc, radix_sh, thr, need);
 
-  int carry_eq = 0, carry_k = 0;
-  for (int base = 0; base < tc; base += kSelThreads) {
-    const int jx = base + tid;
-    const bool live = jx < tc;
-    const unsigned key = live ? key_at(jx) : 0u;
+  // Walk in prompt order.  Row i of the walk is candidates 1024 i .. 1024 i + 1023,
+  // one per thread; (row, wave) cells hold first the number of keys equal to the
+  // threshold, then the number of kept keys, and a prefix sum over the cells
+  // gives every wave of every row its starting rank.
+  const int rows = (tc + kSelThreads - 1) / kSelThreads;
+  auto for_each_row = [&](auto&& fn) {
+    if (KPT > 0) {
+#pragma unroll
+      for (int i = 0; i < NK; ++i)
+        if (i < rows) fn(i, kreg[i]);
+    } else {
+      for (int i = 0; i < rows; ++i) {
+        const int jx = i * kSelThreads + tid;
+        fn(i, jx < tc ? key_at(jx) : 0u);
+      }
+    }
+  };
+  for_each_row([&](int i, unsigned key) {
+    const bool is_eq = i * kSelThreads + tid < tc && key == thr;
+    const unsigned long long v_eq = __ballot(is_eq);
+    if (lane == 0) eq_sh[i * kSelWaves + wave] = __popcll(v_eq);
+  });
+  block_exclusive_scan<kSelThreads>(eq_sh, rows * kSelWaves, tot_sh);
+  auto kept = [&](int i, unsigned key) -> bool {
+    const bool live = i * kSelThreads + tid < tc;
     const bool is_eq = live && key == thr;
     const unsigned long long v_eq = __ballot(is_eq);
-    if (lane == 0) cnt_sh[0][wave] = __popcll(v_eq);
-    __syncthreads();
-    int eq_rank = carry_eq + rank_in_wave(v_eq), eq_tot = 0;
-#pragma unroll
-    for (int wv = 0; wv < kSelWaves; ++wv) {
-      const int cw = cnt_sh[0][wv];
-      if (wv < wave) eq_rank += cw;
-      eq_tot += cw;
-    }
-    carry_eq += eq_tot;
-    const bool keep = live && (key > thr || (is_eq && eq_rank < static_cast<int>(need)));
+    const int eq_rank = eq_sh[i * kSelWaves + wave] + rank_in_wave(v_eq);
+    return live && (key > thr || (is_eq && eq_rank < static_cast<int>(need)));
+  };
+  for_each_row([&](int i, unsigned key) {
+    const unsigned long long v_k = __ballot(kept(i, key));
+    if (lane == 0) keep_sh[i * kSelWaves + wave] = __popcll(v_k);
+  });
+  block_exclusive_scan<kSelThreads>(keep_sh, rows * kSelWaves, tot_sh);
+  for_each_row([&](int i, unsigned key) {
+    const bool keep = kept(i, key);
     const unsigned long long v_k = __ballot(keep);
-    if (lane == 0) cnt_sh[1][wave] = __popcll(v_k);
-    __syncthreads();
-    int k_rank = carry_k + rank_in_wave(v_k), k_tot = 0;
-#pragma unroll
-    for (int wv = 0; wv < kSelWaves; ++wv) {
-      const int cw = cnt_sh[1][wv];
-      if (wv < wave) k_rank += cw;
-      k_tot += cw;
-    }
-    carry_k += k_tot;
-    if (keep) idx[k_rank] = jx;
-    __syncthreads();                                // cnt_sh is reused by the next round
-  }
+    if (keep) idx[keep_sh[i * kSelWaves + wave] + rank_in_wave(v_k)] = i * kSelThreads + tid;
+  });
 }
 
 // EvictByIndex as a gather: workgroup (chunk, stream) copies kept tokens
@@ -419,6 +481,7 @@ PrefillLayout prefill_layout(int64_t streams, int t, int nq_pad, bool own_w, boo
 
 xkv_status check_prefill_shape(const xkv_cache* cache, int32_t t, int32_t ows, int* nb_out) {
   if (t < 1 || ows < 1 || ows > t) return XKV_ERR_INVALID_ARG;
+  if (t - ows > kMaxWalkRows * kSelThreads) return XKV_ERR_UNSUPPORTED;
   const int nq = ows * (cache->n_q_heads / cache->n_kv_heads);
   if (nq > kMaxNq) return XKV_ERR_UNSUPPORTED;
   *nb_out = (nq + 15) / 16;
@@ -511,7 +574,7 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
   hipLaunchKernelGGL(stats_fn, dim3(grid), dim3(kThreads), 0, stream, W);
   profile_end(tok, stream);
   if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
-  hipLaunchKernelGGL(window_merge, dim3(static_cast<unsigned>(streams)), dim3(64), 0, stream, W);
+  hipLaunchKernelGGL(window_merge, dim3(static_cast<unsigned>(streams)), dim3(kThreads), 0, stream, W);
   if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
   hipLaunchKernelGGL(mass_fn, dim3(grid), dim3(kThreads), 0, stream, W);
   if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
@@ -536,7 +599,21 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
       kmax = std::max<int64_t>(kmax, pd.k);
     }
     Gp.stream0 = static_cast<int32_t>(g0 * hkv);
-    hipLaunchKernelGGL(prefill_select, dim3(static_cast<unsigned>(np * hkv)), dim3(kSelThreads), 0,
+    const int tc = t - ows;
+    auto select_fn = tc <= 8 * kSelThreads ? prefill_select<8>
+                     : tc <= kMaxKeyRegs * kSelThreads ? prefill_select<kMaxKeyRegs> : prefill_select<0>;
+    size_t select_lds = 0;
+    if (pooled && tc <= kMaxKeyRegs * kSelThreads) {
+      select_lds = static_cast<size_t>(tc + pool_size) * sizeof(float);
+      if (select_lds > 48 * 1024 &&
+          hipFuncSetAttribute(reinterpret_cast<const void*>(select_fn),
+                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                              static_cast<int>(select_lds)) != hipSuccess) {
+        (void)hipGetLastError();
+        return XKV_ERR_DEVICE;
+      }
+    }
+    hipLaunchKernelGGL(select_fn, dim3(static_cast<unsigned>(np * hkv)), dim3(kSelThreads), select_lds,
                        stream, Gp);
     if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     hipLaunchKernelGGL(prefill_gather,

@@ -224,6 +224,27 @@ def fill_prompt_cache(w: Workload, k_arena: torch.Tensor, v_arena: torch.Tensor,
                     k_arena[s0 + hp] = rows.to(k_arena.dtype)
 
 
+def dense_prompt_layer(w: Workload, layer: int, ows: int, device="cpu"):
+    """One layer of a dense prompt for the prefill-phase eviction: k_src, v_src
+    [1, B, Hkv, T, d] ~ N(0,1) in the storage type with the workload's
+    heavy-hitter keys scaled, and q_win [1, B, Hq, ows, d] ~ N(0,1)."""
+    dev = torch.device(device)
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.seed + 104729 * (layer + 1))
+    T, d = w.context, w.head_dim
+    k = torch.randn((1, w.batch, w.n_kv_heads, T, d), generator=g, dtype=torch.float32, device=dev)
+    for b in range(w.batch):
+        hp = heavy_positions(w, b)
+        if hp:
+            idx = torch.tensor(sorted(hp), dtype=torch.long, device=dev)
+            sc = torch.tensor([hp[p] for p in sorted(hp)], dtype=torch.float32, device=dev)
+            k[0, b, :, idx, :] *= sc[None, :, None]
+    k = k.to(w.torch_dtype())
+    v = torch.randn((1, w.batch, w.n_kv_heads, T, d), generator=g, dtype=torch.float32, device=dev).to(w.torch_dtype())
+    q = torch.randn((1, w.batch, w.n_q_heads, ows, d), generator=g, dtype=torch.float32, device=dev).to(w.torch_dtype())
+    return q, k, v
+
+
 def decode_inputs(w: Workload, steps: Optional[int] = None, device="cpu"):
     """q [steps, L, B, Hq, d], k_new and v_new [steps, L, B, Hkv, d] ~ N(0,1) in
     the storage type, and pos_new int32 [steps, B] = context + step."""
