@@ -88,6 +88,33 @@ xkv_status xkv_allocate_budgets(int32_t n_layers, const float* const* w, const i
                                 int64_t* budgets_out, double* ravg_out);
 
 /*
+ * Device form of the allocation for XKV_ALLOC_TOTAL_SIZE (Alg. 1, Eq. 17), for
+ * score vectors that already live on the device, such as the w_out of
+ * xkv_window_importance: same result as xkv_allocate_budgets whenever no two
+ * layers have contributions that agree to the last bit at the threshold (the
+ * layer sums are added in a different order, which can move such a tie); the
+ * retained importance R_avg of the result is the optimum in every case.
+ *
+ *   w             DEVICE fp32: layer l's len values start at w + l * layer_stride
+ *                 (layer_stride >= len); non-negative and finite (not checked:
+ *                 the call does not read w on the host)
+ *   min_budget, max_budget, budgets_out, ravg_out   HOST, as above
+ *   workspace     DEVICE, 256-byte aligned, xkv_allocate_device_workspace_bytes
+ *
+ * Unlike the other device calls this one returns host results: it waits for
+ * hip_stream (once per round of bound fixing, usually one or two rounds).
+ * Supported: n_layers <= 256.  Errors: INVALID_ARG, INFEASIBLE, UNSUPPORTED,
+ * CAPACITY, DEVICE.
+ */
+xkv_status xkv_allocate_device_workspace_bytes(int32_t n_layers, int64_t len, size_t* bytes_out);
+xkv_status xkv_allocate_budgets_device(int32_t n_layers, const float* w, int64_t len,
+                                       int64_t layer_stride, int64_t total_size,
+                                       const int64_t* min_budget,
+                                       const int64_t* max_budget, int64_t* budgets_out,
+                                       double* ravg_out, void* workspace, size_t workspace_bytes,
+                                       void* hip_stream);
+
+/*
  * The ragged cache.  Region (l, b) holds n_kv_heads streams, one per KV head,
  * each with room for cap[l*batch+b] tokens ("slots") of which the first
  * len[l*batch+b] are live; all heads of a region have the same length.
@@ -220,6 +247,27 @@ xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, int32_t laye
                              int32_t ows, int32_t pool_size, const int32_t* budgets,
                              float softmax_scale, float* w_out, void* workspace,
                              size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The attention processing module of the mini-prefill (Sec. 4.1, Eq. 3) for
+ * layers [layer_begin, layer_end) of a cache geometry: the attention score
+ * distribution vector of every (layer, sequence), ready for the allocator.
+ *
+ *   w_out[l][b][j], j < t - ows  =  pooled_j( sum over the KV heads h of w^h ),
+ * with w^h the window mass of xkv_prefill_evict for stream (l, b, h); the heads
+ * are added in index order in fp32, and pooling is the same left-to-right window
+ * sum over the candidate vector (zeros outside).  Only K is read; the cache's
+ * arenas are not touched (only its shape fields are used).
+ *
+ *   q_win, k_src, t, ows, pool_size, softmax_scale   as for xkv_prefill_evict
+ *   w_out      DEVICE [layers][batch][t - ows] fp32
+ *   workspace  at least xkv_prefill_workspace_bytes
+ * Errors: INVALID_ARG, UNSUPPORTED, CAPACITY, DEVICE.
+ */
+xkv_status xkv_window_importance(const xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                 const void* q_win, const void* k_src, int32_t t, int32_t ows,
+                                 int32_t pool_size, float softmax_scale, float* w_out,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Process-wide options, for tests and benchmarks.

@@ -21,6 +21,9 @@ What follows which passage of the paper (arXiv 2412.05896):
 * ``window_attention_mass``  Alg. 2 steps 1-3 for the prefill phase: W_attn of the
                         observation window (Eq. 2, causal), Select and Merge as
                         in the attention processing module of Sec. 4.1 (Eq. 3).
+* ``window_importance``  the attention score distribution vector of a layer as
+                        the mini-prefill hands it to the allocator (Sec. 4.1):
+                        masses merged over the KV heads, then pooled.
 * ``prefill_select``, ``prefill_evict``  Alg. 2 steps 4-7 on a dense prompt:
                         Pooling over the candidate vector, TopK, EvictByIndex as
                         an ordered gather.
@@ -45,6 +48,7 @@ __all__ = [
     "select_keep",
     "evict_compact",
     "window_attention_mass",
+    "window_importance",
     "prefill_select",
     "prefill_evict",
     "retention_ratio",
@@ -224,6 +228,33 @@ def window_attention_mass(q_win, K, scale=None) -> np.ndarray:
             e = np.exp(s - np.max(s))
             w[:last + 1] += e / np.sum(e)
     return w
+
+
+def window_importance(q_win, K, pool_size: int = 1, scale=None) -> np.ndarray:
+    """Attention score distribution vector of one (layer, sequence).
+
+    q_win [Hkv, G, ows, d], K [Hkv, t, d].  The candidates' masses
+    (``window_attention_mass``, first t - ows entries) are added over the KV
+    heads, then pooled: window sum of width ``pool_size``, stride 1, zeros
+    outside the candidate vector.  float64 throughout; no decision is taken
+    here, so nothing needs a fixed precision.
+    """
+    q_win = np.asarray(q_win)
+    K = np.asarray(K)
+    Hkv, G, ows, d = q_win.shape
+    t = K.shape[1]
+    tc = t - ows
+    total = np.zeros(tc, dtype=np.float64)
+    for h in range(Hkv):
+        total += window_attention_mass(q_win[h], K[h], scale)[:tc]
+    half = pool_size // 2
+    if pool_size < 1 or pool_size % 2 == 0:
+        raise ValueError("pool_size must be odd and >= 1")
+    out = np.zeros(tc, dtype=np.float64)
+    for j in range(tc):
+        lo, hi = max(0, j - half), min(tc, j + half + 1)
+        out[j] = np.sum(total[lo:hi])
+    return out
 
 
 def prefill_select(w, ows: int, budget: int, pool_size: int = 1) -> np.ndarray:

@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     load,
     status_string,
     xkv_allocate_budgets,
+    xkv_allocate_budgets_device,
+    xkv_allocate_device_workspace_bytes,
     xkv_configure,
     xkv_decode_attend_score,
     xkv_evict_compact,
@@ -22,5 +24,6 @@ from .binding import (  # noqa: F401
     xkv_probe_stream_read,
     xkv_profile_enable,
     xkv_profile_read,
+    xkv_window_importance,
     xkv_workspace_bytes,
 )

@@ -17,6 +17,7 @@ EXPORTS = (
     "xkv_status_string", "xkv_allocate_budgets", "xkv_workspace_bytes",
     "xkv_decode_attend_score", "xkv_evict_compact", "xkv_profile_enable", "xkv_profile_read",
     "xkv_configure", "xkv_probe_stream_read", "xkv_prefill_workspace_bytes", "xkv_prefill_evict",
+    "xkv_window_importance", "xkv_allocate_device_workspace_bytes", "xkv_allocate_budgets_device",
 )
 XKV_CFG_ATTEND_PATH = 1
 
@@ -76,6 +77,16 @@ def load():
     lib.xkv_prefill_evict.argtypes = [
         C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
         C.c_int32, C.c_int32, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.xkv_window_importance.restype = C.c_int32
+    lib.xkv_window_importance.argtypes = [
+        C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+        C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.xkv_allocate_device_workspace_bytes.restype = C.c_int32
+    lib.xkv_allocate_device_workspace_bytes.argtypes = [C.c_int32, C.c_int64, C.POINTER(C.c_size_t)]
+    lib.xkv_allocate_budgets_device.restype = C.c_int32
+    lib.xkv_allocate_budgets_device.argtypes = [
+        C.c_int32, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+        C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.xkv_configure.restype = C.c_int32
     lib.xkv_configure.argtypes = [C.c_int32, C.c_int64]
     lib.xkv_probe_stream_read.restype = C.c_int32
@@ -252,6 +263,39 @@ def xkv_prefill_evict(cache: XkvCache, layer_begin, layer_end, q_win, k_src, v_s
         int(t), int(ows), int(pool_size), _ptr(bud), float(softmax_scale), _ptr(w_out), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     _check(st, "xkv_prefill_evict")
+
+
+def xkv_window_importance(cache: XkvCache, layer_begin, layer_end, q_win, k_src, t: int, ows: int, w_out,
+                          workspace, pool_size: int = 1, softmax_scale: float = 0.0, stream=None):
+    """w_out: device fp32 [layers, B, t - ows], the per-(layer, sequence) score distribution vectors."""
+    st = load().xkv_window_importance(
+        C.byref(cache.struct), int(layer_begin), int(layer_end), _ptr(q_win), _ptr(k_src), int(t), int(ows),
+        int(pool_size), float(softmax_scale), _ptr(w_out), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    _check(st, "xkv_window_importance")
+
+
+def xkv_allocate_device_workspace_bytes(n_layers: int, length: int) -> int:
+    out = C.c_size_t(0)
+    _check(load().xkv_allocate_device_workspace_bytes(int(n_layers), int(length), C.byref(out)),
+           "xkv_allocate_device_workspace_bytes")
+    return out.value
+
+
+def xkv_allocate_budgets_device(w, n_layers: int, length: int, layer_stride: int, total_size: int, workspace,
+                                min_budget=None, max_budget=None, stream=None):
+    """w: device fp32 tensor; layer l's `length` values start at element l * layer_stride of it.
+    Returns (budgets int64 [n_layers], R_avg).  Waits for the stream."""
+    lo = None if min_budget is None else np.ascontiguousarray(min_budget, dtype=np.int64)
+    hi = None if max_budget is None else np.ascontiguousarray(max_budget, dtype=np.int64)
+    out = np.zeros(int(n_layers), dtype=np.int64)
+    ravg = C.c_double(0.0)
+    st = load().xkv_allocate_budgets_device(
+        int(n_layers), _ptr(w), int(length), int(layer_stride), int(total_size), _ptr(lo), _ptr(hi),
+        out.ctypes.data, C.byref(ravg), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    _check(st, "xkv_allocate_budgets_device")
+    return out, ravg.value
 
 
 def xkv_configure(key: int, value: int):

@@ -136,14 +136,15 @@ __global__ __launch_bounds__(kThreads) void window_pass(const WindowParams P) {
   for (int nb = 0; nb < NB; ++nb) { m_run[nb] = -INFINITY; l_run[nb] = 0.0f; }
 
   const int groups = (r_end - r_begin + 15) / 16;
-  for (int gi = wave; gi < groups; gi += kWaves) {
-    const int g0 = r_begin + gi * 16;
-    const int row = g0 + x;
+  auto load_group = [&](uint4 (&kreg)[NSL], int gi) {
+    const int row = r_begin + gi * 16 + x;
     const int rc = row < t ? row : t - 1;           // rows past the end repeat the last one, masked below
     const char* src = kbase + static_cast<int64_t>(rc) * ROWB + j * 16;
-    uint4 kreg[NSL];
 #pragma unroll
     for (int sl = 0; sl < NSL; ++sl) kreg[sl] = load_stream16(src + sl * 64);
+  };
+  auto use_group = [&](const uint4 (&kreg)[NSL], int gi) {
+    const int g0 = r_begin + gi * 16;
     float wsum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -185,6 +186,15 @@ __global__ __launch_bounds__(kThreads) void window_pass(const WindowParams P) {
       const int pos = g0 + 4 * j + x;
       if (x < 4 && pos < t) P.w[static_cast<int64_t>(u) * t + pos] = mine;
     }
+  };
+  // Two groups per turn, both requested before either is used.
+  for (int gi = wave; gi < groups; gi += 2 * kWaves) {
+    uint4 ka[NSL], kb[NSL];
+    const bool two = gi + kWaves < groups;
+    load_group(ka, gi);
+    if (two) load_group(kb, gi + kWaves);
+    use_group(ka, gi);
+    if (two) use_group(kb, gi + kWaves);
   }
 
   if (kPhase == 0) {
@@ -432,6 +442,30 @@ __global__ __launch_bounds__(kThreads) void prefill_gather(const GatherParams P)
   }
 }
 
+// Attention score distribution vector of a (layer, sequence): the streams' masses
+// added over the KV heads in index order, then the window sum over the
+// candidates (fp32, left to right, zeros outside).
+__global__ __launch_bounds__(kThreads) void heads_pool(const float* w, float* out, int t, int ows,
+                                                       int n_kv_heads, int pool) {
+  const int pair = blockIdx.y;
+  const int tc = t - ows;
+  const int j = blockIdx.x * kThreads + threadIdx.x;
+  if (j >= tc) return;
+  const float* wp = w + static_cast<int64_t>(pair) * n_kv_heads * t;
+  const int half = pool >> 1;
+  float acc = 0.0f;
+  for (int q = 0; q < pool; ++q) {
+    const int c = j - half + q;
+    float hs = 0.0f;
+    if (c >= 0 && c < tc) {
+      hs = wp[c];
+      for (int h = 1; h < n_kv_heads; ++h) hs = hs + wp[static_cast<int64_t>(h) * t + c];
+    }
+    acc = q == 0 ? hs : acc + hs;
+  }
+  out[static_cast<int64_t>(pair) * tc + j] = acc;
+}
+
 using WindowFn = void (*)(const WindowParams);
 
 template <typename T, int D>
@@ -488,8 +522,85 @@ xkv_status check_prefill_shape(const xkv_cache* cache, int32_t t, int32_t ows, i
   return XKV_OK;
 }
 
+// The three launches that turn (q_win, k_src) into the per-stream masses w.
+xkv_status launch_window_mass(const xkv_cache* cache, int64_t streams, const void* q_win,
+                              const void* k_src, int32_t t, int32_t ows, int nb, float softmax_scale,
+                              WindowFn stats_fn, WindowFn mass_fn, float* stats, float* fin, float* w,
+                              hipStream_t stream) {
+  const int D = cache->head_dim;
+  const int strip_rows = prefill_strip_rows(streams, t);
+  const int64_t nstrips = ceil_div(t, strip_rows);
+  if (streams * nstrips > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;
+  WindowParams W;
+  W.q_win = q_win;
+  W.k_src = k_src;
+  W.stats = stats;
+  W.fin = fin;
+  W.w = w;
+  const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt(static_cast<float>(D));
+  W.scale_log2e = scale * 1.44269504088896340736f;
+  W.t = t; W.ows = ows;
+  W.group = cache->n_q_heads / cache->n_kv_heads;
+  W.n_kv_heads = cache->n_kv_heads;
+  W.strip_rows = strip_rows;
+  W.nstrips = static_cast<int32_t>(nstrips);
+  W.nq_pad = nb * 16;
+  const unsigned grid = static_cast<unsigned>(streams * nstrips);
+  const int tok = profile_begin(2, stream);
+  hipLaunchKernelGGL(stats_fn, dim3(grid), dim3(kThreads), 0, stream, W);
+  profile_end(tok, stream);
+  if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+  hipLaunchKernelGGL(window_merge, dim3(static_cast<unsigned>(streams)), dim3(kThreads), 0, stream, W);
+  if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+  hipLaunchKernelGGL(mass_fn, dim3(grid), dim3(kThreads), 0, stream, W);
+  if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+  return XKV_OK;
+}
+
 }  // namespace
 }  // namespace xkv
+
+extern "C" xkv_status xkv_window_importance(const xkv_cache* cache, int32_t layer_begin,
+                                            int32_t layer_end, const void* q_win, const void* k_src,
+                                            int32_t t, int32_t ows, int32_t pool_size,
+                                            float softmax_scale, float* w_out, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream) {
+  using namespace xkv;
+  xkv_status st = check_cache(cache);
+  if (st != XKV_OK) return st;
+  st = check_layers(cache, layer_begin, layer_end);
+  if (st != XKV_OK) return st;
+  if (q_win == nullptr || k_src == nullptr || w_out == nullptr) return XKV_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(q_win) & 15u) || (reinterpret_cast<uintptr_t>(k_src) & 15u) ||
+      (reinterpret_cast<uintptr_t>(w_out) & 3u))
+    return XKV_ERR_INVALID_ARG;
+  if (pool_size < 1 || (pool_size & 1) == 0) return XKV_ERR_INVALID_ARG;
+  if (!(softmax_scale >= 0.0f) || std::isinf(softmax_scale)) return XKV_ERR_INVALID_ARG;
+  int nb = 0;
+  st = check_prefill_shape(cache, t, ows, &nb);
+  if (st != XKV_OK) return st;
+  const int64_t n_pairs = static_cast<int64_t>(layer_end - layer_begin) * cache->batch;
+  const int64_t streams = n_pairs * cache->n_kv_heads;
+  WindowFn stats_fn = nullptr, mass_fn = nullptr;
+  if (!pick_window(cache->dtype, cache->head_dim, nb, &stats_fn, &mass_fn)) return XKV_ERR_UNSUPPORTED;
+  const PrefillLayout L = prefill_layout(streams, t, nb * 16, true, false);
+  if (workspace == nullptr || L.total > workspace_bytes) return XKV_ERR_CAPACITY;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return XKV_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  float* w_dense = reinterpret_cast<float*>(ws + L.w);
+  st = launch_window_mass(cache, streams, q_win, k_src, t, ows, nb, softmax_scale, stats_fn, mass_fn,
+                          reinterpret_cast<float*>(ws + L.stats), reinterpret_cast<float*>(ws + L.fin),
+                          w_dense, stream);
+  if (st != XKV_OK) return st;
+  const int tc = t - ows;
+  if (tc > 0) {
+    hipLaunchKernelGGL(heads_pool, dim3(static_cast<unsigned>(ceil_div(tc, kThreads)), static_cast<unsigned>(n_pairs)),
+                       dim3(kThreads), 0, stream, w_dense, w_out, t, ows, cache->n_kv_heads, pool_size);
+    if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+  }
+  return XKV_OK;
+}
 
 extern "C" xkv_status xkv_prefill_workspace_bytes(const xkv_cache* cache, int32_t max_layers_per_call,
                                                   int32_t t, int32_t ows, size_t* bytes_out) {
@@ -534,22 +645,17 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
   if (st != XKV_OK) return st;
 
   const int B = cache->batch, hkv = cache->n_kv_heads, D = cache->head_dim;
-  const int G = cache->n_q_heads / hkv;
   const int64_t first = static_cast<int64_t>(layer_begin) * B;
   const int64_t n_pairs = static_cast<int64_t>(layer_end - layer_begin) * B;
   const int64_t streams = n_pairs * hkv;
-  int64_t max_k = 0;
   for (int64_t i = 0; i < n_pairs; ++i) {
     if (budgets[i] < ows) return XKV_ERR_INVALID_ARG;
-    const int64_t kk = std::min<int64_t>(budgets[i], t);
-    if (kk > cache->cap[first + i]) return XKV_ERR_CAPACITY;
-    max_k = std::max(max_k, kk);
+    if (std::min<int64_t>(budgets[i], t) > cache->cap[first + i]) return XKV_ERR_CAPACITY;
   }
   WindowFn stats_fn = nullptr, mass_fn = nullptr;
   if (!pick_window(cache->dtype, D, nb, &stats_fn, &mass_fn)) return XKV_ERR_UNSUPPORTED;
-  const int strip_rows = prefill_strip_rows(streams, t);
-  const int64_t nstrips = ceil_div(t, strip_rows);
-  if (streams * nstrips > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;
+  if (streams * ceil_div(t, prefill_strip_rows(streams, t)) > std::numeric_limits<int32_t>::max())
+    return XKV_ERR_UNSUPPORTED;
   const bool pooled = pool_size > 1;
   const PrefillLayout L = prefill_layout(streams, t, nb * 16, w_out == nullptr, pooled);
   if (workspace == nullptr || L.total > workspace_bytes) return XKV_ERR_CAPACITY;
@@ -557,32 +663,16 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  WindowParams W;
-  W.q_win = q_win;
-  W.k_src = k_src;
-  W.stats = reinterpret_cast<float*>(ws + L.stats);
-  W.fin = reinterpret_cast<float*>(ws + L.fin);
-  W.w = w_out != nullptr ? w_out : reinterpret_cast<float*>(ws + L.w);
-  const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt(static_cast<float>(D));
-  W.scale_log2e = scale * 1.44269504088896340736f;
-  W.t = t; W.ows = ows; W.group = G; W.n_kv_heads = hkv;
-  W.strip_rows = strip_rows;
-  W.nstrips = static_cast<int32_t>(nstrips);
-  W.nq_pad = nb * 16;
-  const unsigned grid = static_cast<unsigned>(streams * nstrips);
-  const int tok = profile_begin(2, stream);
-  hipLaunchKernelGGL(stats_fn, dim3(grid), dim3(kThreads), 0, stream, W);
-  profile_end(tok, stream);
-  if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
-  hipLaunchKernelGGL(window_merge, dim3(static_cast<unsigned>(streams)), dim3(kThreads), 0, stream, W);
-  if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
-  hipLaunchKernelGGL(mass_fn, dim3(grid), dim3(kThreads), 0, stream, W);
-  if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+  float* w_dense = w_out != nullptr ? w_out : reinterpret_cast<float*>(ws + L.w);
+  st = launch_window_mass(cache, streams, q_win, k_src, t, ows, nb, softmax_scale, stats_fn, mass_fn,
+                          reinterpret_cast<float*>(ws + L.stats), reinterpret_cast<float*>(ws + L.fin),
+                          w_dense, stream);
+  if (st != XKV_OK) return st;
 
   GatherParams Gp;
   Gp.k_src = k_src; Gp.v_src = v_src;
   Gp.k = cache->k; Gp.v = cache->v; Gp.score = cache->score; Gp.pos = cache->pos;
-  Gp.w = W.w;
+  Gp.w = w_dense;
   Gp.keys = reinterpret_cast<uint32_t*>(ws + L.keys);
   Gp.idx = reinterpret_cast<int32_t*>(ws + L.idx);
   Gp.t = t; Gp.ows = ows; Gp.pool = pool_size; Gp.n_kv_heads = hkv;

@@ -203,6 +203,33 @@ def test_prefill_argument_errors_leave_state_untouched():
     assert keep["len"].tolist() == [10, 20, 30, 100]
 
 
+def test_device_allocator_and_window_importance_argument_errors():
+    lib = xkv.load()
+    p = 0x2000
+    big = 1 << 30
+    out = C.c_size_t(0)
+    assert lib.xkv_allocate_device_workspace_bytes(4, 1000, C.byref(out)) == 0 and out.value > 0
+    assert lib.xkv_allocate_device_workspace_bytes(0, 1000, C.byref(out)) == -1
+    assert lib.xkv_allocate_device_workspace_bytes(300, 1000, C.byref(out)) == -4       # too many layers
+    bud = np.zeros(4, np.int64)
+    lo = np.array([10, 10, 10, 10], np.int64)
+    hi = np.array([20, 20, 20, 5], np.int64)
+    call = lambda *a: lib.xkv_allocate_budgets_device(*a)
+    assert call(4, p, 1000, 1000, 100, None, None, None, None, p, big, None) == -1      # no output
+    assert call(4, p, 1000, 999, 100, None, None, bud.ctypes.data, None, p, big, None) == -1   # stride < len
+    assert call(4, p, 1000, 1000, 4001, None, None, bud.ctypes.data, None, p, big, None) == -2  # more than there is
+    assert call(4, p, 1000, 1000, 30, lo.ctypes.data, None, bud.ctypes.data, None, p, big, None) == -2  # below the floors
+    assert call(4, p, 1000, 1000, 50, lo.ctypes.data, hi.ctypes.data, bud.ctypes.data, None, p, big, None) == -2  # floor > cap
+    assert call(4, p, 1000, 1000, 100, None, None, bud.ctypes.data, None, p, 64, None) == -3
+    assert call(4, p, 1000, 1000, 100, None, None, bud.ctypes.data, None, 0x2010, big, None) == -1
+    s, keep = _fake_cache()
+    wi = lambda *a: lib.xkv_window_importance(C.byref(s), *a)
+    assert wi(0, 2, p, p, 300, 8, 7, 0.0, None, p, big, None) == -1                     # no output
+    assert wi(0, 2, p, p, 300, 8, 6, 0.0, p, p, big, None) == -1                        # even pooling width
+    assert wi(0, 2, p, p, 300, 40, 7, 0.0, p, p, big, None) == -4
+    assert wi(0, 2, p, p, 300, 8, 7, 0.0, p, p, 64, None) == -3
+
+
 def test_workload_generators_are_seeded_and_consistent():
     w = wl.WORKLOADS["mistral_7b_gqa_b32"]
     b1 = wl.dirichlet_budgets(w.n_layers, 4, w.context, w.total_budget, w.seed)

@@ -133,3 +133,24 @@ def test_evict_gathers_rows_scores_and_positions():
     w_alt[:5] = 9.0
     _, _, _, p3, _ = orc.prefill_evict(q, K, V, budget, ows, pool_size=1, w=w_alt)
     assert set(range(5)) <= set(p3.tolist())
+
+
+def test_window_importance_merges_heads_then_pools():
+    """Against the full causal matrices of every head and a convolution with ones."""
+    r = np.random.default_rng(21)
+    Hkv, G, t, ows, d, ps = 3, 2, 26, 4, 8, 5
+    Q = r.normal(size=(Hkv, G, t, d)).astype(np.float32)
+    K = r.normal(size=(Hkv, t, d)).astype(np.float32)
+    got = orc.window_importance(Q[:, :, t - ows:, :], K, ps)
+    scale = 1.0 / np.sqrt(d)
+    merged = np.zeros(t - ows)
+    for h in range(Hkv):
+        for g in range(G):
+            W = full_causal_attention(Q[h, g].astype(np.float64), K[h].astype(np.float64), scale)
+            merged += W[t - ows:, :t - ows].sum(axis=0)
+    ref = np.convolve(merged, np.ones(ps), mode="same")        # zero padding, same length
+    assert np.allclose(got, ref, rtol=1e-12, atol=1e-15)
+    # without pooling the vector carries everything the windows did not spend on themselves
+    w1 = orc.window_importance(Q[:, :, t - ows:, :], K, 1)
+    own = sum(orc.window_attention_mass(Q[h, :, t - ows:, :], K[h])[t - ows:].sum() for h in range(Hkv))
+    assert abs(w1.sum() + own - Hkv * G * ows) < 1e-9
