@@ -312,8 +312,21 @@ def main():
         from oracle import xkv_oracle as orc
         t0 = time.perf_counter()
         ref, _ = orc.allocate_budgets(alloc["curves"], total_size=w.total_budget, min_budget=alloc["floor"])
-        allocator = {"xkv_allocate_budgets_ms": alloc["lib_ms"], "oracle_ms": (time.perf_counter() - t0) * 1e3,
-                     "identical": bool(np.array_equal(ref, budgets[:, 0])), "r_avg": alloc["r_avg"]}
+        oracle_ms = (time.perf_counter() - t0) * 1e3
+        # the same curves, already on the device (where the mini-prefill leaves them)
+        dev_curves = torch.from_numpy(np.stack(alloc["curves"])).cuda()
+        aws = torch.empty(xkv.xkv_allocate_device_workspace_bytes(L, w.context), dtype=torch.uint8, device="cuda")
+        dev_ms, dev_bud = None, None
+        for _ in range(3):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            dev_bud, _ = xkv.xkv_allocate_budgets_device(dev_curves, L, w.context, w.context, w.total_budget, aws,
+                                                         min_budget=alloc["floor"])
+            dev_ms = (time.perf_counter() - t0) * 1e3
+        allocator = {"xkv_allocate_budgets_ms": alloc["lib_ms"], "oracle_ms": oracle_ms,
+                     "xkv_allocate_budgets_device_ms": dev_ms,
+                     "identical": bool(np.array_equal(ref, budgets[:, 0])),
+                     "device_identical": bool(np.array_equal(dev_bud, budgets[:, 0])), "r_avg": alloc["r_avg"]}
 
     step_gbs = alg_bytes_timed / elapsed / 1e9
     line = {
