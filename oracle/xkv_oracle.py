@@ -30,6 +30,9 @@ What follows which passage of the paper (arXiv 2412.05896):
 * ``retention_ratio``   Eq. 4 (R_i), as a fraction.
 * ``allocate_budgets``  Alg. 1 (allocation list + wait list greedy) for the
                         two problems of Eq. 17 and Eq. 18.
+* ``average_allocations``  Sec. 4.3 (sampling-based overhead reduction): the
+                        average of the allocation lists recorded on sampled
+                        tasks, as an integer list for the next task.
 
 Parity pins: every function here is pinned by tests that do not go through it
 (brute force, closed forms, a library routine, hand-worked cases).  The whole
@@ -53,6 +56,7 @@ __all__ = [
     "prefill_evict",
     "retention_ratio",
     "allocate_budgets",
+    "average_allocations",
     "OracleUnit",
 ]
 
@@ -403,6 +407,54 @@ def allocate_budgets(w, total_size=None, target_ravg=None, min_budget=None, max_
 # --------------------------------------------------------------------------
 # a unit with state, for multi-step runs
 # --------------------------------------------------------------------------
+# --------------------------------------------------------------------------
+# Sec. 4.3: averaged allocation list of sampled tasks
+# --------------------------------------------------------------------------
+def average_allocations(lists, total_size: int, min_budget=None, max_budget=None) -> np.ndarray:
+    """Allocation list for a new task from the lists recorded on sampled tasks.
+
+    lists [n_samples, L] non-negative integers.  The per-layer averages are
+    scaled so that they sum to ``total_size`` (they already do when every
+    sample was allocated that total), x_l = total_size * sum_s lists[s][l] /
+    sum of all entries, in exact rational arithmetic.  Rounding is by largest
+    remainder: every layer gets floor(x_l), the layers with the largest
+    fractional parts one more until the total is met (equal parts: lower layer
+    first).  With bounds the list is then clamped, and single tokens are added
+    to the layer furthest below its x_l (below its cap), or taken from the one
+    furthest above (above its floor), until the total is met again.
+    """
+    from fractions import Fraction
+    lists = np.asarray(lists, dtype=np.int64)
+    if lists.ndim != 2 or lists.shape[0] < 1 or np.any(lists < 0):
+        raise ValueError("lists must be [n_samples, L] non-negative")
+    L = lists.shape[1]
+    col = [int(v) for v in lists.sum(axis=0)]
+    tot = sum(col)
+    N = int(total_size)
+    lo = [0] * L if min_budget is None else [int(v) for v in min_budget]
+    hi = [None] * L if max_budget is None else [int(v) for v in max_budget]
+    if tot == 0:
+        raise ValueError("the samples hold no tokens")
+    if any(h is not None and l > h for l, h in zip(lo, hi)) or N < sum(lo) or \
+            (all(h is not None for h in hi) and N > sum(hi)):
+        raise ValueError("infeasible")
+    x = [Fraction(c * N, tot) for c in col]
+    n = [int(v) for v in (f.numerator // f.denominator for f in x)]
+    frac = [x[l] - n[l] for l in range(L)]
+    for l in sorted(range(L), key=lambda l: (-frac[l], l))[:N - sum(n)]:
+        n[l] += 1
+    n = [max(lo[l], n[l] if hi[l] is None else min(hi[l], n[l])) for l in range(L)]
+    while sum(n) < N:
+        cand = [l for l in range(L) if hi[l] is None or n[l] < hi[l]]
+        l = min(cand, key=lambda l: (-(x[l] - n[l]), l))
+        n[l] += 1
+    while sum(n) > N:
+        cand = [l for l in range(L) if n[l] > lo[l]]
+        l = min(cand, key=lambda l: (-(n[l] - x[l]), l))
+        n[l] -= 1
+    return np.asarray(n, dtype=np.int64)
+
+
 class OracleUnit:
     """State of one (layer, sequence, KV head) across decode steps."""
 
