@@ -88,6 +88,27 @@ xkv_status xkv_allocate_budgets(int32_t n_layers, const float* const* w, const i
                                 int64_t* budgets_out, double* ravg_out);
 
 /*
+ * Sampling-based overhead reduction (Sec. 4.3): the allocation list for a new
+ * task of a known type, from the lists that the allocator produced on sampled
+ * tasks of that type.  Host only.
+ *
+ *   lists        HOST [n_samples][n_layers], each >= 0, not all zero
+ *   total_size   tokens to hand out; the per-layer averages are scaled so that
+ *                they sum to it: x_l = total_size * sum_s lists[s][l] / sum of
+ *                all entries (exact rational arithmetic)
+ *   budgets_out  HOST [n_layers]: floor(x_l), plus one for the layers with the
+ *                largest fractional parts until the total is met (equal parts:
+ *                lower layer first).  With bounds, the list is then clamped and
+ *                single tokens go to the layer furthest below its x_l that is
+ *                under its cap, or leave the one furthest above that is over its
+ *                floor (equal distances: lower layer), until the total is met.
+ * Errors: INVALID_ARG, INFEASIBLE (min > max, total outside [sum min, sum max]).
+ */
+xkv_status xkv_average_allocations(int32_t n_samples, int32_t n_layers, const int64_t* lists,
+                                   int64_t total_size, const int64_t* min_budget,
+                                   const int64_t* max_budget, int64_t* budgets_out);
+
+/*
  * Device form of the allocation for XKV_ALLOC_TOTAL_SIZE (Alg. 1, Eq. 17), for
  * score vectors that already live on the device, such as the w_out of
  * xkv_window_importance: same result as xkv_allocate_budgets whenever no two

@@ -18,6 +18,7 @@ EXPORTS = (
     "xkv_decode_attend_score", "xkv_evict_compact", "xkv_profile_enable", "xkv_profile_read",
     "xkv_configure", "xkv_probe_stream_read", "xkv_prefill_workspace_bytes", "xkv_prefill_evict",
     "xkv_window_importance", "xkv_allocate_device_workspace_bytes", "xkv_allocate_budgets_device",
+    "xkv_average_allocations",
 )
 XKV_CFG_ATTEND_PATH = 1
 
@@ -87,6 +88,9 @@ def load():
     lib.xkv_allocate_budgets_device.argtypes = [
         C.c_int32, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
         C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.xkv_average_allocations.restype = C.c_int32
+    lib.xkv_average_allocations.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                            C.c_void_p]
     lib.xkv_configure.restype = C.c_int32
     lib.xkv_configure.argtypes = [C.c_int32, C.c_int64]
     lib.xkv_probe_stream_read.restype = C.c_int32
@@ -145,6 +149,20 @@ def xkv_allocate_budgets(w: Sequence[np.ndarray], mode: int = XKV_ALLOC_TOTAL_SI
                                   C.byref(ravg))
     _check(st, "xkv_allocate_budgets")
     return out[:L], ravg.value
+
+
+def xkv_average_allocations(lists, total_size: int, min_budget=None, max_budget=None):
+    """lists: integers [n_samples, L] -> budgets int64 [L] summing to total_size."""
+    arr = np.ascontiguousarray(lists, dtype=np.int64)
+    if arr.ndim != 2:
+        raise ValueError("lists must be [n_samples, L]")
+    lo = None if min_budget is None else np.ascontiguousarray(min_budget, dtype=np.int64)
+    hi = None if max_budget is None else np.ascontiguousarray(max_budget, dtype=np.int64)
+    out = np.zeros(max(arr.shape[1], 1), dtype=np.int64)
+    st = load().xkv_average_allocations(arr.shape[0], arr.shape[1], arr.ctypes.data, int(total_size), _ptr(lo),
+                                        _ptr(hi), out.ctypes.data)
+    _check(st, "xkv_average_allocations")
+    return out[:arr.shape[1]]
 
 
 class XkvCache:

@@ -13,6 +13,7 @@
 #include <cmath>
 #include <cstdint>
 #include <functional>
+#include <limits>
 #include <queue>
 #include <utility>
 #include <vector>
@@ -143,5 +144,76 @@ extern "C" xkv_status xkv_allocate_budgets(int32_t n_layers, const float* const*
     budgets_out[l] = n[l];
   }
   if (ravg_out) *ravg_out = ravg / n_layers;
+  return XKV_OK;
+}
+
+// Sampling-based overhead reduction (Sec. 4.3): the allocation lists recorded
+// on sampled tasks are averaged into the list for the next task.  All
+// arithmetic is exact: with column sums c_l and grand total C the target of
+// layer l is x_l = N c_l / C, compared through the integers N c_l - n_l C.
+extern "C" xkv_status xkv_average_allocations(int32_t n_samples, int32_t n_layers,
+                                              const int64_t* lists, int64_t total_size,
+                                              const int64_t* min_budget, const int64_t* max_budget,
+                                              int64_t* budgets_out) {
+  if (n_samples <= 0 || n_layers <= 0 || lists == nullptr || budgets_out == nullptr || total_size < 0)
+    return XKV_ERR_INVALID_ARG;
+  typedef __int128 wide;
+  std::vector<wide> col(static_cast<size_t>(n_layers), 0);
+  wide tot = 0;
+  for (int32_t s = 0; s < n_samples; ++s)
+    for (int32_t l = 0; l < n_layers; ++l) {
+      const int64_t v = lists[static_cast<int64_t>(s) * n_layers + l];
+      if (v < 0) return XKV_ERR_INVALID_ARG;
+      col[l] += v;
+      tot += v;
+    }
+  if (tot == 0) return XKV_ERR_INVALID_ARG;
+  std::vector<int64_t> lo(n_layers), hi(n_layers);
+  wide sum_lo = 0, sum_hi = 0;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    lo[l] = min_budget ? min_budget[l] : 0;
+    hi[l] = max_budget ? max_budget[l] : std::numeric_limits<int64_t>::max();
+    if (lo[l] < 0 || lo[l] > hi[l]) return XKV_ERR_INFEASIBLE;
+    sum_lo += lo[l];
+    sum_hi += hi[l];
+  }
+  if (total_size < sum_lo || total_size > sum_hi) return XKV_ERR_INFEASIBLE;
+
+  const wide N = total_size;
+  std::vector<int64_t> n(n_layers);
+  std::vector<wide> rem(n_layers);               // N c_l mod C: the fractional part times C
+  wide given = 0;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    n[l] = static_cast<int64_t>(N * col[l] / tot);
+    rem[l] = N * col[l] % tot;
+    given += n[l];
+  }
+  std::vector<int32_t> order(n_layers);
+  for (int32_t l = 0; l < n_layers; ++l) order[l] = l;
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return rem[a] > rem[b]; });
+  for (int64_t i = 0; i < static_cast<int64_t>(N - given); ++i) n[order[static_cast<size_t>(i)]] += 1;
+
+  wide have = 0;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    n[l] = std::max(lo[l], std::min(hi[l], n[l]));
+    have += n[l];
+  }
+  // deficit of layer l times C: N c_l - n_l C (how far it is below its target)
+  auto deficit = [&](int32_t l) { return N * col[l] - static_cast<wide>(n[l]) * tot; };
+  while (have != N) {
+    int32_t pick = -1;
+    for (int32_t l = 0; l < n_layers; ++l) {
+      if (have < N) {
+        if (n[l] >= hi[l]) continue;
+        if (pick < 0 || deficit(l) > deficit(pick)) pick = l;
+      } else {
+        if (n[l] <= lo[l]) continue;
+        if (pick < 0 || deficit(l) < deficit(pick)) pick = l;
+      }
+    }
+    if (pick < 0) return XKV_ERR_INFEASIBLE;     // cannot happen after the checks above
+    if (have < N) { n[pick] += 1; have += 1; } else { n[pick] -= 1; have -= 1; }
+  }
+  for (int32_t l = 0; l < n_layers; ++l) budgets_out[l] = n[l];
   return XKV_OK;
 }

@@ -241,3 +241,45 @@ def test_workload_generators_are_seeded_and_consistent():
     assert wl.WORKLOADS["llama3_70b_128k"].total_budget == 1572864
     off, cap, slots = wl.region_table(np.array([[8, 16], [24, 8]]), 4)
     assert off.tolist() == [0, 32, 96, 192] and slots == 224
+
+
+# ---- averaged allocation lists (host only) ----
+def test_average_allocations_matches_oracle():
+    from oracle import xkv_oracle as orc
+    r = np.random.default_rng(3)
+    for trial in range(200):
+        L, S = int(r.integers(1, 9)), int(r.integers(1, 6))
+        lists = r.integers(0, 50, size=(S, L))
+        if lists.sum() == 0:
+            lists[0, 0] = 3
+        use_bounds = trial % 3 == 0
+        lo = r.integers(0, 10, size=L) if use_bounds else None
+        hi = (lo + r.integers(0, 60, size=L)) if use_bounds else None
+        N = int(r.integers(lo.sum(), hi.sum() + 1)) if use_bounds else int(r.integers(0, 400))
+        got = xkv.xkv_average_allocations(lists, N, lo, hi)
+        ref = orc.average_allocations(lists, N, lo, hi)
+        assert np.array_equal(got, ref), (trial, lists, N, lo, hi, got, ref)
+    # the lists that the allocator gives for similar tasks, averaged, still sum to the total
+    curves = [wl.zipf_importance_curves(6, 300, seed=s) for s in range(4)]
+    lists = np.stack([xkv.xkv_allocate_budgets(c, total_size=500)[0] for c in curves])
+    avg = xkv.xkv_average_allocations(lists, 500)
+    assert avg.sum() == 500 and np.all(avg >= lists.min(axis=0)) and np.all(avg <= lists.max(axis=0))
+
+
+def test_average_allocations_errors():
+    lib = xkv.load()
+    lists = np.array([[1, 2], [3, 4]], np.int64)
+    out = np.zeros(2, np.int64)
+    f = lambda *a: lib.xkv_average_allocations(*a)
+    assert f(2, 2, lists.ctypes.data, 10, None, None, out.ctypes.data) == 0 and out.tolist() == [4, 6]
+    assert f(0, 2, lists.ctypes.data, 10, None, None, out.ctypes.data) == -1
+    assert f(2, 2, None, 10, None, None, out.ctypes.data) == -1
+    assert f(2, 2, lists.ctypes.data, -1, None, None, out.ctypes.data) == -1
+    neg = np.array([[1, -2], [3, 4]], np.int64)
+    assert f(2, 2, neg.ctypes.data, 10, None, None, out.ctypes.data) == -1
+    zero = np.zeros((2, 2), np.int64)
+    assert f(2, 2, zero.ctypes.data, 10, None, None, out.ctypes.data) == -1
+    lo = np.array([8, 8], np.int64)
+    assert f(2, 2, lists.ctypes.data, 10, lo.ctypes.data, None, out.ctypes.data) == -2
+    hi = np.array([3, 3], np.int64)
+    assert f(2, 2, lists.ctypes.data, 10, None, hi.ctypes.data, out.ctypes.data) == -2
