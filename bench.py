@@ -37,6 +37,10 @@ def parse():
     ap.add_argument("--no-roofline-pass", action="store_true")
     ap.add_argument("--keep-prompt-arena", action="store_true",
                     help="stay in the prompt-sized arena after the first eviction instead of moving to one sized by the budgets")
+    ap.add_argument("--evict-every", type=int, default=1,
+                    help="decode steps between evictions (1 = every step; 8 = once per observation window)")
+    ap.add_argument("--n-protect", type=int, default=0, help="most recent tokens that are never evicted")
+    ap.add_argument("--pool-size", type=int, default=1, help="pooling width of the eviction keys (odd)")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill-phase eviction leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of 1 GiB x 10 (reference point for HBM byte counters)")
@@ -154,11 +158,16 @@ def main():
         return
     w = wl.WORKLOADS[args.workload]
     W = max(args.warmup, 0)
+    if args.evict_every > 1:
+        W = max(W, args.evict_every)          # the warm-up ends with the first (prompt-sized) eviction
     K = args.steps if args.steps is not None else max(w.decode_steps - W, 1)
     L, B = w.n_layers, w.batch
 
     budgets, alloc = make_budgets(xkv, wl, w)
-    caps = np.full((L, B), wl.round_up(w.context + 1, 8), dtype=np.int32)
+    every = max(args.evict_every, 1)
+    if args.n_protect > 0:
+        budgets = np.maximum(budgets, args.n_protect).astype(np.int32)
+    caps = np.full((L, B), wl.round_up(w.context + every, 8), dtype=np.int32)
     cache = xkv.XkvCache(L, B, w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, caps)
     wl.fill_prompt_cache(w, cache.k, cache.v, cache.score, cache.pos, cache.region_off, cache.cap)
     cache.len[:] = w.context
@@ -180,7 +189,9 @@ def main():
         pos_step[:] = w.context + t
         alg_bytes[0] += algorithmic_bytes(w, c.len + 1)
         xkv.xkv_decode_attend_score(c, 0, L, q[i], kn[i], vn[i], pos_step, out, state["ws"], stream=stream)
-        xkv.xkv_evict_compact(c, 0, L, budgets, state["ws"], stream=stream)
+        if (t + 1) % every == 0:
+            xkv.xkv_evict_compact(c, 0, L, budgets, state["ws"], pool_size=args.pool_size,
+                                  n_protect=args.n_protect, stream=stream)
 
     t = 0
     step0_ms = None
@@ -191,9 +202,10 @@ def main():
         torch.cuda.synchronize()
         if t == 0:
             step0_ms = (time.perf_counter() - t0) * 1e3
+        if t == every - 1:
             if not args.keep_prompt_arena:
                 # the prompt-sized arena has done its job: continue in one sized by the budgets
-                packed = repack(cache, budgets)
+                packed = repack(cache, budgets, slack=every)
                 del ws, cache
                 state["cache"] = None
                 state["ws"] = None
@@ -217,14 +229,15 @@ def main():
     value = L * K / elapsed
 
     roofline = None
-    steady = bool(np.all(cache.len.reshape(L, B) <= budgets))
+    steady = bool(np.all(cache.len.reshape(L, B) < budgets + every))
     if not args.no_roofline_pass:
-        alg_bytes_step = algorithmic_bytes(w, cache.len + 1)
+        alg_bytes[0] = 0
         xkv.xkv_profile_enable(True)
         for _ in range(K):
             step(t)
             t += 1
         torch.cuda.synchronize()
+        alg_bytes_step = alg_bytes[0] / K
         launches, total_ms = xkv.xkv_profile_read(0)
         sel_launches, sel_ms = xkv.xkv_profile_read(1)
         xkv.xkv_profile_enable(False)
@@ -338,7 +351,9 @@ def main():
                    "head_dim": w.head_dim, "batch": B, "context": w.context,
                    "total_budget": int(budgets[:, 0].sum()), "budget_frac": w.budget_frac,
                    "budget_min": int(budgets.min()), "budget_max": int(budgets.max()),
-                   "schedule": "every step, every layer: append, attend+score, evict to budget",
+                   "schedule": "every step, every layer: append, attend+score" +
+                               (", evict to budget" if every == 1 else f"; every {every} steps: evict to budget"),
+                   "pool_size": args.pool_size, "n_protect": args.n_protect,
                    "arena": "prompt-sized" if args.keep_prompt_arena or W == 0 else "budget-sized after the first eviction",
                    "kv_arena_bytes": int(2 * cache.arena_slots * w.head_dim * w.elem_bytes),
                    "steady_state": steady},

@@ -127,6 +127,7 @@ __global__ __launch_bounds__(kSelThreads) void evict_select(const EvictParams P)
     const bool protect = P.n_protect > 0;
     if (protect) {
       int mx = std::numeric_limits<int>::min();
+#pragma unroll 4
       for (int j = tid; j < n; j += kSelThreads) mx = max(mx, pos[j]);
 #pragma unroll
       for (int off = 32; off > 0; off >>= 1) mx = max(mx, __shfl_xor(mx, off));
@@ -141,14 +142,22 @@ __global__ __launch_bounds__(kSelThreads) void evict_select(const EvictParams P)
       __syncthreads();
     }
     const int half = P.pool >> 1;
+#pragma unroll 2
     for (int j = tid; j < n; j += kSelThreads) {
-      // window sum, fp32, left to right, zeros outside the stream
-      int x = j - half;
-      float acc = (x >= 0 && x < n) ? score[x] : 0.0f;
-      for (int t = 1; t < P.pool; ++t) {
-        ++x;
-        const float term = (x >= 0 && x < n) ? score[x] : 0.0f;
-        acc = acc + term;
+      // window sum, fp32, left to right, zeros outside the stream; the terms are
+      // fetched eight at a time so that their loads overlap
+      float acc = 0.0f;
+      for (int t0 = 0; t0 < P.pool; t0 += 8) {
+        float term[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const int x = j - half + t0 + q;
+          const bool in = t0 + q < P.pool && x >= 0 && x < n;
+          term[q] = in ? score[x] : 0.0f;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+          if (t0 + q < P.pool) acc = (t0 + q == 0) ? term[q] : acc + term[q];
       }
       unsigned key = __float_as_uint(acc);
       if (protect && pos[j] >= limit) key = 0x7f800000u;
@@ -168,6 +177,7 @@ __global__ __launch_bounds__(kSelThreads) void evict_select(const EvictParams P)
     unsigned long long last = 0;            // every pack is > 0: ~slot has its top bit set
     for (int r = 0; r < E; ++r) {
       unsigned long long best = ~0ull;
+#pragma unroll 4
       for (int j = tid; j < n; j += kSelThreads) {
         const unsigned long long pk =
             (static_cast<unsigned long long>(key_at(j)) << 32) | (0xffffffffu - static_cast<unsigned>(j));
