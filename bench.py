@@ -47,6 +47,11 @@ def parse():
     return ap.parse_args()
 
 
+def note(msg):
+    """Progress line on stderr (the result line on stdout stays the only one there)."""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def make_budgets(xkv, wl, w):
     """int32 [L, B] per the workload's rule; also returns allocator timings."""
     import numpy as np
@@ -163,6 +168,7 @@ def main():
     K = args.steps if args.steps is not None else max(w.decode_steps - W, 1)
     L, B = w.n_layers, w.batch
 
+    note(f"workload {w.name}: budgets")
     budgets, alloc = make_budgets(xkv, wl, w)
     every = max(args.evict_every, 1)
     if args.n_protect > 0:
@@ -193,6 +199,7 @@ def main():
             xkv.xkv_evict_compact(c, 0, L, budgets, state["ws"], pool_size=args.pool_size,
                                   n_protect=args.n_protect, stream=stream)
 
+    note("prompt cache filled; warm-up steps")
     t = 0
     step0_ms = None
     for _ in range(W):
@@ -217,6 +224,7 @@ def main():
 
 
     torch.cuda.synchronize()
+    note(f"timing {K} steps")
     alg_bytes[0] = 0
     t0 = time.perf_counter()
     for _ in range(K):
@@ -231,6 +239,7 @@ def main():
     roofline = None
     steady = bool(np.all(cache.len.reshape(L, B) < budgets + every))
     if not args.no_roofline_pass:
+        note("roofline pass")
         alg_bytes[0] = 0
         xkv.xkv_profile_enable(True)
         for _ in range(K):
@@ -245,7 +254,7 @@ def main():
         bytes_per_launch = alg_bytes_step / launches_per_step
         achieved = bytes_per_launch / (total_ms / launches * 1e-3) / 1e9
         traffic = None
-        tfile = os.path.join(ROOT, "profiles", f"attend_strip_{w.name}_hbm_traffic.txt")
+        tfile = os.path.join(ROOT, "profiles", f"decode_kernels_{w.name}_hbm_traffic.txt")
         if os.path.exists(tfile):
             for line in open(tfile):
                 if line.startswith("traffic_bytes_per_launch:"):
@@ -282,6 +291,7 @@ def main():
     # prefill would call it: one dense layer of the prompt at a time into a budget-sized cache.
     prefill = None
     if not args.no_prefill:
+        note("prefill-phase eviction leg")
         ows, ps = 8, 7
         bud_p = np.maximum(budgets, ows)
         caps_p = ((np.minimum(bud_p, w.context).astype(np.int64) + 7) // 8 * 8).astype(np.int32)
@@ -316,12 +326,14 @@ def main():
 
     cpu = None
     if args.cpu_seconds > 0:
+        note("oracle on the host cores")
         i = t % gen_steps
         pos_step[:] = w.context + t
         cpu = cpu_baseline(w, wl, cache, budgets, q[i], kn[i], vn[i], pos_step, args.cpu_seconds)
 
     allocator = None
     if alloc:
+        note("allocator timings")
         from oracle import xkv_oracle as orc
         t0 = time.perf_counter()
         ref, _ = orc.allocate_budgets(alloc["curves"], total_size=w.total_budget, min_budget=alloc["floor"])
