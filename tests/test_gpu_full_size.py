@@ -30,11 +30,16 @@ def unit_mass(cache):
 def run_full(xkv, name, steps, n_sample):
     w = wl.WORKLOADS[name]
     L, B, G = w.n_layers, w.batch, w.group
-    curves = wl.zipf_importance_curves(L, w.context, w.seed)
-    floor = [w.min_budget] * L if w.min_budget else None
-    b1, ravg = xkv.xkv_allocate_budgets(curves, total_size=w.total_budget, min_budget=floor)
-    assert int(b1.sum()) == w.total_budget
-    budgets = np.repeat(b1.astype(np.int32)[:, None], B, axis=1)
+    if w.budget_rule == "dirichlet":
+        budgets = np.ascontiguousarray(wl.dirichlet_budgets(L, B, w.context, w.total_budget, w.seed), dtype=np.int32)
+        assert np.all(budgets.sum(axis=0) == w.total_budget)
+        b1 = budgets[:, 0]
+    else:
+        curves = wl.zipf_importance_curves(L, w.context, w.seed)
+        floor = [w.min_budget] * L if w.min_budget else None
+        b1, ravg = xkv.xkv_allocate_budgets(curves, total_size=w.total_budget, min_budget=floor)
+        assert int(b1.sum()) == w.total_budget
+        budgets = np.repeat(b1.astype(np.int32)[:, None], B, axis=1)
     caps = np.full((L, B), (w.context + 1 + 7) // 8 * 8, dtype=np.int32)
     cache = xkv.XkvCache(L, B, w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, caps)
     print(f"{name}: filling {2 * cache.arena_slots * w.head_dim * w.elem_bytes / 1e9:.1f} GB of K/V", flush=True)
@@ -108,3 +113,13 @@ def test_llama2_7b_4k_full_size(xkv, attend_path):
 
 def test_llama2_7b_32k_full_size(xkv, attend_path):
     run_full(xkv, "llama2_7b_32k", steps=3, n_sample=8)
+
+
+def test_mistral_7b_gqa_b32_full_size(xkv):
+    """Batched GQA (G = 4) through the matrix-core kernel: 8 launches per call, per-sequence budgets."""
+    run_full(xkv, "mistral_7b_gqa_b32", steps=2, n_sample=6)
+
+
+def test_llama3_70b_128k_full_size(xkv):
+    """G = 8, 128k-token streams, 172 GB of K/V in the prompt-sized arena."""
+    run_full(xkv, "llama3_70b_128k", steps=2, n_sample=5)
