@@ -149,3 +149,19 @@ def test_decode_continues_on_a_prefilled_cache(xkv):
         K2, V2, s2, p2 = get_unit(cache, l, 0, h)
         assert rel_err(out[l, 0, h * 2:(h + 1) * 2].cpu().numpy(), o) <= TOL["bf16"]
         assert len(p2) == budgets[l, 0] and t in p2.tolist()
+
+
+def test_full_size_layer_of_the_long_context_workload(xkv):
+    """One layer of the 32k workload as the benchmark's prefill leg calls it (32 heads, t = 32768,
+    register-resident keys in the selection); four sampled heads against the oracle."""
+    units = {(0, 0, h) for h in (0, 7, 18, 31)}
+    e = run_prefill(xkv, "bf16", 128, 32, 32, 1, 1, 32768, 8, 7, [[6554]], seed=31, check_units=units)
+    print("32k layer w rel err", e, flush=True)
+
+
+def test_full_size_layer_of_the_128k_gqa_workload(xkv):
+    """One layer of the 128k GQA workload (G = 8: 64 window rows per KV head, t = 131072, keys through
+    the workspace), two sequences with the largest and the smallest budget; three sampled units."""
+    units = {(0, 0, 0), (0, 1, 7), (0, 0, 5)}
+    e = run_prefill(xkv, "bf16", 128, 64, 8, 1, 2, 131072, 8, 7, [[19661, 256]], seed=32, check_units=units)
+    print("128k layer w rel err", e, flush=True)
