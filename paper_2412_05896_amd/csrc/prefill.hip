@@ -38,6 +38,12 @@ constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kMaxNq = 64;                 // query rows (ows * G) per KV head
 constexpr int kMaxKeyRegs = 32;            // prefill_select: keys a thread keeps in registers
 constexpr int kMaxWalkRows = 256;          // prefill_select without register keys: rows of candidates
+// Selection of a long stream split over several workgroups (see split_*): candidates per
+// workgroup, and the words of per-stream state: 4 histograms, threshold and need, (gt, eq) per chunk.
+constexpr int kSplitKeys = 8;
+constexpr int kSplitChunk = kSplitKeys * kSelThreads;
+constexpr int kSplitMaxChunks = kMaxWalkRows * kSelThreads / kSplitChunk;
+constexpr int kSplitWords = 4 * 256 + 2 + 2 * kSplitMaxChunks;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -267,6 +273,7 @@ struct GatherParams {
   const float* w;        // [streams][t]
   uint32_t* keys;        // [streams][t] pooled keys (only used when pool > 1)
   int32_t* idx;          // [streams][t] kept positions, ascending
+  unsigned* split;       // [streams][kSplitWords]: state of the selection split over several workgroups
   int32_t t, ows, pool, n_kv_heads, row_bytes;
   int32_t stream0;       // index of this launch's first stream within the call
   GatherPair pairs[kMaxPairs];
@@ -401,6 +408,226 @@ __global__ __launch_bounds__(kSelThreads) void prefill_select(const GatherParams
   });
 }
 
+// ---- selection of a long stream by several workgroups ------------------------
+// With few streams of many candidates one workgroup per stream leaves most of the
+// chip idle.  Here workgroup (chunk, stream) owns kSplitChunk candidates and the
+// steps of prefill_select become launches, the kernel boundaries standing in for
+// its barriers: split_keys (pooled keys, histogram of the top byte), three times
+// split_hist (next byte, among the keys that match the bins picked so far; every
+// workgroup re-derives those bins from the stream's histograms), split_count
+// (threshold; keys above it and equal to it per chunk), split_write (ranks from
+// the chunk counts, then the ordered walk inside the chunk).  All counters are
+// integers added with atomics: the result does not depend on the order.
+struct SplitCtx {
+  int ul, c, t, tc, kc, first, n;     // stream, chunk, lengths, first candidate and count of the chunk
+  int64_t u;
+  unsigned* st;                       // the stream's state words
+};
+
+__device__ __forceinline__ SplitCtx split_ctx(const GatherParams& P) {
+  SplitCtx x;
+  x.ul = blockIdx.y;
+  x.c = blockIdx.x;
+  x.u = static_cast<int64_t>(P.stream0) + x.ul;
+  x.t = P.t;
+  x.tc = P.t - P.ows;
+  x.kc = P.pairs[x.ul / P.n_kv_heads].k - P.ows;
+  x.first = x.c * kSplitChunk;
+  x.n = min(kSplitChunk, x.tc - x.first);
+  x.st = P.split + x.u * kSplitWords;
+  return x;
+}
+
+__device__ __forceinline__ bool split_idle(const SplitCtx& x) {   // nothing to select, or no candidates here
+  return x.kc >= x.tc || x.kc <= 0 || x.n <= 0;
+}
+
+// Adds the chunk's keys that match (mask, prefix) to the stream's histogram of digit `pass`.
+__device__ __forceinline__ void split_add_hist(const SplitCtx& x, const unsigned (&kreg)[kSplitKeys], int pass,
+                                               unsigned prefix, unsigned mask, unsigned* hist_sh) {
+  const int tid = threadIdx.x;
+  const int shift = 24 - 8 * pass;
+  if (tid < 256) hist_sh[tid] = 0;
+  __syncthreads();
+  unsigned run_bin = 0, run_len = 0;
+#pragma unroll
+  for (int i = 0; i < kSplitKeys; ++i) {
+    if (i * kSelThreads + tid < x.n && (kreg[i] & mask) == prefix) {
+      const unsigned bin = (kreg[i] >> shift) & 255u;
+      if (bin != run_bin && run_len != 0) {
+        atomicAdd(&hist_sh[run_bin], run_len);
+        run_len = 0;
+      }
+      run_bin = bin;
+      ++run_len;
+    }
+  }
+  if (run_len != 0) atomicAdd(&hist_sh[run_bin], run_len);
+  __syncthreads();
+  if (tid < 256 && hist_sh[tid] != 0) atomicAdd(&x.st[pass * 256 + tid], hist_sh[tid]);
+}
+
+// The bins of digits 0 .. passes-1 from the stream's histograms.
+__device__ __forceinline__ void split_prefix(const SplitCtx& x, int passes, RadixShared& sh, unsigned& prefix,
+                                             unsigned& mask, unsigned& need) {
+  prefix = 0; mask = 0;
+  need = static_cast<unsigned>(x.kc);
+  for (int p = 0; p < passes; ++p) {
+    unsigned bin;
+    radix_pick_bin(x.st + p * 256, need, sh, bin, need);
+    prefix |= bin << (24 - 8 * p);
+    mask |= 255u << (24 - 8 * p);
+  }
+}
+
+__device__ __forceinline__ void split_load_keys(const GatherParams& P, const SplitCtx& x,
+                                                unsigned (&kreg)[kSplitKeys]) {
+  const uint32_t* keys = P.keys + x.u * x.t;
+#pragma unroll
+  for (int i = 0; i < kSplitKeys; ++i) {
+    const int jl = i * kSelThreads + threadIdx.x;
+    kreg[i] = jl < x.n ? keys[x.first + jl] : 0u;
+  }
+}
+
+__global__ void split_zero(const GatherParams P) {
+  unsigned* st = P.split + (static_cast<int64_t>(P.stream0) + blockIdx.x) * kSplitWords;
+  for (int i = threadIdx.x; i < kSplitWords; i += blockDim.x) st[i] = 0u;
+}
+
+__global__ __launch_bounds__(kSelThreads) void split_keys(const GatherParams P) {
+  __shared__ unsigned hist_sh[256];
+  __shared__ float wpad_sh[kSplitChunk + 64];
+  const SplitCtx x = split_ctx(P);
+  if (split_idle(x)) return;
+  const int tid = threadIdx.x;
+  const float* w = P.w + x.u * x.t;
+  const int half = P.pool >> 1;               // pool <= 63 on this path (checked on the host)
+  // candidates first - half .. first + n + half, zeros outside the candidate vector
+  for (int i = tid; i < x.n + 2 * half; i += kSelThreads) {
+    const int cnd = x.first - half + i;
+    wpad_sh[i] = (cnd >= 0 && cnd < x.tc) ? w[cnd] : 0.0f;
+  }
+  __syncthreads();
+  unsigned kreg[kSplitKeys];
+  uint32_t* keys = P.keys + x.u * x.t;
+#pragma unroll
+  for (int i = 0; i < kSplitKeys; ++i) {
+    const int jl = i * kSelThreads + tid;
+    unsigned key = 0u;
+    if (jl < x.n) {
+      float acc = wpad_sh[jl];                // window sum, fp32, left to right
+      for (int q = 1; q < P.pool; ++q) acc = acc + wpad_sh[jl + q];
+      key = __float_as_uint(acc);
+      keys[x.first + jl] = key;
+    }
+    kreg[i] = key;
+  }
+  split_add_hist(x, kreg, 0, 0u, 0u, hist_sh);
+}
+
+__global__ __launch_bounds__(kSelThreads) void split_hist(const GatherParams P, int pass) {
+  __shared__ unsigned hist_sh[256];
+  __shared__ RadixShared radix_sh;
+  const SplitCtx x = split_ctx(P);
+  if (split_idle(x)) return;
+  unsigned kreg[kSplitKeys];
+  split_load_keys(P, x, kreg);
+  unsigned prefix, mask, need;
+  split_prefix(x, pass, radix_sh, prefix, mask, need);
+  split_add_hist(x, kreg, pass, prefix, mask, hist_sh);
+}
+
+__global__ __launch_bounds__(kSelThreads) void split_count(const GatherParams P) {
+  __shared__ RadixShared radix_sh;
+  __shared__ unsigned cnt_sh[2];
+  const SplitCtx x = split_ctx(P);
+  if (split_idle(x)) return;
+  const int tid = threadIdx.x;
+  if (tid < 2) cnt_sh[tid] = 0u;
+  unsigned kreg[kSplitKeys];
+  split_load_keys(P, x, kreg);
+  unsigned thr, mask, need;
+  split_prefix(x, 4, radix_sh, thr, mask, need);      // has barriers: cnt_sh is zero for everyone
+  unsigned gt = 0, eq = 0;
+#pragma unroll
+  for (int i = 0; i < kSplitKeys; ++i)
+    if (i * kSelThreads + tid < x.n) {
+      gt += kreg[i] > thr;
+      eq += kreg[i] == thr;
+    }
+  if (gt) atomicAdd(&cnt_sh[0], gt);
+  if (eq) atomicAdd(&cnt_sh[1], eq);
+  __syncthreads();
+  if (tid == 0) {
+    x.st[4 * 256 + 2 + 2 * x.c] = cnt_sh[0];
+    x.st[4 * 256 + 2 + 2 * x.c + 1] = cnt_sh[1];
+    if (x.c == 0) {
+      x.st[4 * 256] = thr;
+      x.st[4 * 256 + 1] = need;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kSelThreads) void split_write(const GatherParams P) {
+  __shared__ int eq_sh[kSplitKeys * kSelWaves], keep_sh[kSplitKeys * kSelWaves];
+  __shared__ int tot_sh[kSelWaves + 1];
+  const SplitCtx x = split_ctx(P);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  int32_t* idx = P.idx + x.u * x.t;
+  if (x.c == 0)
+    for (int r = tid; r < P.ows; r += kSelThreads) idx[max(x.kc, 0) + r] = x.tc + r;
+  if (x.n <= 0 || x.kc <= 0) return;
+  if (x.kc >= x.tc) {                               // every candidate stays
+    for (int jl = tid; jl < x.n; jl += kSelThreads) idx[x.first + jl] = x.first + jl;
+    return;
+  }
+  unsigned kreg[kSplitKeys];
+  split_load_keys(P, x, kreg);
+  const unsigned thr = x.st[4 * 256];
+  const int need = static_cast<int>(x.st[4 * 256 + 1]);
+  // Ranks at the start of this chunk, from the counts of the chunks before it.
+  int eq_before = 0, keep_before = 0;
+  for (int cc = 0; cc < x.c; ++cc) {
+    const int gt = static_cast<int>(x.st[4 * 256 + 2 + 2 * cc]);
+    const int eq = static_cast<int>(x.st[4 * 256 + 2 + 2 * cc + 1]);
+    keep_before += gt + min(max(need - eq_before, 0), eq);
+    eq_before += eq;
+  }
+  const int rows = (x.n + kSelThreads - 1) / kSelThreads;
+#pragma unroll
+  for (int i = 0; i < kSplitKeys; ++i)
+    if (i < rows) {
+      const bool is_eq = i * kSelThreads + tid < x.n && kreg[i] == thr;
+      const unsigned long long v_eq = __ballot(is_eq);
+      if (lane == 0) eq_sh[i * kSelWaves + wave] = __popcll(v_eq);
+    }
+  block_exclusive_scan<kSelThreads>(eq_sh, rows * kSelWaves, tot_sh);
+  auto kept = [&](int i) -> bool {
+    const bool live = i * kSelThreads + tid < x.n;
+    const bool is_eq = live && kreg[i] == thr;
+    const unsigned long long v_eq = __ballot(is_eq);
+    const int eq_rank = eq_before + eq_sh[i * kSelWaves + wave] + rank_in_wave(v_eq);
+    return live && (kreg[i] > thr || (is_eq && eq_rank < need));
+  };
+#pragma unroll
+  for (int i = 0; i < kSplitKeys; ++i)
+    if (i < rows) {
+      const unsigned long long v_k = __ballot(kept(i));
+      if (lane == 0) keep_sh[i * kSelWaves + wave] = __popcll(v_k);
+    }
+  block_exclusive_scan<kSelThreads>(keep_sh, rows * kSelWaves, tot_sh);
+#pragma unroll
+  for (int i = 0; i < kSplitKeys; ++i)
+    if (i < rows) {
+      const bool keep = kept(i);
+      const unsigned long long v_k = __ballot(keep);
+      if (keep)
+        idx[keep_before + keep_sh[i * kSelWaves + wave] + rank_in_wave(v_k)] = x.first + i * kSelThreads + tid;
+    }
+}
+
 // EvictByIndex as a gather: workgroup (chunk, stream) copies kept tokens
 // [256 chunk, 256 chunk + 256) of the stream; a wave moves four rows of up to
 // 256 bytes per instruction.
@@ -489,7 +716,7 @@ bool pick_window(int dtype, int head_dim, int nb, WindowFn* stats, WindowFn* mas
 
 // Workspace layout for `streams` streams of t tokens; every part starts on a
 // 256-byte boundary.  Returns the total; the offsets are in bytes.
-struct PrefillLayout { size_t stats, fin, w, keys, idx, total; };
+struct PrefillLayout { size_t stats, fin, w, keys, idx, split, total; };
 
 size_t round256(size_t b) { return (b + 255) / 256 * 256; }
 
@@ -509,6 +736,7 @@ PrefillLayout prefill_layout(int64_t streams, int t, int nq_pad, bool own_w, boo
   L.w = off;     off += own_w ? round256(static_cast<size_t>(streams) * t * sizeof(float)) : 0;
   L.keys = off;  off += pooled ? round256(static_cast<size_t>(streams) * t * sizeof(uint32_t)) : 0;
   L.idx = off;   off += round256(static_cast<size_t>(streams) * t * sizeof(int32_t));
+  L.split = off; off += round256(static_cast<size_t>(streams) * kSplitWords * sizeof(unsigned));
   L.total = off;
   return L;
 }
@@ -657,7 +885,9 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
   if (streams * ceil_div(t, prefill_strip_rows(streams, t)) > std::numeric_limits<int32_t>::max())
     return XKV_ERR_UNSUPPORTED;
   const bool pooled = pool_size > 1;
-  const PrefillLayout L = prefill_layout(streams, t, nb * 16, w_out == nullptr, pooled);
+  // Few long streams: the selection of a stream is split over several workgroups.
+  const bool use_split = streams < 256 && t - ows >= 4 * kSplitChunk && pool_size <= 63;
+  const PrefillLayout L = prefill_layout(streams, t, nb * 16, w_out == nullptr, pooled || use_split);
   if (workspace == nullptr || L.total > workspace_bytes) return XKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return XKV_ERR_INVALID_ARG;
 
@@ -675,6 +905,7 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
   Gp.w = w_dense;
   Gp.keys = reinterpret_cast<uint32_t*>(ws + L.keys);
   Gp.idx = reinterpret_cast<int32_t*>(ws + L.idx);
+  Gp.split = reinterpret_cast<unsigned*>(ws + L.split);
   Gp.t = t; Gp.ows = ows; Gp.pool = pool_size; Gp.n_kv_heads = hkv;
   Gp.row_bytes = D * (cache->dtype == XKV_F32 ? 4 : 2);
   for (int64_t g0 = 0; g0 < n_pairs; g0 += kMaxPairs) {
@@ -690,22 +921,33 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
     }
     Gp.stream0 = static_cast<int32_t>(g0 * hkv);
     const int tc = t - ows;
-    auto select_fn = tc <= 8 * kSelThreads ? prefill_select<8>
-                     : tc <= kMaxKeyRegs * kSelThreads ? prefill_select<kMaxKeyRegs> : prefill_select<0>;
-    size_t select_lds = 0;
-    if (pooled && tc <= kMaxKeyRegs * kSelThreads) {
-      select_lds = static_cast<size_t>(tc + pool_size) * sizeof(float);
-      if (select_lds > 48 * 1024 &&
-          hipFuncSetAttribute(reinterpret_cast<const void*>(select_fn),
-                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                              static_cast<int>(select_lds)) != hipSuccess) {
-        (void)hipGetLastError();
-        return XKV_ERR_DEVICE;
+    const unsigned n_streams = static_cast<unsigned>(np * hkv);
+    if (use_split) {
+      const dim3 grid(static_cast<unsigned>(ceil_div(tc, kSplitChunk)), n_streams);
+      hipLaunchKernelGGL(split_zero, dim3(n_streams), dim3(kThreads), 0, stream, Gp);
+      hipLaunchKernelGGL(split_keys, grid, dim3(kSelThreads), 0, stream, Gp);
+      for (int pass = 1; pass < 4; ++pass)
+        hipLaunchKernelGGL(split_hist, grid, dim3(kSelThreads), 0, stream, Gp, pass);
+      hipLaunchKernelGGL(split_count, grid, dim3(kSelThreads), 0, stream, Gp);
+      hipLaunchKernelGGL(split_write, grid, dim3(kSelThreads), 0, stream, Gp);
+      if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+    } else {
+      auto select_fn = tc <= 8 * kSelThreads ? prefill_select<8>
+                       : tc <= kMaxKeyRegs * kSelThreads ? prefill_select<kMaxKeyRegs> : prefill_select<0>;
+      size_t select_lds = 0;
+      if (pooled && tc <= kMaxKeyRegs * kSelThreads) {
+        select_lds = static_cast<size_t>(tc + pool_size) * sizeof(float);
+        if (select_lds > 48 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(select_fn),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                static_cast<int>(select_lds)) != hipSuccess) {
+          (void)hipGetLastError();
+          return XKV_ERR_DEVICE;
+        }
       }
+      hipLaunchKernelGGL(select_fn, dim3(n_streams), dim3(kSelThreads), select_lds, stream, Gp);
+      if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     }
-    hipLaunchKernelGGL(select_fn, dim3(static_cast<unsigned>(np * hkv)), dim3(kSelThreads), select_lds,
-                       stream, Gp);
-    if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     hipLaunchKernelGGL(prefill_gather,
                        dim3(static_cast<unsigned>(ceil_div(kmax, kThreads)), static_cast<unsigned>(np * hkv)),
                        dim3(kThreads), 0, stream, Gp);

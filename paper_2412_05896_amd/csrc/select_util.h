@@ -22,6 +22,44 @@ __device__ __forceinline__ int rank_in_wave(unsigned long long vote) {
                                    __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(vote), 0));
 }
 
+// One digit of a radix select: given the 256 counts of the current digit
+// (`hist`, LDS or global), finds the bin in which the running count, from the
+// top bin down, reaches `need`, and how many of that bin's keys are still
+// needed.  Thread t < 256 takes bin 255 - t and an inclusive scan over t locates
+// the bin.  Every thread of the workgroup (at least 256 threads) must call it;
+// begins and ends with a barrier.
+__device__ __forceinline__ void radix_pick_bin(const unsigned* hist, unsigned need, RadixShared& sh,
+                                               unsigned& bin, unsigned& need_out) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  __syncthreads();
+  unsigned cnt = 0, incl = 0;
+  if (tid < 256) {
+    cnt = hist[255 - tid];
+    incl = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const unsigned y = __shfl_up(incl, off);
+      if (lane >= off) incl += y;
+    }
+    if (lane == 63) sh.scan[wave] = static_cast<int>(incl);
+  }
+  __syncthreads();
+  if (tid < 256) {
+    for (int w = 0; w < wave; ++w) incl += static_cast<unsigned>(sh.scan[w]);
+    const unsigned before = incl - cnt;
+    if (before < need && need <= incl) {
+      sh.sel_bin = 255u - static_cast<unsigned>(tid);
+      sh.sel_need = need - before;
+    }
+  }
+  __syncthreads();
+  bin = sh.sel_bin;
+  need_out = sh.sel_need;
+  __syncthreads();
+}
+
 // The kk-th largest of the workgroup's keys, 1 <= kk <= number of keys, compared
 // as unsigned integers (for non-negative floats that is the float order): four
 // passes over 8 bits each, every pass a 256-bin histogram of the keys that
@@ -37,8 +75,6 @@ template <typename ForEachKey>
 __device__ __forceinline__ void radix_select(ForEachKey for_each_key, int kk, RadixShared& sh,
                                              unsigned& thr, unsigned& need) {
   const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
   unsigned prefix = 0, mask = 0;
   need = static_cast<unsigned>(kk);
   for (int shift = 24; shift >= 0; shift -= 8) {
@@ -58,33 +94,10 @@ __device__ __forceinline__ void radix_select(ForEachKey for_each_key, int kk, Ra
     });
     if (run_len != 0) atomicAdd(&sh.hist[run_bin], run_len);
     __syncthreads();
-    // Thread t < 256 takes bin 255 - t; an inclusive scan over t finds the bin
-    // in which the running count, from the top, reaches `need`.
-    unsigned cnt = 0, incl = 0;
-    if (tid < 256) {
-      cnt = sh.hist[255 - tid];
-      incl = cnt;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const unsigned y = __shfl_up(incl, off);
-        if (lane >= off) incl += y;
-      }
-      if (lane == 63) sh.scan[wave] = static_cast<int>(incl);
-    }
-    __syncthreads();
-    if (tid < 256) {
-      for (int w = 0; w < wave; ++w) incl += static_cast<unsigned>(sh.scan[w]);
-      const unsigned before = incl - cnt;
-      if (before < need && need <= incl) {
-        sh.sel_bin = 255u - static_cast<unsigned>(tid);
-        sh.sel_need = need - before;
-      }
-    }
-    __syncthreads();
-    prefix |= sh.sel_bin << shift;
+    unsigned bin;
+    radix_pick_bin(sh.hist, need, sh, bin, need);
+    prefix |= bin << shift;
     mask |= 255u << shift;
-    need = sh.sel_need;
-    __syncthreads();
   }
   thr = prefix;
 }

@@ -165,3 +165,33 @@ def test_full_size_layer_of_the_128k_gqa_workload(xkv):
     units = {(0, 0, 0), (0, 1, 7), (0, 0, 5)}
     e = run_prefill(xkv, "bf16", 128, 64, 8, 1, 2, 131072, 8, 7, [[19661, 256]], seed=32, check_units=units)
     print("128k layer w rel err", e, flush=True)
+
+
+@pytest.mark.parametrize("ps", [1, 5])
+def test_long_stream_selection_split_over_workgroups_with_bulk_ties(xkv, ps):
+    """Few long streams take the selection that is split over several workgroups.  Equal keys
+    everywhere make every candidate tie, across the workgroups' chunks too: the kept ones must be
+    the first.  (With pooling the two ends of the candidate vector have smaller keys.)"""
+    t, ows, d, budget = 40005, 4, 64, 20004
+    cache = xkv.XkvCache(1, 1, 1, 1, d, "f32", [[budget + 4]])
+    k_src = torch.ones((1, 1, 1, t, d), device="cuda")
+    v_src = torch.randn((1, 1, 1, t, d), device="cuda")
+    q_win = torch.randn((1, 1, 1, ows, d), device="cuda")
+    ws = torch.empty(xkv.xkv_prefill_workspace_bytes(cache, 1, t, ows), dtype=torch.uint8, device="cuda")
+    w_out = torch.empty((1, 1, 1, t), dtype=torch.float32, device="cuda")
+    xkv.xkv_prefill_evict(cache, 0, 1, q_win, k_src, v_src, t, ows, np.array([[budget]], np.int32), ws,
+                          pool_size=ps, w_out=w_out)
+    torch.cuda.synchronize()
+    K2, V2, s2, p2 = get_unit(cache, 0, 0, 0)
+    wd = w_out.cpu().numpy()[0, 0, 0]
+    ref = orc.prefill_select(wd, ows, budget, ps)
+    assert np.array_equal(p2, ref)
+    half = ps // 2
+    assert p2[0] == half and p2[budget - ows - 1] == half + budget - ows - 1     # a prefix, after the weak edge
+    assert np.array_equal(V2, storage(v_src[0, 0, 0])[p2])
+
+
+def test_long_streams_split_selection_random_scores(xkv):
+    o = run_prefill(xkv, "bf16", 128, 4, 2, 1, 2, 50003, 8, 7, [[12345, 49000]], seed=41)
+    print("split selection w rel err", o, flush=True)
+    run_prefill(xkv, "f32", 64, 2, 2, 1, 1, 33000, 8, 1, [[8]], seed=42)        # window only
