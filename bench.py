@@ -41,6 +41,8 @@ def parse():
                     help="decode steps between evictions (1 = every step; 8 = once per observation window)")
     ap.add_argument("--n-protect", type=int, default=0, help="most recent tokens that are never evicted")
     ap.add_argument("--pool-size", type=int, default=1, help="pooling width of the eviction keys (odd)")
+    ap.add_argument("--attend-path", type=int, default=0,
+                    help="0 library's choice, 1 streaming + finalize kernels, 2 fused cooperative launch")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill-phase eviction leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of 1 GiB x 10 (reference point for HBM byte counters)")
@@ -145,6 +147,7 @@ def main():
     import xkv_workloads as wl
 
     xkv.load()
+    xkv.xkv_configure(xkv.XKV_CFG_ATTEND_PATH, args.attend_path)
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
@@ -365,7 +368,7 @@ def main():
                    "budget_min": int(budgets.min()), "budget_max": int(budgets.max()),
                    "schedule": "every step, every layer: append, attend+score" +
                                (", evict to budget" if every == 1 else f"; every {every} steps: evict to budget"),
-                   "pool_size": args.pool_size, "n_protect": args.n_protect,
+                   "pool_size": args.pool_size, "n_protect": args.n_protect, "attend_path": args.attend_path,
                    "arena": "prompt-sized" if args.keep_prompt_arena or W == 0 else "budget-sized after the first eviction",
                    "kv_arena_bytes": int(2 * cache.arena_slots * w.head_dim * w.elem_bytes),
                    "steady_state": steady},

@@ -1,0 +1,75 @@
+"""A steady-state decode step (append + attention/scoring + eviction) captured in a HIP graph:
+the library launches on the capturing stream, copies nothing from the host and records no memset
+nodes, so replays must reproduce the eager result bit for bit, also with eager work in between."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import random_fill
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype,d,Hq,Hkv", [("bf16", 128, 4, 4), ("bf16", 128, 8, 2), ("f32", 64, 4, 4)])
+def test_captured_step_replays_like_eager(xkv, dtype, d, Hq, Hkv):
+    L, B = 3, 2
+    budgets = np.array([[700, 300], [64, 1500], [256, 257]], np.int32)
+    caps = budgets + 8
+
+    def fresh():
+        cache = xkv.XkvCache(L, B, Hq, Hkv, d, dtype, caps)
+        random_fill(cache, budgets, seed=5)
+        return cache
+
+    g = torch.Generator(device="cpu").manual_seed(9)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    steps = 4
+    qs = torch.randn((steps, L, B, Hq, d), generator=g).to(tdt).cuda()
+    kns = torch.randn((steps, L, B, Hkv, d), generator=g).to(tdt).cuda()
+    vns = torch.randn((steps, L, B, Hkv, d), generator=g).to(tdt).cuda()
+    pos_new = np.array([9000, 9001], np.int32)
+
+    # eager reference: the state after every step
+    ref = fresh()
+    ws_ref = torch.empty(xkv.xkv_workspace_bytes(ref, L), dtype=torch.uint8, device="cuda")
+    out_ref = torch.empty((L, B, Hq, d), dtype=torch.float32, device="cuda")
+    states = []
+    for s in range(steps):
+        xkv.xkv_decode_attend_score(ref, 0, L, qs[s], kns[s], vns[s], pos_new, out_ref, ws_ref)
+        xkv.xkv_evict_compact(ref, 0, L, budgets, ws_ref)
+        torch.cuda.synchronize()
+        states.append((out_ref.clone(), ref.k.clone(), ref.score.clone(), ref.pos.clone()))
+
+    # captured: static input buffers, one graph, replayed once per step
+    cache = fresh()
+    ws = torch.empty(xkv.xkv_workspace_bytes(cache, L), dtype=torch.uint8, device="cuda")
+    out = torch.empty((L, B, Hq, d), dtype=torch.float32, device="cuda")
+    q, kn, vn = qs[0].clone(), kns[0].clone(), vns[0].clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    snapshot = (cache.k.clone(), cache.v.clone(), cache.score.clone(), cache.pos.clone())
+    with torch.cuda.stream(side):
+        # warm-up launch outside the capture (loads the code objects), then restore the state
+        xkv.xkv_decode_attend_score(cache, 0, L, q, kn, vn, pos_new, out, ws, stream=side)
+        xkv.xkv_evict_compact(cache, 0, L, budgets, ws, stream=side)
+        side.synchronize()
+        for dst, src in zip((cache.k, cache.v, cache.score, cache.pos), snapshot):
+            dst.copy_(src)
+        side.synchronize()
+        assert np.array_equal(cache.len.reshape(L, B), budgets)       # the step returns to its lengths
+        with torch.cuda.graph(graph, stream=side):
+            xkv.xkv_decode_attend_score(cache, 0, L, q, kn, vn, pos_new, out, ws, stream=side)
+            xkv.xkv_evict_compact(cache, 0, L, budgets, ws, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    assert np.array_equal(cache.len.reshape(L, B), budgets)
+    for s in range(steps):
+        q.copy_(qs[s]); kn.copy_(kns[s]); vn.copy_(vns[s])
+        graph.replay()
+        torch.cuda.synchronize()
+        # eager work between replays
+        junk = (torch.randn(1 << 16, device="cuda") * 2).sum().item()
+        assert np.isfinite(junk)
+        o, k, sc, ps = states[s]
+        assert torch.equal(out, o), f"replay {s}: output"
+        assert torch.equal(cache.k, k) and torch.equal(cache.score, sc) and torch.equal(cache.pos, ps), f"replay {s}: cache"
