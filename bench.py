@@ -43,6 +43,7 @@ def parse():
     ap.add_argument("--pool-size", type=int, default=1, help="pooling width of the eviction keys (odd)")
     ap.add_argument("--attend-path", type=int, default=0,
                     help="0 library's choice, 1 streaming + finalize kernels, 2 fused cooperative launch")
+    ap.add_argument("--no-graph", action="store_true", help="skip the graph-replay figure")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill-phase eviction leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of 1 GiB x 10 (reference point for HBM byte counters)")
@@ -270,6 +271,31 @@ def main():
                     "launches_per_step": launches_per_step, "algorithmic_bytes_per_launch": bytes_per_launch,
                     "evict_select_avg_ms": (sel_ms / sel_launches) if sel_launches else None}
 
+    # The same step captured once in a HIP graph and replayed (extra figure, not `value`: every
+    # replay appends the captured step's token and position again).
+    graph_ms = None
+    if every == 1 and not args.no_graph:
+        note("graph replay")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        gr = torch.cuda.CUDAGraph()
+        i = t % gen_steps
+        pos_step[:] = w.context + t
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(gr, stream=side):
+                xkv.xkv_decode_attend_score(cache, 0, L, q[i], kn[i], vn[i], pos_step, out, ws, stream=side)
+                xkv.xkv_evict_compact(cache, 0, L, budgets, ws, pool_size=args.pool_size,
+                                      n_protect=args.n_protect, stream=side)
+        torch.cuda.current_stream().wait_stream(side)
+        gr.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            gr.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) / K * 1e3
+        del gr
+
     # What a read-only kernel of the same shape reaches on this machine (context for the roofline fraction).
     ceiling = None
     if not args.no_roofline_pass:
@@ -372,7 +398,7 @@ def main():
                    "arena": "prompt-sized" if args.keep_prompt_arena or W == 0 else "budget-sized after the first eviction",
                    "kv_arena_bytes": int(2 * cache.arena_slots * w.head_dim * w.elem_bytes),
                    "steady_state": steady},
-        "step0_ms": step0_ms,
+        "step0_ms": step0_ms, "graph_replay_ms_per_step": graph_ms,
         "algorithmic_bytes_per_step": alg_bytes_timed / K,
         "step_hbm_gbs": step_gbs, "step_hbm_frac": step_gbs / HBM_PEAK_GBS,
         "roofline": roofline, "stream_read_ceiling": ceiling, "prefill_evict": prefill, "cpu_baseline": cpu,
