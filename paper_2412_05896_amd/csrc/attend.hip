@@ -994,8 +994,8 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const AttendParams P) {
     __builtin_amdgcn_wave_barrier();
     if (4 * lane < kTile * G) {
       const floatx4 lg = *reinterpret_cast<const floatx4*>(&lg_sh[wave][4 * lane]);
-      __builtin_nontemporal_store(
-          lg, reinterpret_cast<floatx4*>(rec + static_cast<int64_t>(row0 - r_begin) * G + 4 * lane));
+      const float lgv[4] = {lg[0], lg[1], lg[2], lg[3]};
+      store_stream16(rec + static_cast<int64_t>(row0 - r_begin) * G + 4 * lane, lgv);
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -1133,7 +1133,10 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P
     }
     const int row = r_begin + j;
     const float old = (P.append && row == n - 1) ? 0.0f : score[row];
-    score[row] = old + add;
+    // With several launches per call (the GQA workloads) scores left dirty in L2 are
+    // written back under the next launch's K/V stream: there they are written through.
+    if constexpr (kByRow) store_stream(&score[row], old + add);
+    else score[row] = old + add;
   }
   if (P.append && f_own == 0 && tid == 0) P.pos[stream_slot + n - 1] = P.pos_new[lo];
 
