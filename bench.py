@@ -302,15 +302,20 @@ def main():
         buf = cache.k
         per_wg = 128 * 1024
         nbytes = buf.numel() * buf.element_size() // per_wg * per_wg
-        sink = torch.empty((nbytes // per_wg) * 386, dtype=torch.float32, device="cuda")
+        sink = torch.empty((nbytes // per_wg) * 1024, dtype=torch.float32, device="cuda")
         ceiling = {"bytes_per_launch": nbytes}
-        for tag, nt, st in (("non_temporal_GBs", True, 0), ("ordinary_loads_GBs", False, 0),
-                            ("non_temporal_with_1544B_record_store_per_128KiB_GBs", True, 386)):
+        # loads: non-temporal or ordinary; then non-temporal loads with 1.5 KB (a strip record) or 4 KB
+        # (the logits of 256 slots at G = 4) stored per 128 KiB read, under the three store policies
+        cases = [("non_temporal_GBs", True, 0, 2), ("ordinary_loads_GBs", False, 0, 2)]
+        for fl, label in ((386, "1544B"), (1024, "4096B")):
+            for pol, pname in ((0, "ordinary"), (1, "non_temporal"), (2, "system_scope")):
+                cases.append((f"non_temporal_with_{label}_{pname}_store_per_128KiB_GBs", True, fl, pol))
+        for tag, nt, st, pol in cases:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            xkv.xkv_probe_stream_read(buf, nt, st, sink, stream=stream)
+            xkv.xkv_probe_stream_read(buf, nt, st, sink, stream=stream, store_policy=pol)
             e0.record(stream)
             for _ in range(20):
-                xkv.xkv_probe_stream_read(buf, nt, st, sink, stream=stream)
+                xkv.xkv_probe_stream_read(buf, nt, st, sink, stream=stream, store_policy=pol)
             e1.record(stream)
             torch.cuda.synchronize()
             ceiling[tag] = nbytes * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e9

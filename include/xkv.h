@@ -321,12 +321,15 @@ xkv_status xkv_profile_read(int32_t kernel_index, int64_t* launches_out, double*
  * in the shape of the attention kernels' K/V read (256-thread workgroups, 128 KiB
  * each, 16-byte loads), with non-temporal loads or ordinary ones, and writes
  * store_floats_per_workgroup floats per workgroup to the DEVICE array `sink`
- * (which must hold that many floats per 128 KiB read, and at least one).  The
- * buffer should not consist of words whose XOR is 0x9e3779b9.
+ * (which must hold that many floats per 128 KiB read, and at least one) with
+ * store_policy 0 = ordinary stores, 1 = non-temporal stores, 2 = the stores the
+ * library uses for its workspace (system scope, written through).  The buffer
+ * should not consist of words whose XOR is 0x9e3779b9.
  * The caller times it.  Errors: INVALID_ARG, DEVICE.
  */
 xkv_status xkv_probe_stream_read(const void* buffer, size_t bytes, int32_t non_temporal,
-                                 int32_t store_floats_per_workgroup, float* sink, void* hip_stream);
+                                 int32_t store_floats_per_workgroup, int32_t store_policy,
+                                 float* sink, void* hip_stream);
 
 #ifdef __cplusplus
 }

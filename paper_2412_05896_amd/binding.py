@@ -94,7 +94,8 @@ def load():
     lib.xkv_configure.restype = C.c_int32
     lib.xkv_configure.argtypes = [C.c_int32, C.c_int64]
     lib.xkv_probe_stream_read.restype = C.c_int32
-    lib.xkv_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.xkv_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                          C.c_void_p]
     lib.xkv_profile_enable.restype = C.c_int32
     lib.xkv_profile_enable.argtypes = [C.c_int32]
     lib.xkv_profile_read.restype = C.c_int32
@@ -321,11 +322,12 @@ def xkv_configure(key: int, value: int):
 
 
 def xkv_probe_stream_read(buffer, non_temporal: bool, store_floats_per_workgroup: int = 0, sink=None,
-                          stream=None):
+                          stream=None, store_policy: int = 2):
     """One launch of the read-only streaming kernel over a torch device tensor."""
     _check(load().xkv_probe_stream_read(_ptr(buffer), buffer.numel() * buffer.element_size(),
                                         1 if non_temporal else 0, int(store_floats_per_workgroup),
-                                        _ptr(sink), _stream_handle(stream)), "xkv_probe_stream_read")
+                                        int(store_policy), _ptr(sink), _stream_handle(stream)),
+           "xkv_probe_stream_read")
 
 
 def xkv_profile_enable(on: bool):
