@@ -89,9 +89,11 @@ def algorithmic_bytes(w, lens_after_append):
     return int(lens_after_append.astype("int64").sum()) * w.n_kv_heads * per_token
 
 
-def cpu_baseline(w, wl, cache, budgets, q, kn, vn, pos_new, seconds):
-    """The oracle, as it stands, on a seeded sample of units of one steady-state
-    step (append + attention/scoring + eviction), one thread."""
+def cpu_baseline(w, wl, cache, budgets, inputs, t, seconds):
+    """The oracle, as it stands, on a seeded sample of units of steady-state steps
+    (append + attention/scoring + eviction), one thread.  Every unit is taken from
+    the cache as it stands; when all units of a step have been done before the time
+    is up, the next pass uses the next step's queries and new tokens."""
     import numpy as np
     from oracle import xkv_oracle as orc
     try:
@@ -99,31 +101,36 @@ def cpu_baseline(w, wl, cache, budgets, q, kn, vn, pos_new, seconds):
         limiter = threadpool_limits(limits=1)
     except Exception:                                   # pragma: no cover
         limiter = None
+    q_all, kn_all, vn_all, gen_steps = inputs
     G = w.group
     units = [(l, b, h) for l in range(w.n_layers) for b in range(w.batch) for h in range(w.n_kv_heads)]
     order = np.random.default_rng(w.seed).permutation(len(units))
-    spent, done, tokens = 0.0, 0, 0
-    for idx in order:
-        l, b, h = units[idx]
-        n = cache.length(l, b)
-        s0 = cache.stream_slot(l, b, h)
-        K = wl.to_numpy_storage(cache.k[s0:s0 + n])
-        V = wl.to_numpy_storage(cache.v[s0:s0 + n])
-        sc = cache.score[s0:s0 + n].cpu().numpy()
-        ps = cache.pos[s0:s0 + n].cpu().numpy()
-        qq = wl.to_numpy_storage(q[l, b, h * G:(h + 1) * G])
-        kk = wl.to_numpy_storage(kn[l, b, h])
-        vv = wl.to_numpy_storage(vn[l, b, h])
-        t0 = time.perf_counter()
-        u = orc.OracleUnit(K, V, sc, ps)
-        u.append(kk, vv, int(pos_new[b]))
-        u.attend(qq)
-        u.evict(int(budgets[l, b]))
-        spent += time.perf_counter() - t0
-        done += 1
-        tokens += n + 1
-        if spent >= seconds:
-            break
+    spent, done, tokens, passes = 0.0, 0, 0, 0
+    while spent < seconds:
+        i = (t + passes) % gen_steps
+        q, kn, vn = q_all[i], kn_all[i], vn_all[i]
+        for idx in order:
+            l, b, h = units[idx]
+            n = cache.length(l, b)
+            s0 = cache.stream_slot(l, b, h)
+            K = wl.to_numpy_storage(cache.k[s0:s0 + n])
+            V = wl.to_numpy_storage(cache.v[s0:s0 + n])
+            sc = cache.score[s0:s0 + n].cpu().numpy()
+            ps = cache.pos[s0:s0 + n].cpu().numpy()
+            qq = wl.to_numpy_storage(q[l, b, h * G:(h + 1) * G])
+            kk = wl.to_numpy_storage(kn[l, b, h])
+            vv = wl.to_numpy_storage(vn[l, b, h])
+            t0 = time.perf_counter()
+            u = orc.OracleUnit(K, V, sc, ps)
+            u.append(kk, vv, w.context + t + passes)
+            u.attend(qq)
+            u.evict(int(budgets[l, b]))
+            spent += time.perf_counter() - t0
+            done += 1
+            tokens += n + 1
+            if spent >= seconds:
+                break
+        passes += 1
     if limiter is not None:
         limiter.restore_original_limits() if hasattr(limiter, "restore_original_limits") else None
     units_per_layer_step = w.batch * w.n_kv_heads
@@ -131,7 +138,8 @@ def cpu_baseline(w, wl, cache, budgets, q, kn, vn, pos_new, seconds):
     mean_tokens_per_layer_step = float((budgets.astype("int64") + 1).sum()) * w.n_kv_heads / w.n_layers
     rate = (tokens / spent) / mean_tokens_per_layer_step
     return {"value": rate, "unit": "layer-steps/s", "cores": 1, "kind": "oracle",
-            "sample": f"{done} of {len(units)} (layer, sequence, KV-head) units of one steady-state step, "
+            "sample": f"{done} (layer, sequence, KV-head) unit-steps ({len(units)} units per step, "
+                      f"{passes} pass(es) with successive decode inputs), "
                       f"{spent:.1f} s of NumPy float64 on one thread, extrapolated by token count "
                       f"({units_per_layer_step} units per layer-step)"}
 
@@ -361,9 +369,7 @@ def main():
     cpu = None
     if args.cpu_seconds > 0:
         note("oracle on the host cores")
-        i = t % gen_steps
-        pos_step[:] = w.context + t
-        cpu = cpu_baseline(w, wl, cache, budgets, q[i], kn[i], vn[i], pos_step, args.cpu_seconds)
+        cpu = cpu_baseline(w, wl, cache, budgets, (q, kn, vn, gen_steps), t, args.cpu_seconds)
 
     allocator = None
     if alloc:
