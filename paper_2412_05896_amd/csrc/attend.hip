@@ -1233,9 +1233,9 @@ int choose_strip_rows(int max_rows, int64_t streams, int64_t total_rows) {
 constexpr size_t kFusedLdsBudget = 72 * 1024;   // logits per workgroup; two workgroups share a compute unit
 
 int g_attend_path = 0;                          // 0 auto, 1 two kernels, 2 fused or error
-// What "auto" picks.  On the 32k benchmark workload the fused launch and the two
-// kernels currently take the same time within 2 %, the two kernels being the
-// simpler path; the fused launch stays selectable.
+// What "auto" picks.  On the 32k benchmark workload the fused launch is 5 % slower
+// than the two kernels (its grid barrier and second phase cost more than the logit
+// stores it saves), and its larger query groups run on the VALUs; it stays selectable.
 constexpr bool kAutoPrefersFused = false;
 
 int compute_units() {
