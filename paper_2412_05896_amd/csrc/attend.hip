@@ -1114,7 +1114,7 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P
   const int r_begin = s_begin << shift;
   const int rows = min(n, (s_begin + F) << shift) - r_begin;
   const float* lg0 = rec0 + static_cast<int64_t>(s_begin) * REC;
-#pragma unroll 4
+#pragma unroll 8
   for (int j = tid; j < rows; j += kThreads) {
     const int js = j & (strip_rows - 1);
     const float* lg = lg0 + static_cast<int64_t>(j >> shift) * REC + (kByRow ? js * G : js);
