@@ -89,14 +89,15 @@ __device__ __forceinline__ void merge_ml(float& m, float& l, float m2, float l2)
 //   kPhase 0  window_stats: per-strip (max, sum) of every query row
 //   kPhase 1  window_mass:  w[j] = sum over query rows of 2^(s - max) / sum
 // Workgroup = (stream, strip); its waves take the strip's groups of 16 rows in
-// turn.  Lane (j, x): operand loads are 16 bytes at offset 64 sl + 16 j of K row
-// x of the group and of query row 16 nb + x; the result has the logit of
+// turn.  Lane (j, x): an operand is 16 bytes at offset 64 sl + 16 j of K row x of
+// the group and of query row 16 nb + x; the result has the logit of
 // (row 4 j + i, query row 16 nb + x) in register i.
 template <typename T, int D, int NB, int kPhase>
 __global__ __launch_bounds__(kThreads) void window_pass(const WindowParams P) {
   constexpr int ROWB = D * T::kBytes;
   constexpr int NSL = ROWB / 64;
   __shared__ float ml_sh[kWaves][NB * 16][2];
+  __shared__ __attribute__((aligned(16))) char tile_sh[kWaves][2][16 * (ROWB + 16)];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -142,15 +143,32 @@ __global__ __launch_bounds__(kThreads) void window_pass(const WindowParams P) {
   for (int nb = 0; nb < NB; ++nb) { m_run[nb] = -INFINITY; l_run[nb] = 0.0f; }
 
   const int groups = (r_end - r_begin + 15) / 16;
+  // A group's 16 K rows are read as whole rows (lane (rr, cx): 16 bytes at column cx of
+  // row i * RPI + rr for load i) and turned into the operand layout (row x, 16 bytes at
+  // column 4 sl + j) through a per-wave LDS tile with padded rows.
+  constexpr int LPR = ROWB / 16, RPI = 64 / LPR, kPitch = ROWB + 16;
+  const int rr = lane / LPR, cx = lane % LPR;
   auto load_group = [&](uint4 (&kreg)[NSL], int gi) {
-    const int row = r_begin + gi * 16 + x;
-    const int rc = row < t ? row : t - 1;           // rows past the end repeat the last one, masked below
-    const char* src = kbase + static_cast<int64_t>(rc) * ROWB + j * 16;
 #pragma unroll
-    for (int sl = 0; sl < NSL; ++sl) kreg[sl] = load_stream16(src + sl * 64);
+    for (int i = 0; i < NSL; ++i) {
+      const int row = r_begin + gi * 16 + i * RPI + rr;
+      const int rc = row < t ? row : t - 1;         // rows past the end repeat the last one, masked below
+      kreg[i] = load_stream16(kbase + static_cast<int64_t>(rc) * ROWB + cx * 16);
+    }
   };
-  auto use_group = [&](const uint4 (&kreg)[NSL], int gi) {
+  auto use_group = [&](const uint4 (&kraw)[NSL], int gi, char* tile) {
     const int g0 = r_begin + gi * 16;
+#pragma unroll
+    for (int i = 0; i < NSL; ++i)
+      *reinterpret_cast<uint4*>(tile + (i * RPI + rr) * kPitch + cx * 16) = kraw[i];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    uint4 kreg[NSL];
+#pragma unroll
+    for (int sl = 0; sl < NSL; ++sl)
+      kreg[sl] = *reinterpret_cast<const uint4*>(tile + x * kPitch + sl * 64 + j * 16);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
     float wsum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -199,8 +217,8 @@ __global__ __launch_bounds__(kThreads) void window_pass(const WindowParams P) {
     const bool two = gi + kWaves < groups;
     load_group(ka, gi);
     if (two) load_group(kb, gi + kWaves);
-    use_group(ka, gi);
-    if (two) use_group(kb, gi + kWaves);
+    use_group(ka, gi, tile_sh[wave][0]);
+    if (two) use_group(kb, gi + kWaves, tile_sh[wave][1]);
   }
 
   if (kPhase == 0) {
