@@ -27,6 +27,10 @@
  *   - Argument errors are detected before anything is enqueued and leave all
  *     state untouched.  No call throws, aborts or synchronises the device.
  *   - Calls on one cache must be ordered by the caller (same stream).
+ *   - The library keeps a little process-wide state (xkv_configure,
+ *     xkv_profile_*, cached device properties of the first device used): calls
+ *     from several host threads must be serialised by the caller, and one
+ *     process drives one GPU.
  */
 #ifndef XKV_H
 #define XKV_H
