@@ -288,8 +288,6 @@ __global__ __launch_bounds__(kSelThreads) void evict_select(const EvictParams P)
 }
 
 __global__ __launch_bounds__(kMoveThreads) void evict_move(const EvictParams P) {
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
   const int u = blockIdx.x;
   const int moves = P.ws_count[u];
   if (moves == 0) return;
@@ -300,9 +298,28 @@ __global__ __launch_bounds__(kMoveThreads) void evict_move(const EvictParams P) 
   const int64_t ws_off = static_cast<int64_t>(pd.ws0) + static_cast<int64_t>(h) * ws_stride(pd.n);
   const int32_t* holes = P.ws_holes + ws_off;
   const int32_t* movers = P.ws_movers + ws_off;
-  const int waves = kMoveThreads / 64;
-  for (int i = blockIdx.y * waves + wave; i < moves; i += gridDim.y * waves)
-    move_row(P, stream_slot, holes[i], movers[i], lane);
+  // A workgroup takes rows_per_pass moves at a time: every thread copies one 16-byte
+  // piece of a K row and of a V row, the first thread of each row also score, pos and
+  // the kept index.
+  const int frags = P.row_bytes >> 4;                 // 8, 16 or 32 pieces per row
+  const int rows_per_pass = kMoveThreads / frags;
+  const int fr = threadIdx.x % frags, rw = threadIdx.x / frags;
+  char* kb = static_cast<char*>(P.k) + stream_slot * P.row_bytes;
+  char* vb = static_cast<char*>(P.v) + stream_slot * P.row_bytes;
+  for (int i = blockIdx.y * rows_per_pass + rw; i < moves; i += gridDim.y * rows_per_pass) {
+    const int dst = holes[i], src = movers[i];
+    const int64_t so = static_cast<int64_t>(src) * P.row_bytes + fr * 16;
+    const int64_t dof = static_cast<int64_t>(dst) * P.row_bytes + fr * 16;
+    const uint4 a = *reinterpret_cast<const uint4*>(kb + so);
+    const uint4 b = *reinterpret_cast<const uint4*>(vb + so);
+    *reinterpret_cast<uint4*>(kb + dof) = a;
+    *reinterpret_cast<uint4*>(vb + dof) = b;
+    if (fr == 0) {
+      P.score[stream_slot + dst] = P.score[stream_slot + src];
+      P.pos[stream_slot + dst] = P.pos[stream_slot + src];
+      if (P.kept_idx != nullptr) P.kept_idx[stream_slot + dst] = src;
+    }
+  }
 }
 
 }  // namespace
