@@ -14,6 +14,21 @@ from gpu_util import TOL, get_unit, rel_err, storage
 pytestmark = pytest.mark.gpu
 
 
+def check_selection_is_valid_for(w_ref, kept_pos, t, ows, ps, tol):
+    """Independent of anything the device computed: against the oracle's own masses the kept
+    candidates must be a top set up to the tolerance (several sets are correct when keys lie
+    that close to the threshold)."""
+    tc = t - ows
+    kc = len(kept_pos) - ows
+    if kc <= 0 or kc >= tc:
+        return
+    key = orc.pooled_keys(w_ref[:tc].astype(np.float32), ps).astype(np.float64)
+    kept = np.zeros(tc, bool)
+    kept[kept_pos[:kc]] = True
+    slack = tol * ps * float(key.max())
+    assert key[kept].min() >= key[~kept].max() - 2 * slack
+
+
 def run_prefill(xkv, dtype, d, Hq, Hkv, L, B, t, ows, ps, budgets, seed, scale=0.0, layer_range=None,
                 heavy=True, with_w=True, check_units=None):
     budgets = np.asarray(budgets, np.int32).reshape(L, B)
@@ -62,6 +77,7 @@ def run_prefill(xkv, dtype, d, Hq, Hkv, L, B, t, ows, ps, budgets, seed, scale=0
                     Ko, Vo, so, po, _ = orc.prefill_evict(q, K, V, kk, ows, ps, w=wd)
                     assert np.array_equal(p2, po), f"kept positions differ in unit {(l, b, h)}"
                     assert np.array_equal(K2, Ko) and np.array_equal(V2, Vo) and np.array_equal(s2, so)
+                    check_selection_is_valid_for(w_ref, p2, t, ows, ps, TOL[dtype])
                 else:
                     # without w_out: what is unique is checked (the window, order, rows, scores
                     # within tolerance) and the kept set is valid for scores within tolerance
