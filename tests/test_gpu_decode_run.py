@@ -32,6 +32,7 @@ def lockstep(xkv, w, budgets, units, steps, pool=1, protect=0, first_evict_step=
     kept = torch.zeros(cache.arena_slots, dtype=torch.int32, device="cuda")
     orcs = {u: orc.OracleUnit(*get_unit(cache, *u)) for u in units}
     evicted_mass = {u: 0.0 for u in units}
+    own_scores = {}
     for step in range(steps):
         xkv.xkv_decode_attend_score(cache, 0, w.n_layers, q[step], kn[step], vn[step], pos_new[step], out, ws)
         torch.cuda.synchronize()
@@ -49,6 +50,7 @@ def lockstep(xkv, w, budgets, units, steps, pool=1, protect=0, first_evict_step=
             assert np.array_equal(pos, u.pos) and np.array_equal(K, u.K) and np.array_equal(V, u.V)
             total = float(sc.astype(np.float64).sum()) + evicted_mass[(l, b, h)]
             assert abs(total - G * (step + 1)) <= 1e-4 * G * (step + 1), "attention mass is conserved"
+            own_scores[(l, b, h)] = u.score.copy()
             u.score = sc                       # select from the same score array
         if step < first_evict_step:
             continue
@@ -57,7 +59,9 @@ def lockstep(xkv, w, budgets, units, steps, pool=1, protect=0, first_evict_step=
         torch.cuda.synchronize()
         for (l, b, h), u in orcs.items():
             before = float(u.score.astype(np.float64).sum())
+            n_before, pos_before = u.n, u.pos.copy()
             ki = u.evict(int(budgets[l, b]), pool, protect)
+            check_valid_top_set(own_scores[(l, b, h)], pos_before, ki, pool, protect, TOL[w.dtype])
             evicted_mass[(l, b, h)] += before - float(u.score.astype(np.float64).sum())
             s0 = cache.stream_slot(l, b, h)
             assert cache.length(l, b) == u.n
@@ -67,6 +71,25 @@ def lockstep(xkv, w, budgets, units, steps, pool=1, protect=0, first_evict_step=
             assert np.array_equal(sc, u.score) and np.array_equal(pos, u.pos)
             assert sorted(pos.tolist()) == sorted(u.pos.tolist())
     return cache
+
+
+def check_valid_top_set(own_score, pos, kept_idx, pool, protect, tol):
+    """The kept slots against the scores the oracle computed itself for this step (nothing of
+    the device in them): up to the tolerance they are a top set of the unprotected slots."""
+    n = own_score.shape[0]
+    kept = np.zeros(n, bool)
+    kept[kept_idx] = True
+    if kept.all():
+        return
+    key = orc.pooled_keys(own_score, pool).astype(np.float64)
+    free = np.ones(n, bool)
+    if protect > 0:
+        free = pos < 1 + int(pos.max()) - protect
+        assert kept[~free].all()
+    if not (kept & free).any():
+        return
+    slack = tol * pool * float(key.max())
+    assert key[kept & free].min() >= key[~kept].max() - 2 * slack
 
 
 def all_units(w):
