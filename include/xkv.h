@@ -256,20 +256,25 @@ xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, int32_t laye
  *   q_win    DEVICE [layers][batch][n_q_heads][ows][head_dim], cache dtype
  *   k_src, v_src  DEVICE [layers][batch][n_kv_heads][t][head_dim], cache dtype;
  *            must not overlap the cache
- *   t        prompt length, the same for every sequence; 1 <= ows <= t
+ *   t        rows per stream of k_src / v_src / w_out: the longest prompt of the batch
+ *   t_per_seq  HOST [batch] or NULL: the prompt length t_b of every sequence,
+ *            ows <= t_b <= t (rows at or beyond t_b are never read, and their
+ *            w_out entries are not written); NULL = all prompts have t tokens.
+ *            Wherever t appears above, sequence b uses t_b.  1 <= ows <= t
  *   budgets  HOST [layers][batch], each >= ows
  *   softmax_scale  0 = 1/sqrt(head_dim)
  *   w_out    DEVICE [layers][batch][n_kv_heads][t] fp32 or NULL: receives w
  *   workspace  at least xkv_prefill_workspace_bytes
  *
- * Supported: ows * G <= 64, t - ows <= 262144.  Errors: INVALID_ARG, UNSUPPORTED,
+ * Supported: ows * G <= 64, t - ows <= 262144, batch <= 256 when t_per_seq is given.  Errors: INVALID_ARG, UNSUPPORTED,
  * CAPACITY (k' > cap or the workspace is too small), DEVICE.  Bit-reproducible.
  */
 xkv_status xkv_prefill_workspace_bytes(const xkv_cache* cache, int32_t max_layers_per_call,
                                        int32_t t, int32_t ows, size_t* bytes_out);
 xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
                              const void* q_win, const void* k_src, const void* v_src, int32_t t,
-                             int32_t ows, int32_t pool_size, const int32_t* budgets,
+                             const int32_t* t_per_seq, int32_t ows, int32_t pool_size,
+                             const int32_t* budgets,
                              float softmax_scale, float* w_out, void* workspace,
                              size_t workspace_bytes, void* hip_stream);
 
@@ -284,14 +289,14 @@ xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, int32_t laye
  * sum over the candidate vector (zeros outside).  Only K is read; the cache's
  * arenas are not touched (only its shape fields are used).
  *
- *   q_win, k_src, t, ows, pool_size, softmax_scale   as for xkv_prefill_evict
- *   w_out      DEVICE [layers][batch][t - ows] fp32
+ *   q_win, k_src, t, t_per_seq, ows, pool_size, softmax_scale   as for xkv_prefill_evict
+ *   w_out      DEVICE [layers][batch][t - ows] fp32 (sequence b: the first t_b - ows entries)
  *   workspace  at least xkv_prefill_workspace_bytes
  * Errors: INVALID_ARG, UNSUPPORTED, CAPACITY, DEVICE.
  */
 xkv_status xkv_window_importance(const xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
-                                 const void* q_win, const void* k_src, int32_t t, int32_t ows,
-                                 int32_t pool_size, float softmax_scale, float* w_out,
+                                 const void* q_win, const void* k_src, int32_t t,
+                                 const int32_t* t_per_seq, int32_t ows, int32_t pool_size, float softmax_scale, float* w_out,
                                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*

@@ -77,11 +77,12 @@ def load():
     lib.xkv_prefill_evict.restype = C.c_int32
     lib.xkv_prefill_evict.argtypes = [
         C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
-        C.c_int32, C.c_int32, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t,
+        C.c_void_p]
     lib.xkv_window_importance.restype = C.c_int32
     lib.xkv_window_importance.argtypes = [
-        C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
-        C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+        C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.xkv_allocate_device_workspace_bytes.restype = C.c_int32
     lib.xkv_allocate_device_workspace_bytes.argtypes = [C.c_int32, C.c_int64, C.POINTER(C.c_size_t)]
     lib.xkv_allocate_budgets_device.restype = C.c_int32
@@ -273,23 +274,27 @@ def xkv_prefill_workspace_bytes(cache: XkvCache, max_layers_per_call: int, t: in
 
 def xkv_prefill_evict(cache: XkvCache, layer_begin, layer_end, q_win, k_src, v_src, t: int, ows: int,
                       budgets, workspace, pool_size: int = 1, softmax_scale: float = 0.0, w_out=None,
-                      stream=None):
+                      stream=None, t_per_seq=None):
     """q_win [layers, B, Hq, ows, d], k_src / v_src [layers, B, Hkv, t, d]: device tensors of the
     cache dtype; budgets: int32 host array [layers, B]; w_out: device fp32 [layers, B, Hkv, t] or None."""
     bud = None if budgets is None else np.ascontiguousarray(budgets, dtype=np.int32)
+    tps = None if t_per_seq is None else np.ascontiguousarray(t_per_seq, dtype=np.int32)
     st = load().xkv_prefill_evict(
         C.byref(cache.struct), int(layer_begin), int(layer_end), _ptr(q_win), _ptr(k_src), _ptr(v_src),
-        int(t), int(ows), int(pool_size), _ptr(bud), float(softmax_scale), _ptr(w_out), _ptr(workspace),
+        int(t), _ptr(tps), int(ows), int(pool_size), _ptr(bud), float(softmax_scale), _ptr(w_out),
+        _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     _check(st, "xkv_prefill_evict")
 
 
 def xkv_window_importance(cache: XkvCache, layer_begin, layer_end, q_win, k_src, t: int, ows: int, w_out,
-                          workspace, pool_size: int = 1, softmax_scale: float = 0.0, stream=None):
+                          workspace, pool_size: int = 1, softmax_scale: float = 0.0, stream=None,
+                          t_per_seq=None):
     """w_out: device fp32 [layers, B, t - ows], the per-(layer, sequence) score distribution vectors."""
+    tps = None if t_per_seq is None else np.ascontiguousarray(t_per_seq, dtype=np.int32)
     st = load().xkv_window_importance(
-        C.byref(cache.struct), int(layer_begin), int(layer_end), _ptr(q_win), _ptr(k_src), int(t), int(ows),
-        int(pool_size), float(softmax_scale), _ptr(w_out), _ptr(workspace),
+        C.byref(cache.struct), int(layer_begin), int(layer_end), _ptr(q_win), _ptr(k_src), int(t), _ptr(tps),
+        int(ows), int(pool_size), float(softmax_scale), _ptr(w_out), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     _check(st, "xkv_window_importance")
 

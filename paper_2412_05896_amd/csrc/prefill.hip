@@ -36,6 +36,7 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kSelThreads = 1024;          // prefill_select: one large workgroup per stream
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kMaxNq = 64;                 // query rows (ows * G) per KV head
+constexpr int kMaxSeqLens = 256;           // sequences with a prompt length of their own
 constexpr int kMaxKeyRegs = 32;            // prefill_select: keys a thread keeps in registers
 constexpr int kMaxWalkRows = 256;          // prefill_select without register keys: rows of candidates
 // Selection of a long stream split over several workgroups (see split_*): candidates per
@@ -55,8 +56,10 @@ struct WindowParams {
   float* fin;             // [streams][nq_pad][2]           (max, 1 / sum)
   float* w;               // [streams][t]
   float scale_log2e;
-  int32_t t, ows, group, n_kv_heads;
+  int32_t t, ows, group, n_kv_heads;      // t: rows per stream of k_src and w (the longest prompt)
   int32_t strip_rows, nstrips, nq_pad;
+  int32_t n_seq;                          // entries of t_seq: the batch, or 1 when all prompts have t tokens
+  int32_t t_seq[kMaxSeqLens];             // prompt length of sequence b (pair % n_seq)
 };
 
 // One MFMA step over the 16 bytes that lane (j, x) holds of row x of A and of
@@ -107,11 +110,12 @@ __global__ __launch_bounds__(kThreads) void window_pass(const WindowParams P) {
   const int s = blockIdx.x - u * P.nstrips;
   const int pair = u / P.n_kv_heads;
   const int h = u - pair * P.n_kv_heads;
-  const int t = P.t, ows = P.ows;
+  const int t = P.t_seq[pair % P.n_seq], ows = P.ows;   // this sequence's prompt length
   const int nq = ows * P.group;
   const int r_begin = s * P.strip_rows;
+  if (r_begin >= t) return;                         // strip past the end of a shorter prompt
   const int r_end = min(t, r_begin + P.strip_rows);
-  const char* kbase = static_cast<const char*>(P.k_src) + static_cast<int64_t>(u) * t * ROWB;
+  const char* kbase = static_cast<const char*>(P.k_src) + static_cast<int64_t>(u) * P.t * ROWB;
 
   // Query operands; query row qi = g * ows + r is head g, window row r.
   uint4 qreg[NB][NSL];
@@ -208,7 +212,7 @@ __global__ __launch_bounds__(kThreads) void window_pass(const WindowParams P) {
         if (x == i) mine = tot;
       }
       const int pos = g0 + 4 * j + x;
-      if (x < 4 && pos < t) P.w[static_cast<int64_t>(u) * t + pos] = mine;
+      if (x < 4 && pos < t) P.w[static_cast<int64_t>(u) * P.t + pos] = mine;
     }
   };
   // Two groups per turn, both requested before either is used.
@@ -257,9 +261,11 @@ __global__ __launch_bounds__(kThreads) void window_merge(const WindowParams P) {
   const int nq = P.nq_pad;                    // 16, 32, 48 or 64
   const int S = kThreads / nq;
   const int qi = tid % nq, slice = tid / nq;
+  const int t = P.t_seq[(u / P.n_kv_heads) % P.n_seq];
+  const int nstrips = (t + P.strip_rows - 1) / P.strip_rows;   // the strips this sequence's prompt has
   float m = -INFINITY, l = 0.0f;
   if (slice < S)
-    for (int s = slice; s < P.nstrips; s += S) {
+    for (int s = slice; s < nstrips; s += S) {
       const float* st = P.stats + ((static_cast<int64_t>(u) * P.nstrips + s) * nq + qi) * 2;
       merge_ml(m, l, st[0], st[1]);
     }
@@ -279,6 +285,7 @@ struct GatherPair {
   int64_t slot0;   // first slot of the region
   int32_t cap;     // slots per stream
   int32_t k;       // tokens kept: min(budget, t)
+  int32_t t;       // prompt length of the region's sequence
 };
 
 struct GatherParams {
@@ -292,7 +299,7 @@ struct GatherParams {
   uint32_t* keys;        // [streams][t] pooled keys (only used when pool > 1)
   int32_t* idx;          // [streams][t] kept positions, ascending
   unsigned* split;       // [streams][kSplitWords]: state of the selection split over several workgroups
-  int32_t t, ows, pool, n_kv_heads, row_bytes;
+  int32_t t, ows, pool, n_kv_heads, row_bytes;   // t: rows per stream of the dense arrays
   int32_t stream0;       // index of this launch's first stream within the call
   GatherPair pairs[kMaxPairs];
 };
@@ -317,7 +324,7 @@ __global__ __launch_bounds__(kSelThreads) void prefill_select(const GatherParams
   const int ul = blockIdx.x;                        // stream within the launch
   const GatherPair pd = P.pairs[ul / P.n_kv_heads];
   const int64_t u = static_cast<int64_t>(P.stream0) + ul;
-  const int t = P.t, tc = P.t - P.ows;
+  const int t = P.t, tc = pd.t - P.ows;
   const int kc = pd.k - P.ows;                      // candidates to keep
   const float* w = P.w + u * t;
   uint32_t* keys = P.keys + u * t;
@@ -437,7 +444,7 @@ __global__ __launch_bounds__(kSelThreads) void prefill_select(const GatherParams
 // the chunk counts, then the ordered walk inside the chunk).  All counters are
 // integers added with atomics: the result does not depend on the order.
 struct SplitCtx {
-  int ul, c, t, tc, kc, first, n;     // stream, chunk, lengths, first candidate and count of the chunk
+  int ul, c, t, tc, kc, first, n;     // stream, chunk, row stride, candidates, kept, first candidate and count of the chunk
   int64_t u;
   unsigned* st;                       // the stream's state words
 };
@@ -448,7 +455,7 @@ __device__ __forceinline__ SplitCtx split_ctx(const GatherParams& P) {
   x.c = blockIdx.x;
   x.u = static_cast<int64_t>(P.stream0) + x.ul;
   x.t = P.t;
-  x.tc = P.t - P.ows;
+  x.tc = P.pairs[x.ul / P.n_kv_heads].t - P.ows;
   x.kc = P.pairs[x.ul / P.n_kv_heads].k - P.ows;
   x.first = x.c * kSplitChunk;
   x.n = min(kSplitChunk, x.tc - x.first);
@@ -690,13 +697,13 @@ __global__ __launch_bounds__(kThreads) void prefill_gather(const GatherParams P)
 // Attention score distribution vector of a (layer, sequence): the streams' masses
 // added over the KV heads in index order, then the window sum over the
 // candidates (fp32, left to right, zeros outside).
-__global__ __launch_bounds__(kThreads) void heads_pool(const float* w, float* out, int t, int ows,
-                                                       int n_kv_heads, int pool) {
+__global__ __launch_bounds__(kThreads) void heads_pool(const WindowParams P, float* out, int pool) {
   const int pair = blockIdx.y;
-  const int tc = t - ows;
+  const int t = P.t, n_kv_heads = P.n_kv_heads;
+  const int tc = P.t_seq[pair % P.n_seq] - P.ows;     // this sequence's candidates
   const int j = blockIdx.x * kThreads + threadIdx.x;
   if (j >= tc) return;
-  const float* wp = w + static_cast<int64_t>(pair) * n_kv_heads * t;
+  const float* wp = P.w + static_cast<int64_t>(pair) * n_kv_heads * t;
   const int half = pool >> 1;
   float acc = 0.0f;
   for (int q = 0; q < pool; ++q) {
@@ -708,7 +715,7 @@ __global__ __launch_bounds__(kThreads) void heads_pool(const float* w, float* ou
     }
     acc = q == 0 ? hs : acc + hs;
   }
-  out[static_cast<int64_t>(pair) * tc + j] = acc;
+  out[static_cast<int64_t>(pair) * (t - P.ows) + j] = acc;
 }
 
 using WindowFn = void (*)(const WindowParams);
@@ -759,6 +766,23 @@ PrefillLayout prefill_layout(int64_t streams, int t, int nq_pad, bool own_w, boo
   return L;
 }
 
+// Fills the per-sequence prompt lengths of a launch (one entry meaning "all t").
+xkv_status fill_seq_lens(const xkv_cache* cache, int32_t t, int32_t ows, const int32_t* t_per_seq,
+                         WindowParams* W) {
+  if (t_per_seq == nullptr) {
+    W->n_seq = 1;
+    W->t_seq[0] = t;
+    return XKV_OK;
+  }
+  if (cache->batch > kMaxSeqLens) return XKV_ERR_UNSUPPORTED;
+  W->n_seq = cache->batch;
+  for (int b = 0; b < cache->batch; ++b) {
+    if (t_per_seq[b] < ows || t_per_seq[b] > t) return XKV_ERR_INVALID_ARG;
+    W->t_seq[b] = t_per_seq[b];
+  }
+  return XKV_OK;
+}
+
 xkv_status check_prefill_shape(const xkv_cache* cache, int32_t t, int32_t ows, int* nb_out) {
   if (t < 1 || ows < 1 || ows > t) return XKV_ERR_INVALID_ARG;
   if (t - ows > kMaxWalkRows * kSelThreads) return XKV_ERR_UNSUPPORTED;
@@ -769,15 +793,15 @@ xkv_status check_prefill_shape(const xkv_cache* cache, int32_t t, int32_t ows, i
 }
 
 // The three launches that turn (q_win, k_src) into the per-stream masses w.
+// W arrives with its sequence lengths filled in and leaves complete.
 xkv_status launch_window_mass(const xkv_cache* cache, int64_t streams, const void* q_win,
                               const void* k_src, int32_t t, int32_t ows, int nb, float softmax_scale,
                               WindowFn stats_fn, WindowFn mass_fn, float* stats, float* fin, float* w,
-                              hipStream_t stream) {
+                              hipStream_t stream, WindowParams& W) {
   const int D = cache->head_dim;
   const int strip_rows = prefill_strip_rows(streams, t);
   const int64_t nstrips = ceil_div(t, strip_rows);
   if (streams * nstrips > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;
-  WindowParams W;
   W.q_win = q_win;
   W.k_src = k_src;
   W.stats = stats;
@@ -808,7 +832,8 @@ xkv_status launch_window_mass(const xkv_cache* cache, int64_t streams, const voi
 
 extern "C" xkv_status xkv_window_importance(const xkv_cache* cache, int32_t layer_begin,
                                             int32_t layer_end, const void* q_win, const void* k_src,
-                                            int32_t t, int32_t ows, int32_t pool_size,
+                                            int32_t t, const int32_t* t_per_seq, int32_t ows,
+                                            int32_t pool_size,
                                             float softmax_scale, float* w_out, void* workspace,
                                             size_t workspace_bytes, void* hip_stream) {
   using namespace xkv;
@@ -825,6 +850,9 @@ extern "C" xkv_status xkv_window_importance(const xkv_cache* cache, int32_t laye
   int nb = 0;
   st = check_prefill_shape(cache, t, ows, &nb);
   if (st != XKV_OK) return st;
+  WindowParams W;
+  st = fill_seq_lens(cache, t, ows, t_per_seq, &W);
+  if (st != XKV_OK) return st;
   const int64_t n_pairs = static_cast<int64_t>(layer_end - layer_begin) * cache->batch;
   const int64_t streams = n_pairs * cache->n_kv_heads;
   WindowFn stats_fn = nullptr, mass_fn = nullptr;
@@ -837,12 +865,12 @@ extern "C" xkv_status xkv_window_importance(const xkv_cache* cache, int32_t laye
   float* w_dense = reinterpret_cast<float*>(ws + L.w);
   st = launch_window_mass(cache, streams, q_win, k_src, t, ows, nb, softmax_scale, stats_fn, mass_fn,
                           reinterpret_cast<float*>(ws + L.stats), reinterpret_cast<float*>(ws + L.fin),
-                          w_dense, stream);
+                          w_dense, stream, W);
   if (st != XKV_OK) return st;
   const int tc = t - ows;
   if (tc > 0) {
     hipLaunchKernelGGL(heads_pool, dim3(static_cast<unsigned>(ceil_div(tc, kThreads)), static_cast<unsigned>(n_pairs)),
-                       dim3(kThreads), 0, stream, w_dense, w_out, t, ows, cache->n_kv_heads, pool_size);
+                       dim3(kThreads), 0, stream, W, w_out, pool_size);
     if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
   }
   return XKV_OK;
@@ -871,7 +899,8 @@ extern "C" xkv_status xkv_prefill_workspace_bytes(const xkv_cache* cache, int32_
 
 extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
                                         const void* q_win, const void* k_src, const void* v_src,
-                                        int32_t t, int32_t ows, int32_t pool_size,
+                                        int32_t t, const int32_t* t_per_seq, int32_t ows,
+                                        int32_t pool_size,
                                         const int32_t* budgets, float softmax_scale, float* w_out,
                                         void* workspace, size_t workspace_bytes, void* hip_stream) {
   using namespace xkv;
@@ -894,9 +923,13 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
   const int64_t first = static_cast<int64_t>(layer_begin) * B;
   const int64_t n_pairs = static_cast<int64_t>(layer_end - layer_begin) * B;
   const int64_t streams = n_pairs * hkv;
+  WindowParams W;
+  st = fill_seq_lens(cache, t, ows, t_per_seq, &W);
+  if (st != XKV_OK) return st;
+  auto seq_len = [&](int64_t pair) { return W.t_seq[pair % W.n_seq]; };   // pairs are [layer][sequence]
   for (int64_t i = 0; i < n_pairs; ++i) {
     if (budgets[i] < ows) return XKV_ERR_INVALID_ARG;
-    if (std::min<int64_t>(budgets[i], t) > cache->cap[first + i]) return XKV_ERR_CAPACITY;
+    if (std::min<int64_t>(budgets[i], seq_len(i)) > cache->cap[first + i]) return XKV_ERR_CAPACITY;
   }
   WindowFn stats_fn = nullptr, mass_fn = nullptr;
   if (!pick_window(cache->dtype, D, nb, &stats_fn, &mass_fn)) return XKV_ERR_UNSUPPORTED;
@@ -914,7 +947,7 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
   float* w_dense = w_out != nullptr ? w_out : reinterpret_cast<float*>(ws + L.w);
   st = launch_window_mass(cache, streams, q_win, k_src, t, ows, nb, softmax_scale, stats_fn, mass_fn,
                           reinterpret_cast<float*>(ws + L.stats), reinterpret_cast<float*>(ws + L.fin),
-                          w_dense, stream);
+                          w_dense, stream, W);
   if (st != XKV_OK) return st;
 
   GatherParams Gp;
@@ -934,7 +967,8 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
       GatherPair& pd = Gp.pairs[i];
       pd.slot0 = cache->region_off[idx];
       pd.cap = cache->cap[idx];
-      pd.k = static_cast<int32_t>(std::min<int64_t>(budgets[g0 + i], t));
+      pd.t = seq_len(g0 + i);
+      pd.k = static_cast<int32_t>(std::min<int64_t>(budgets[g0 + i], pd.t));
       kmax = std::max<int64_t>(kmax, pd.k);
     }
     Gp.stream0 = static_cast<int32_t>(g0 * hkv);
@@ -972,6 +1006,6 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
     if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
   }
   for (int64_t i = 0; i < n_pairs; ++i)
-    cache->len[first + i] = static_cast<int32_t>(std::min<int64_t>(budgets[i], t));
+    cache->len[first + i] = static_cast<int32_t>(std::min<int64_t>(budgets[i], seq_len(i)));
   return XKV_OK;
 }

@@ -30,9 +30,11 @@ def check_selection_is_valid_for(w_ref, kept_pos, t, ows, ps, tol):
 
 
 def run_prefill(xkv, dtype, d, Hq, Hkv, L, B, t, ows, ps, budgets, seed, scale=0.0, layer_range=None,
-                heavy=True, with_w=True, check_units=None):
+                heavy=True, with_w=True, check_units=None, t_per_seq=None):
+    """t_per_seq: prompt length of every sequence (rows beyond it hold NaN: they must never be read)."""
     budgets = np.asarray(budgets, np.int32).reshape(L, B)
-    caps = np.minimum(budgets, t) + 3
+    tb = np.full(B, t, np.int64) if t_per_seq is None else np.asarray(t_per_seq, np.int64)
+    caps = np.minimum(budgets, tb[None, :]) + 3
     cache = xkv.XkvCache(L, B, Hq, Hkv, d, dtype, caps)
     G = Hq // Hkv
     l0, l1 = layer_range or (0, L)
@@ -43,14 +45,18 @@ def run_prefill(xkv, dtype, d, Hq, Hkv, L, B, t, ows, ps, budgets, seed, scale=0
     if heavy:                                   # a few dominant tokens, as in the paper's heat map
         hot = torch.randperm(t, generator=g)[:max(1, t // 50)]
         k_src[:, :, :, hot, :] *= 3.0
+    v_src = torch.randn((nl, B, Hkv, t, d), generator=g)
+    for b in range(B):
+        k_src[:, b, :, int(tb[b]):, :] = float("nan")
+        v_src[:, b, :, int(tb[b]):, :] = float("nan")
     k_src = k_src.to(tdt).cuda()
-    v_src = torch.randn((nl, B, Hkv, t, d), generator=g).to(tdt).cuda()
+    v_src = v_src.to(tdt).cuda()
     q_win = torch.randn((nl, B, Hq, ows, d), generator=g).to(tdt).cuda()
     ws = torch.empty(xkv.xkv_prefill_workspace_bytes(cache, L, t, ows), dtype=torch.uint8, device="cuda")
     w_out = torch.full((nl, B, Hkv, t), float("nan"), dtype=torch.float32, device="cuda") if with_w else None
     cache.len[:] = 1                            # whatever was there is overwritten
     xkv.xkv_prefill_evict(cache, l0, l1, q_win, k_src, v_src, t, ows, budgets[l0:l1], ws, pool_size=ps,
-                          softmax_scale=scale, w_out=w_out)
+                          softmax_scale=scale, w_out=w_out, t_per_seq=t_per_seq)
     torch.cuda.synchronize()
     w_dev = w_out.cpu().numpy() if with_w else None
     worst = 0.0
@@ -59,29 +65,31 @@ def run_prefill(xkv, dtype, d, Hq, Hkv, L, B, t, ows, ps, budgets, seed, scale=0
             if not (l0 <= l < l1):
                 assert cache.length(l, b) == 1
                 continue
-            kk = min(int(budgets[l, b]), t)
+            ts = int(tb[b])                      # this sequence's prompt
+            kk = min(int(budgets[l, b]), ts)
             assert cache.length(l, b) == kk
             for h in range(Hkv):
                 if check_units is not None and (l, b, h) not in check_units:
                     continue
-                K = storage(k_src[l - l0, b, h])
-                V = storage(v_src[l - l0, b, h])
+                K = storage(k_src[l - l0, b, h])[:ts]
+                V = storage(v_src[l - l0, b, h])[:ts]
                 q = storage(q_win[l - l0, b, h * G:(h + 1) * G])
                 w_ref = orc.window_attention_mass(q, K, None if scale == 0.0 else scale)
                 K2, V2, s2, p2 = get_unit(cache, l, b, h)
                 if with_w:
-                    wd = w_dev[l - l0, b, h]
+                    wd = w_dev[l - l0, b, h][:ts]
                     assert np.all(np.isfinite(wd))
+                    assert np.all(np.isnan(w_dev[l - l0, b, h][ts:]))      # nothing written past the prompt
                     worst = max(worst, rel_err(wd, w_ref))
                     assert abs(float(wd.astype(np.float64).sum()) - G * ows) < 1e-3 * G * ows
                     Ko, Vo, so, po, _ = orc.prefill_evict(q, K, V, kk, ows, ps, w=wd)
                     assert np.array_equal(p2, po), f"kept positions differ in unit {(l, b, h)}"
                     assert np.array_equal(K2, Ko) and np.array_equal(V2, Vo) and np.array_equal(s2, so)
-                    check_selection_is_valid_for(w_ref, p2, t, ows, ps, TOL[dtype])
+                    check_selection_is_valid_for(w_ref, p2, ts, ows, ps, TOL[dtype])
                 else:
                     # without w_out: what is unique is checked (the window, order, rows, scores
                     # within tolerance) and the kept set is valid for scores within tolerance
-                    assert np.all(np.diff(p2) > 0) and np.array_equal(p2[kk - ows:], np.arange(t - ows, t))
+                    assert np.all(np.diff(p2) > 0) and np.array_equal(p2[kk - ows:], np.arange(ts - ows, ts))
                     assert np.array_equal(K2, K[p2]) and np.array_equal(V2, V[p2])
                     worst = max(worst, rel_err(s2, w_ref[p2]))
     assert worst <= TOL[dtype], f"w rel err {worst}"
@@ -211,3 +219,38 @@ def test_long_streams_split_selection_random_scores(xkv):
     o = run_prefill(xkv, "bf16", 128, 4, 2, 1, 2, 50003, 8, 7, [[12345, 49000]], seed=41)
     print("split selection w rel err", o, flush=True)
     run_prefill(xkv, "f32", 64, 2, 2, 1, 1, 33000, 8, 1, [[8]], seed=42)        # window only
+
+
+@pytest.mark.parametrize("dtype,d,G", [("bf16", 128, 4), ("f32", 64, 1), ("bf16", 128, 1)])
+def test_batch_of_prompts_of_different_lengths(xkv, dtype, d, G):
+    """Every sequence has its own prompt length; the rows past it hold NaN and must not be read.
+    Lengths end inside a 16-row group, equal the window, fill all rows."""
+    t, ows = 1500, 8
+    tps = [1500, 8, 777, 1001]
+    budgets = [[300, 8, 800, 50], [1500, 100, 9, 1001]]
+    run_prefill(xkv, dtype, d, 2 * G, 2, 2, 4, t, ows, 7, budgets, seed=70 + G, t_per_seq=tps)
+
+
+def test_different_lengths_in_the_split_selection_and_score_vectors(xkv):
+    """Long prompts of different lengths (selection split over workgroups), and the allocator's
+    per-sequence score vectors for them."""
+    t, ows, ps, Hq, Hkv, d = 40000, 8, 7, 4, 2, 128
+    tps = [40000, 33333]
+    run_prefill(xkv, "bf16", d, Hq, Hkv, 1, 2, t, ows, ps, [[9000, 33000]], seed=81, t_per_seq=tps)
+    cache = xkv.XkvCache(1, 2, Hq, Hkv, d, "bf16", [[8, 8]])
+    g = torch.Generator(device="cpu").manual_seed(82)
+    k_src = torch.randn((1, 2, Hkv, t, d), generator=g)
+    k_src[0, 1, :, tps[1]:, :] = float("nan")
+    k_src = k_src.bfloat16().cuda()
+    q_win = torch.randn((1, 2, Hq, ows, d), generator=g).bfloat16().cuda()
+    ws = torch.empty(xkv.xkv_prefill_workspace_bytes(cache, 1, t, ows), dtype=torch.uint8, device="cuda")
+    w_layer = torch.full((1, 2, t - ows), float("nan"), dtype=torch.float32, device="cuda")
+    xkv.xkv_window_importance(cache, 0, 1, q_win, k_src, t, ows, w_layer, ws, pool_size=ps, t_per_seq=tps)
+    torch.cuda.synchronize()
+    got = w_layer.cpu().numpy()
+    for b in range(2):
+        tc = tps[b] - ows
+        q = storage(q_win[0, b]).reshape(Hkv, Hq // Hkv, ows, d)
+        ref = orc.window_importance(q, storage(k_src[0, b])[:, :tps[b]], ps)
+        assert rel_err(got[0, b, :tc], ref) <= TOL["bf16"]
+        assert np.all(np.isnan(got[0, b, tc:]))

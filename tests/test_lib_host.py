@@ -183,7 +183,7 @@ def test_prefill_argument_errors_leave_state_untouched():
     assert lib.xkv_prefill_workspace_bytes(C.byref(s), 2, 300, 40, C.byref(out)) == -4   # ows * G > 64
     call = lambda *a: lib.xkv_prefill_evict(C.byref(s), *a)
     ok_args = lambda **o: [o.get("l0", 0), o.get("l1", 2), o.get("q", p), o.get("k", p), o.get("v", p),
-                           o.get("t", 300), o.get("ows", 8), o.get("ps", 7),
+                           o.get("t", 300), o.get("tps", None), o.get("ows", 8), o.get("ps", 7),
                            o.get("bud", bud.ctypes.data), o.get("scale", 0.0), None, o.get("ws", p),
                            o.get("wsb", big), None]
     assert call(*ok_args(l1=3)) == -1
@@ -200,6 +200,12 @@ def test_prefill_argument_errors_leave_state_untouched():
     assert call(*ok_args(bud=large.ctypes.data)) == -3
     assert call(*ok_args(wsb=64)) == -3
     assert call(*ok_args(ws=0x2010)) == -1                               # misaligned workspace
+    short = np.array([300, 7], np.int32)                                 # a prompt shorter than the window
+    assert call(*ok_args(tps=short.ctypes.data)) == -1
+    long_ = np.array([301, 100], np.int32)                               # longer than the row count
+    assert call(*ok_args(tps=long_.ctypes.data)) == -1
+    seqs = np.array([300, 60], np.int32)                                 # budget 50 <= 60: fits, so the
+    assert call(*ok_args(tps=seqs.ctypes.data, wsb=64)) == -3            # next check (workspace) is reached
     assert keep["len"].tolist() == [10, 20, 30, 100]
 
 
@@ -224,10 +230,12 @@ def test_device_allocator_and_window_importance_argument_errors():
     assert call(4, p, 1000, 1000, 100, None, None, bud.ctypes.data, None, 0x2010, big, None) == -1
     s, keep = _fake_cache()
     wi = lambda *a: lib.xkv_window_importance(C.byref(s), *a)
-    assert wi(0, 2, p, p, 300, 8, 7, 0.0, None, p, big, None) == -1                     # no output
-    assert wi(0, 2, p, p, 300, 8, 6, 0.0, p, p, big, None) == -1                        # even pooling width
-    assert wi(0, 2, p, p, 300, 40, 7, 0.0, p, p, big, None) == -4
-    assert wi(0, 2, p, p, 300, 8, 7, 0.0, p, p, 64, None) == -3
+    assert wi(0, 2, p, p, 300, None, 8, 7, 0.0, None, p, big, None) == -1               # no output
+    assert wi(0, 2, p, p, 300, None, 8, 6, 0.0, p, p, big, None) == -1                  # even pooling width
+    assert wi(0, 2, p, p, 300, None, 40, 7, 0.0, p, p, big, None) == -4
+    assert wi(0, 2, p, p, 300, None, 8, 7, 0.0, p, p, 64, None) == -3
+    bad = np.array([300, 3], np.int32)
+    assert wi(0, 2, p, p, 300, bad.ctypes.data, 8, 7, 0.0, p, p, big, None) == -1       # prompt < window
 
 
 def test_workload_generators_are_seeded_and_consistent():
