@@ -67,7 +67,8 @@ struct PairDesc {
                     // in the finalize launch: first finalize workgroup of the region
 };
 
-struct AttendParams {
+// What every launch carries besides the geometry tables.
+struct AttendCommon {
   const void* q;
   const void* k_new;
   const void* v_new;
@@ -89,10 +90,30 @@ struct AttendParams {
   int32_t rec_floats;     // floats per strip record in the workspace
   int32_t lds_rows;       // fused kernel: rows of logits a workgroup can hold
   int32_t fin_strips;     // finalize kernel: strips per workgroup
+};
+
+// Geometry of up to kMaxPairs regions inside the kernel arguments: nothing is
+// copied to the device for such a call.
+struct AttendParams : AttendCommon {
   PairDesc pairs[kMaxPairs];
   int32_t pos_new[kMaxPairs];    // original position of the token appended to each region
   uint8_t tail_order[kMaxPairs]; // regions with a partial last strip, longest tail first
 };
+
+// Geometry of a call with more regions: the same tables in device memory (in the
+// caller's workspace, written there by table_write launches), so that the whole
+// call is still one streaming launch and one finalize launch.
+struct AttendTableParams : AttendCommon {
+  const PairDesc* pairs;
+  const int32_t* pos_new;
+  const int32_t* tail_order;
+  const int32_t* fin0;           // first finalize workgroup of each region
+};
+
+// First finalize workgroup of region i: with the tables in the arguments the host
+// rewrites full0 between the two launches.
+__device__ __forceinline__ int fin_first(const AttendParams& P, int i) { return P.pairs[i].full0; }
+__device__ __forceinline__ int fin_first(const AttendTableParams& P, int i) { return P.fin0[i]; }
 
 // Floats per strip record: per query head, strip_rows logits, D partial outputs,
 // (m, l); padded so that every record starts on a 128-byte line.
@@ -105,7 +126,8 @@ struct StripWork { int pair_local, h, s; };
 // Streaming kernels: full strips first (all the same size), then the partial
 // last strips of the streams, longest first, so that short work fills the end
 // of the launch.
-__device__ __forceinline__ StripWork locate_stream_block(const AttendParams& P, int bid) {
+template <typename PT>
+__device__ __forceinline__ StripWork locate_stream_block(const PT& P, int bid) {
   StripWork w;
   if (bid < P.full_blocks) {
     int lo = 0, hi = P.n_pairs - 1;
@@ -184,8 +206,8 @@ struct StreamCtx {
 
   // Stream (region pair_local, head h_) of the launch; append_here says whether
   // the caller's row range may hold the appended token.
-  __device__ __forceinline__ void init_stream(const AttendParams& P, int pair_local, int h_,
-                                              bool may_append) {
+  template <typename PT>
+  __device__ __forceinline__ void init_stream(const PT& P, int pair_local, int h_, bool may_append) {
     const PairDesc pd = P.pairs[pair_local];
     n = pd.n; h = h_; s = 0;
     pair = P.pair_base + pair_local;
@@ -201,7 +223,8 @@ struct StreamCtx {
     }
     rec = nullptr;
   }
-  __device__ __forceinline__ void init(const AttendParams& P, const StripWork& wk) {
+  template <typename PT>
+  __device__ __forceinline__ void init(const PT& P, const StripWork& wk) {
     const PairDesc pd = P.pairs[wk.pair_local];
     const int nstrips = (pd.n + P.strip_rows - 1) / P.strip_rows;
     init_stream(P, wk.pair_local, wk.h, wk.s == nstrips - 1);   // row n-1 lies in the last strip
@@ -209,7 +232,8 @@ struct StreamCtx {
     rec = P.ws + (static_cast<int64_t>(pd.strip0) + static_cast<int64_t>(h) * nstrips + s) * P.rec_floats;
   }
   // Queries of the group, widened to fp32, this lane's columns only.
-  __device__ __forceinline__ void load_q(const AttendParams& P, int cl, float (&qf)[G][EPL]) const {
+  template <typename PT>
+  __device__ __forceinline__ void load_q(const PT& P, int cl, float (&qf)[G][EPL]) const {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       const int64_t hq = (static_cast<int64_t>(pair) * P.n_kv_heads + h) * G + g;
@@ -229,8 +253,8 @@ struct StreamCtx {
 // to LDS (lg[g * lg_stride + row - r_begin]); the four waves merge at the end
 // and the segment's partial output o[G][D] and statistics ml[G][2] are written
 // with `put`.  Ends with a barrier, after which mrg_sh may be reused.
-template <typename T, int D, int G, int TPI, typename Put>
-__device__ __forceinline__ void segment_pass(const AttendParams& P, const StreamCtx<T, D, G>& cx,
+template <typename T, int D, int G, int TPI, typename PT, typename Put>
+__device__ __forceinline__ void segment_pass(const PT& P, const StreamCtx<T, D, G>& cx,
                                              int r_begin, int r_end, float* lg, int lg_stride,
                                              float (*mrg_sh)[G][D + 2], float* rec_o, float* rec_ml,
                                              Put put) {
@@ -378,8 +402,8 @@ __device__ __forceinline__ void segment_pass(const AttendParams& P, const Stream
 // ---------------------------------------------------------------------------
 // Strip kernel for small query groups: one workgroup per (stream, strip); the
 // strip's logits are collected in LDS and written in one burst.
-template <typename T, int D, int G, int TPI>
-__global__ __launch_bounds__(kThreads) void attend_strip(const AttendParams P) {
+template <typename T, int D, int G, int TPI, typename PT = AttendParams>
+__global__ __launch_bounds__(kThreads) void attend_strip(const PT P) {
   extern __shared__ float lg_sh[];          // [G][strip_rows] logits of the strip
   __shared__ float mrg_sh[kWaves][G][D + 2];
 
@@ -592,8 +616,8 @@ __global__ __launch_bounds__(kThreads) void attend_fused(const AttendParams P) {
 // ---------------------------------------------------------------------------
 // Chunk kernel for larger query groups: strips are kChunk slots, the workgroup
 // makes one pass (thread t owns slot t for the statistics).
-template <typename T, int D, int G>
-__global__ __launch_bounds__(kThreads) void attend_chunk(const AttendParams P) {
+template <typename T, int D, int G, typename PT = AttendParams>
+__global__ __launch_bounds__(kThreads) void attend_chunk(const PT P) {
   using Ctx = StreamCtx<T, D, G>;
   constexpr int EPL = Ctx::EPL, LPR = Ctx::LPR, RPW = Ctx::RPW, ROWB = Ctx::ROWB;
   constexpr int NT = 64 / RPW;              // loads per wave for its 64 rows
@@ -815,8 +839,8 @@ __global__ __launch_bounds__(kThreads) void attend_chunk(const AttendParams P) {
 //            with byte permutes; MFMA c then produces channels 8 x + c.
 // A probability enters the MFMA as the sum of two bf16 numbers (the rounded
 // value and the rounded remainder), which keeps its relative error below 2^-16.
-template <int G>
-__global__ __launch_bounds__(kThreads) void attend_gqa(const AttendParams P) {
+template <int G, typename PT = AttendParams>
+__global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
   constexpr int D = 128, ROWB = 256, NS = D / 32, kTile = 32;
   typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
   __shared__ float o_sh[kWaves][G][D];
@@ -1043,8 +1067,8 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const AttendParams P) {
 
 // ---------------------------------------------------------------------------
 // kByRow: the record's logits are stored [slot][head] (attend_gqa) instead of [head][slot].
-template <int D, int G, bool kByRow = false>
-__global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P) {
+template <int D, int G, bool kByRow = false, typename PT = AttendParams>
+__global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
   constexpr int GD = G * D;
   extern __shared__ float w_sh[];           // [G][nstrips] strip weights 2^(m_s - m) / l
   __shared__ float m_sh[G], inv_sh[G];
@@ -1058,19 +1082,19 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P
   const int F = P.fin_strips;
   const int64_t REC = record_floats(G, D, strip_rows);
 
-  // Region: last pair whose first finalize workgroup is <= bid (in this launch
-  // full0 holds that number).  An empty stream owns one strip and one workgroup.
+  // Region: last pair whose first finalize workgroup is <= bid.  An empty stream
+  // owns one strip and one workgroup.
   int lo = 0, hi = P.n_pairs - 1;
   while (lo < hi) {
     const int mid = (lo + hi + 1) >> 1;
-    if (P.pairs[mid].full0 <= bid) lo = mid; else hi = mid - 1;
+    if (fin_first(P, mid) <= bid) lo = mid; else hi = mid - 1;
   }
   const PairDesc pd = P.pairs[lo];
   const int n = pd.n;
   const int nstrips_live = (n + strip_rows - 1) / strip_rows;
   const int nstrips = nstrips_live > 0 ? nstrips_live : 1;
   const int nfin = (nstrips + F - 1) / F;
-  const int local = bid - pd.full0;
+  const int local = bid - fin_first(P, lo);
   const int h = local / nfin;
   const int f_own = local - h * nfin;
   const int pair = P.pair_base + lo;
@@ -1171,11 +1195,36 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const AttendParams P
 }
 
 // ---------------------------------------------------------------------------
+// Writes one chunk of the geometry tables of a large call into device memory: the
+// entries travel in the kernel arguments, so no host-to-device copy is involved
+// and the call stays capturable in a graph.
+constexpr int kTableChunk = 96;
+struct TableChunk {
+  int32_t first, count;
+  PairDesc pairs[kTableChunk];
+  int32_t pos_new[kTableChunk];
+  int32_t tail_order[kTableChunk];
+  int32_t fin0[kTableChunk];
+};
+
+__global__ void table_write(const TableChunk c, PairDesc* pairs, int32_t* pos_new, int32_t* tail_order,
+                            int32_t* fin0) {
+  const int i = threadIdx.x;
+  if (i >= c.count) return;
+  pairs[c.first + i] = c.pairs[i];
+  pos_new[c.first + i] = c.pos_new[i];
+  tail_order[c.first + i] = c.tail_order[i];
+  fin0[c.first + i] = c.fin0[i];
+}
+
 using KernelFn = void (*)(const AttendParams);
+using TableKernelFn = void (*)(const AttendTableParams);
 struct Kernels {
   KernelFn stream = nullptr;
   KernelFn finalize = nullptr;
   KernelFn fused = nullptr;
+  TableKernelFn stream_tab = nullptr;      // the same kernels with the geometry tables in device memory
+  TableKernelFn finalize_tab = nullptr;
   int max_strip_rows = kChunk;  // longest strip the streaming kernel is given (a power of two)
   bool lds_logits = false;      // the streaming kernel collects the strip's logits in dynamic LDS
 };
@@ -1185,26 +1234,38 @@ bool pick_group(int group, Kernels* k) {
   switch (group) {
     case 1:
       k->stream = attend_strip<T, D, 1, 8>; k->finalize = attend_finalize<D, 1>;
+      k->stream_tab = attend_strip<T, D, 1, 8, AttendTableParams>;
+      k->finalize_tab = attend_finalize<D, 1, false, AttendTableParams>;
       k->max_strip_rows = kMaxStripRows; k->lds_logits = true;
       k->fused = attend_fused<T, D, 1, 8>;
       return true;
     case 2:
       k->stream = attend_strip<T, D, 2, 8>; k->finalize = attend_finalize<D, 2>;
+      k->stream_tab = attend_strip<T, D, 2, 8, AttendTableParams>;
+      k->finalize_tab = attend_finalize<D, 2, false, AttendTableParams>;
       k->max_strip_rows = kMaxStripRows; k->lds_logits = true;
       k->fused = attend_fused<T, D, 2, 8>;
       return true;
     case 4:
       k->stream = attend_chunk<T, D, 4>; k->finalize = attend_finalize<D, 4>;
+      k->stream_tab = attend_chunk<T, D, 4, AttendTableParams>;
+      k->finalize_tab = attend_finalize<D, 4, false, AttendTableParams>;
       k->fused = attend_fused<T, D, 4, 4>;
       if constexpr (std::is_same<T, BF16>::value && D == 128) {
         k->stream = attend_gqa<4>; k->finalize = attend_finalize<D, 4, true>; k->max_strip_rows = kGqaStripRows;
+        k->stream_tab = attend_gqa<4, AttendTableParams>;
+        k->finalize_tab = attend_finalize<D, 4, true, AttendTableParams>;
       }
       return true;
     case 8:
       k->stream = attend_chunk<T, D, 8>; k->finalize = attend_finalize<D, 8>;
+      k->stream_tab = attend_chunk<T, D, 8, AttendTableParams>;
+      k->finalize_tab = attend_finalize<D, 8, false, AttendTableParams>;
       k->fused = attend_fused<T, D, 8, 2>;
       if constexpr (std::is_same<T, BF16>::value && D == 128) {
         k->stream = attend_gqa<8>; k->finalize = attend_finalize<D, 8, true>; k->max_strip_rows = kGqaStripRows;
+        k->stream_tab = attend_gqa<8, AttendTableParams>;
+        k->finalize_tab = attend_finalize<D, 8, true, AttendTableParams>;
       }
       return true;
     default: return false;
@@ -1384,6 +1445,8 @@ size_t attend_workspace_bytes(const xkv_cache* c, int32_t layers) {
   std::sort(need.begin(), need.end(), std::greater<size_t>());
   size_t tot = 0;
   for (int32_t l = 0; l < layers && l < c->n_layers; ++l) tot += need[l];
+  // geometry tables of a call with more than kMaxPairs regions
+  tot += static_cast<size_t>(std::min(layers, c->n_layers)) * c->batch * (sizeof(PairDesc) + 12) + 1024;
   return tot;
 }
 
@@ -1476,6 +1539,87 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
   P.lds_rows = 0;
   P.fin_strips = fin_strips;
   P.barrier = nullptr;
+
+  if (n_pairs > kMaxPairs) {
+    // More regions than the kernel arguments hold: the tables go to device memory
+    // (behind the strip records in the workspace) and the call is still one
+    // streaming launch and one finalize launch.
+    if (n_pairs > std::numeric_limits<int32_t>::max() / 2) return XKV_ERR_UNSUPPORTED;
+    const size_t np = static_cast<size_t>(n_pairs);
+    std::vector<PairDesc> hp(np);
+    std::vector<int32_t> hpos(np), horder(np, 0), hfin(np), tail_len(np);
+    int64_t strips = 0, full = 0, fin_blocks = 0, tails = 0;
+    for (size_t i = 0; i < np; ++i) {
+      const int64_t idx = first + static_cast<int64_t>(i);
+      PairDesc& pd = hp[i];
+      pd.slot0 = cache->region_off[idx];
+      pd.cap = cache->cap[idx];
+      pd.n = cache->len[idx] + (append ? 1 : 0);
+      if (strips > std::numeric_limits<int32_t>::max() || full > std::numeric_limits<int32_t>::max() ||
+          fin_blocks > std::numeric_limits<int32_t>::max())
+        return XKV_ERR_UNSUPPORTED;
+      pd.strip0 = static_cast<int32_t>(strips);
+      pd.full0 = static_cast<int32_t>(full);
+      hfin[i] = static_cast<int32_t>(fin_blocks);
+      hpos[i] = append ? pos_new[i % B] : 0;
+      const int64_t nstrips = std::max<int64_t>(ceil_div(pd.n, strip_rows), 1);
+      strips += nstrips * hkv;
+      full += static_cast<int64_t>(pd.n / strip_rows) * hkv;
+      fin_blocks += ceil_div(nstrips, fin_strips) * hkv;
+      tail_len[i] = pd.n % strip_rows;
+      if (tail_len[i] > 0) horder[tails++] = static_cast<int32_t>(i);
+    }
+    std::stable_sort(horder.begin(), horder.begin() + tails,
+                     [&](int32_t a, int32_t b) { return tail_len[a] > tail_len[b]; });
+    const int64_t blocks = full + tails * hkv;
+    if (strips > std::numeric_limits<int32_t>::max() || blocks > std::numeric_limits<int32_t>::max() ||
+        fin_blocks > std::numeric_limits<int32_t>::max())
+      return XKV_ERR_UNSUPPORTED;
+    const size_t rec_bytes = (static_cast<size_t>(total_strips) * rec * sizeof(float) + 255) / 256 * 256;
+    const size_t table_bytes = np * (sizeof(PairDesc) + 12);
+    if (rec_bytes + table_bytes > workspace_bytes) return XKV_ERR_CAPACITY;
+    char* tb = static_cast<char*>(workspace) + rec_bytes;
+    PairDesc* d_pairs = reinterpret_cast<PairDesc*>(tb);
+    int32_t* d_pos = reinterpret_cast<int32_t*>(tb + np * sizeof(PairDesc));
+    int32_t* d_order = d_pos + np;
+    int32_t* d_fin = d_order + np;
+    for (size_t c0 = 0; c0 < np; c0 += kTableChunk) {
+      TableChunk ch;
+      ch.first = static_cast<int32_t>(c0);
+      ch.count = static_cast<int32_t>(std::min<size_t>(kTableChunk, np - c0));
+      for (int i = 0; i < ch.count; ++i) {
+        ch.pairs[i] = hp[c0 + i];
+        ch.pos_new[i] = hpos[c0 + i];
+        ch.tail_order[i] = horder[c0 + i];
+        ch.fin0[i] = hfin[c0 + i];
+      }
+      hipLaunchKernelGGL(table_write, dim3(1), dim3(128), 0, stream, ch, d_pairs, d_pos, d_order, d_fin);
+    }
+    if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+    AttendTableParams T;
+    static_cast<AttendCommon&>(T) = static_cast<const AttendCommon&>(P);
+    T.pairs = d_pairs;
+    T.pos_new = d_pos;
+    T.tail_order = d_order;
+    T.fin0 = d_fin;
+    T.n_pairs = static_cast<int32_t>(n_pairs);
+    T.pair_base = 0;
+    T.full_blocks = static_cast<int32_t>(full);
+    T.n_tail_pairs = static_cast<int32_t>(tails);
+    T.ws = static_cast<float*>(workspace);
+    if (blocks > 0) {
+      const int tok = profile_begin(0, stream);
+      hipLaunchKernelGGL(kern.stream_tab, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), stream_lds,
+                         stream, T);
+      profile_end(tok, stream);
+      if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+    }
+    hipLaunchKernelGGL(kern.finalize_tab, dim3(static_cast<unsigned>(fin_blocks)), dim3(kThreads), fin_lds,
+                       stream, T);
+    if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+    for (int64_t i = 0; append && i < n_pairs; ++i) cache->len[first + i] += 1;
+    return XKV_OK;
+  }
 
   int64_t strips_done = 0;
   for (int64_t g0 = 0; g0 < n_pairs; g0 += kMaxPairs) {

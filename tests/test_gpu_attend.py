@@ -108,12 +108,18 @@ def test_layer_subrange_and_custom_scale(xkv):
              layer_range=(1, 3))
 
 
-def test_many_regions_span_several_launch_groups(xkv):
-    """More (layer, sequence) regions than one launch describes."""
+@pytest.mark.parametrize("dtype,d,Hq,Hkv", [("bf16", 128, 4, 1), ("bf16", 128, 2, 2), ("f32", 64, 8, 2),
+                                            ("f32", 64, 1, 1), ("bf16", 128, 16, 2)])
+def test_more_regions_than_the_kernel_arguments_hold(xkv, dtype, d, Hq, Hkv):
+    """More than 128 (layer, sequence) regions: the geometry tables go through device memory and
+    the call is one launch (every streaming kernel has such a variant); the fused path still
+    works in groups."""
     L, B = 5, 60
-    r = np.random.default_rng(0)
+    r = np.random.default_rng(Hq)
     lens = r.integers(0, 400, size=(L, B))
-    run_case(xkv, "bf16", 128, 4, 1, L, B, lens, True, seed=5)
+    lens[0, :3] = [0, 1, 1400]
+    run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, True, seed=5)
+    run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, False, seed=6, paths=(0,), layer_range=(1, 4))
 
 
 def test_long_stream_many_chunks(xkv):
