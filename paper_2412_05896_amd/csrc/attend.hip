@@ -32,9 +32,11 @@
 //                    score[j] for its own slots, and computes its share of the
 //                    channels of out = sum_s 2^(m_s - m) o_s / l.
 //
-// The ragged geometry travels in the kernel arguments (at most kMaxPairs
-// (layer, sequence) regions per launch), so nothing is copied to the device
-// and the launches can be captured in a HIP graph.
+// The ragged geometry travels in the kernel arguments: up to kMaxPairs (layer,
+// sequence) regions directly, more through tables that small launches write into
+// the workspace from their own arguments.  Nothing is copied from the host, the
+// launches can be captured in a HIP graph, and a call is one streaming launch and
+// one finalize launch whatever its size.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>

@@ -42,7 +42,7 @@ struct EvictPair {
   int32_t ws0;     // first workspace word of the region (per array)
 };
 
-struct EvictParams {
+struct EvictCommon {
   void* k;
   void* v;
   float* score;
@@ -59,13 +59,32 @@ struct EvictParams {
   int32_t row_bytes;
   int32_t fused;
   int32_t small;         // every stream evicts at most kSmallE tokens
+};
+
+// Geometry of up to kMaxPairs regions inside the kernel arguments, or, for larger
+// calls, in device memory (written there from kernel arguments by evict_table_write),
+// so that a call is one selection launch whatever its size.
+struct EvictParams : EvictCommon {
   EvictPair pairs[kMaxPairs];
 };
+struct EvictTableParams : EvictCommon {
+  const EvictPair* pairs;
+};
+
+constexpr int kEvictTableChunk = 160;
+struct EvictTableChunk {
+  int32_t first, count;
+  EvictPair pairs[kEvictTableChunk];
+};
+__global__ void evict_table_write(const EvictTableChunk c, EvictPair* pairs) {
+  const int i = threadIdx.x;
+  if (i < c.count) pairs[c.first + i] = c.pairs[i];
+}
 
 __device__ __forceinline__ int ws_stride(int n) { return (n + kWsAlign - 1) / kWsAlign * kWsAlign; }
 
 // Copies the token at slot src over slot dst: K row, V row, score, pos.
-__device__ __forceinline__ void move_row(const EvictParams& P, int64_t stream_slot, int dst, int src,
+__device__ __forceinline__ void move_row(const EvictCommon& P, int64_t stream_slot, int dst, int src,
                                          int lane) {
   const int frags = P.row_bytes >> 4;
   if (lane < frags) {
@@ -86,7 +105,8 @@ __device__ __forceinline__ void move_row(const EvictParams& P, int64_t stream_sl
   }
 }
 
-__global__ __launch_bounds__(kSelThreads) void evict_select(const EvictParams P) {
+template <typename PT>
+__global__ __launch_bounds__(kSelThreads) void evict_select(const PT P) {
   __shared__ RadixShared radix_sh;
   __shared__ int scan_sh[kSelWaves];
   __shared__ int cnt_sh[3][kSelWaves];
@@ -287,7 +307,8 @@ __global__ __launch_bounds__(kSelThreads) void evict_select(const EvictParams P)
   for (int i = wave; i < carry_h; i += kSelWaves) move_row(P, stream_slot, hole_l[i], mover_l[i], lane);
 }
 
-__global__ __launch_bounds__(kMoveThreads) void evict_move(const EvictParams P) {
+template <typename PT>
+__global__ __launch_bounds__(kMoveThreads) void evict_move(const PT P) {
   const int u = blockIdx.x;
   const int moves = P.ws_count[u];
   if (moves == 0) return;
@@ -356,7 +377,10 @@ extern "C" xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, i
     words += ceil_div(n, kWsAlign) * kWsAlign * hkv;
   }
   const int64_t units = n_pairs * hkv;
-  const uint64_t need_bytes = static_cast<uint64_t>(words) * 12 + static_cast<uint64_t>(units) * 4;
+  // keys, holes, movers; a move counter per stream; the region table of a large call
+  const uint64_t table_off = (static_cast<uint64_t>(words) * 12 + static_cast<uint64_t>(units) * 4 + 255) / 256 * 256;
+  const uint64_t need_bytes = n_pairs > kMaxPairs ? table_off + static_cast<uint64_t>(n_pairs) * sizeof(EvictPair)
+                                                  : static_cast<uint64_t>(words) * 12 + static_cast<uint64_t>(units) * 4;
   if (workspace == nullptr || need_bytes > workspace_bytes) return XKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return XKV_ERR_INVALID_ARG;
 
@@ -378,38 +402,53 @@ extern "C" xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, i
     const unsigned move_blocks =
         static_cast<unsigned>(std::min<int64_t>(64, std::max<int64_t>(1, ceil_div(max_moves, 64))));
 
-    int64_t word0 = 0;
-    for (int64_t g0 = 0; g0 < n_pairs; g0 += kMaxPairs) {
-      const int np = static_cast<int>(std::min<int64_t>(kMaxPairs, n_pairs - g0));
-      // A launch addresses its workspace with 32-bit word offsets.
-      P.ws_keys = static_cast<uint32_t*>(workspace) + word0;
-      P.ws_holes = reinterpret_cast<int32_t*>(static_cast<uint32_t*>(workspace) + words) + word0;
-      P.ws_movers = reinterpret_cast<int32_t*>(static_cast<uint32_t*>(workspace) + 2 * words) + word0;
-      P.ws_count = counts + g0 * hkv;
+    if (words > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;   // 32-bit word offsets
+    P.ws_count = counts;
+    P.n_pairs = static_cast<int32_t>(n_pairs);
+    auto fill_pair = [&](EvictPair& pd, int64_t i, int64_t w) {
+      const int64_t idx = first + i;
+      pd.slot0 = cache->region_off[idx];
+      pd.cap = cache->cap[idx];
+      pd.n = cache->len[idx];
+      pd.k = static_cast<int32_t>(std::min<int64_t>(budgets[i], pd.n));
+      pd.ws0 = static_cast<int32_t>(w);
+      return w + ceil_div(pd.n, kWsAlign) * kWsAlign * hkv;
+    };
+    const dim3 sel_grid(static_cast<unsigned>(units));
+    const dim3 move_grid(static_cast<unsigned>(units), move_blocks);
+    if (n_pairs <= kMaxPairs) {
       int64_t w = 0;
-      for (int i = 0; i < np; ++i) {
-        const int64_t idx = first + g0 + i;
-        EvictPair& pd = P.pairs[i];
-        pd.slot0 = cache->region_off[idx];
-        pd.cap = cache->cap[idx];
-        pd.n = cache->len[idx];
-        pd.k = static_cast<int32_t>(std::min<int64_t>(budgets[g0 + i], pd.n));
-        if (w > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;
-        pd.ws0 = static_cast<int32_t>(w);
-        w += ceil_div(pd.n, kWsAlign) * kWsAlign * hkv;
-      }
-      P.n_pairs = np;
+      for (int64_t i = 0; i < n_pairs; ++i) w = fill_pair(P.pairs[i], i, w);
       const int tok = profile_begin(1, stream);
-      hipLaunchKernelGGL(evict_select, dim3(static_cast<unsigned>(np * hkv)), dim3(kSelThreads), 0,
-                         stream, P);
+      hipLaunchKernelGGL(evict_select<EvictParams>, sel_grid, dim3(kSelThreads), 0, stream, P);
       profile_end(tok, stream);
       if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
       if (!P.fused) {
-        hipLaunchKernelGGL(evict_move, dim3(static_cast<unsigned>(np * hkv), move_blocks),
-                           dim3(kMoveThreads), 0, stream, P);
+        hipLaunchKernelGGL(evict_move<EvictParams>, move_grid, dim3(kMoveThreads), 0, stream, P);
         if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
       }
-      word0 += w;
+    } else {
+      EvictPair* d_pairs = reinterpret_cast<EvictPair*>(static_cast<char*>(workspace) + table_off);
+      int64_t w = 0;
+      for (int64_t c0 = 0; c0 < n_pairs; c0 += kEvictTableChunk) {
+        EvictTableChunk ch;
+        ch.first = static_cast<int32_t>(c0);
+        ch.count = static_cast<int32_t>(std::min<int64_t>(kEvictTableChunk, n_pairs - c0));
+        for (int i = 0; i < ch.count; ++i) w = fill_pair(ch.pairs[i], c0 + i, w);
+        hipLaunchKernelGGL(evict_table_write, dim3(1), dim3(kEvictTableChunk), 0, stream, ch, d_pairs);
+      }
+      if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+      EvictTableParams T;
+      static_cast<EvictCommon&>(T) = static_cast<const EvictCommon&>(P);
+      T.pairs = d_pairs;
+      const int tok = profile_begin(1, stream);
+      hipLaunchKernelGGL(evict_select<EvictTableParams>, sel_grid, dim3(kSelThreads), 0, stream, T);
+      profile_end(tok, stream);
+      if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+      if (!T.fused) {
+        hipLaunchKernelGGL(evict_move<EvictTableParams>, move_grid, dim3(kMoveThreads), 0, stream, T);
+        if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+      }
     }
   }
   for (int64_t i = 0; i < n_pairs; ++i) {

@@ -61,9 +61,10 @@ size_t evict_workspace_bytes(const xkv_cache* c, int32_t layers) {
   // Per stream: keys, hole list and mover list (one 32-bit word per slot each,
   // slot counts rounded up to 32) and one move counter.
   const int hkv = c->n_kv_heads;
+  // ... and, for calls on more regions than the kernel arguments hold, 24 bytes per region.
   return top_layers_sum(c, layers, [=](int64_t cap) {
-    return static_cast<size_t>(hkv) * (static_cast<size_t>(ceil_div(cap, 32) * 32) * 12 + 4);
-  });
+    return static_cast<size_t>(hkv) * (static_cast<size_t>(ceil_div(cap, 32) * 32) * 12 + 4) + 24;
+  }) + 512;
 }
 
 // ---- per-kernel event timing ------------------------------------------------

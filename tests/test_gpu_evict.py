@@ -88,12 +88,17 @@ def test_steady_state_single_eviction_and_subrange(xkv):
              [[300, 32], [1000, 2048], [76, 4999]], 1, 0, seed=8, ties=True, with_kept=False)
 
 
-def test_many_regions_span_several_launch_groups(xkv):
+@pytest.mark.parametrize("pool,protect,top", [(1, 0, 300), (7, 8, 300), (1, 0, 3000)])
+def test_more_regions_than_the_kernel_arguments_hold(xkv, pool, protect, top):
+    """More than 128 regions: the region table goes through device memory and the call is one
+    selection launch (plus the move launch when streams move many rows, top = 3000)."""
     L, B = 3, 70
-    r = np.random.default_rng(1)
-    lens = r.integers(1, 300, size=(L, B))
-    budgets = np.maximum(1, (lens * r.random((L, B))).astype(np.int32))
-    run_case(xkv, "bf16", 64, 2, L, B, lens, budgets, 1, 0, seed=9, ties=True)
+    r = np.random.default_rng(1 + top)
+    lens = r.integers(1, top, size=(L, B))
+    budgets = np.maximum(max(1, protect), (lens * r.random((L, B))).astype(np.int32))
+    run_case(xkv, "bf16", 64, 2, L, B, lens, budgets, pool, protect, seed=9, ties=True)
+    # steady state of decoding: one eviction per stream
+    run_case(xkv, "f32", 64, 1, L, B, lens, np.maximum(lens - 1, max(1, protect)), pool, protect, seed=10, ties=False)
 
 
 @pytest.mark.parametrize("pool,protect", [(1, 0), (7, 8)])
