@@ -1199,8 +1199,9 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
 // ---------------------------------------------------------------------------
 // Writes one chunk of the geometry tables of a large call into device memory: the
 // entries travel in the kernel arguments, so no host-to-device copy is involved
-// and the call stays capturable in a graph.
-constexpr int kTableChunk = 96;
+// and the call stays capturable in a graph.  (Kernel arguments of this size, 36 KB,
+// are accepted by the HIP runtime here; 64 KB were tried.)
+constexpr int kTableChunk = 1024;
 struct TableChunk {
   int32_t first, count;
   PairDesc pairs[kTableChunk];
@@ -1595,7 +1596,7 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
         ch.tail_order[i] = horder[c0 + i];
         ch.fin0[i] = hfin[c0 + i];
       }
-      hipLaunchKernelGGL(table_write, dim3(1), dim3(128), 0, stream, ch, d_pairs, d_pos, d_order, d_fin);
+      hipLaunchKernelGGL(table_write, dim3(1), dim3(kTableChunk), 0, stream, ch, d_pairs, d_pos, d_order, d_fin);
     }
     if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     AttendTableParams T;

@@ -71,7 +71,7 @@ struct EvictTableParams : EvictCommon {
   const EvictPair* pairs;
 };
 
-constexpr int kEvictTableChunk = 160;
+constexpr int kEvictTableChunk = 1024;
 struct EvictTableChunk {
   int32_t first, count;
   EvictPair pairs[kEvictTableChunk];
