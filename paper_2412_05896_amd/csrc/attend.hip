@@ -1530,9 +1530,11 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
     return XKV_ERR_CAPACITY;
   const int64_t max_strips = std::max<int64_t>(ceil_div(max_n, strip_rows), 1);
   const size_t fin_lds = static_cast<size_t>(max_strips) * G * sizeof(float);
-  // A finalize workgroup covers up to kMaxStripRows slots, fewer when the call
-  // is small and would otherwise leave compute units without one.
-  int fin_strips = std::max(1, kMaxStripRows / strip_rows);
+  // A finalize workgroup covers up to kMaxStripRows slots, fewer when the streams are
+  // short or the call is small and would otherwise leave compute units without one.
+  // (short streams: 1024, which balances better; measured on the two GQA workloads)
+  const int fin_rows = total_rows / std::max<int64_t>(n_pairs * hkv, 1) < 8192 ? 1024 : kMaxStripRows;
+  int fin_strips = std::max(1, fin_rows / strip_rows);
   while (fin_strips > 1 && total_strips / fin_strips < 1024) fin_strips >>= 1;
   if (fin_lds > 48 * 1024) return XKV_ERR_UNSUPPORTED;
   const size_t stream_lds = kern.lds_logits ? static_cast<size_t>(G) * strip_rows * sizeof(float) : 0;
