@@ -10,10 +10,17 @@ from gpu_util import random_fill
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("dtype,d,Hq,Hkv", [("bf16", 128, 4, 4), ("bf16", 128, 8, 2), ("f32", 64, 4, 4)])
-def test_captured_step_replays_like_eager(xkv, dtype, d, Hq, Hkv):
-    L, B = 3, 2
-    budgets = np.array([[700, 300], [64, 1500], [256, 257]], np.int32)
+@pytest.mark.parametrize("dtype,d,Hq,Hkv,many", [("bf16", 128, 4, 4, False), ("bf16", 128, 8, 2, False),
+                                                 ("f32", 64, 4, 4, False), ("bf16", 128, 8, 2, True)])
+def test_captured_step_replays_like_eager(xkv, dtype, d, Hq, Hkv, many):
+    """many: more regions than the kernel arguments hold, so the graph also holds the launches
+    that write the geometry tables."""
+    if many:
+        L, B = 3, 50
+        budgets = np.random.default_rng(4).integers(8, 200, size=(L, B)).astype(np.int32)
+    else:
+        L, B = 3, 2
+        budgets = np.array([[700, 300], [64, 1500], [256, 257]], np.int32)
     caps = budgets + 8
 
     def fresh():
@@ -27,7 +34,7 @@ def test_captured_step_replays_like_eager(xkv, dtype, d, Hq, Hkv):
     qs = torch.randn((steps, L, B, Hq, d), generator=g).to(tdt).cuda()
     kns = torch.randn((steps, L, B, Hkv, d), generator=g).to(tdt).cuda()
     vns = torch.randn((steps, L, B, Hkv, d), generator=g).to(tdt).cuda()
-    pos_new = np.array([9000, 9001], np.int32)
+    pos_new = (9000 + np.arange(B)).astype(np.int32)
 
     # eager reference: the state after every step
     ref = fresh()
