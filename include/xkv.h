@@ -193,7 +193,9 @@ xkv_status xkv_workspace_bytes(const xkv_cache* cache, int32_t max_layers_per_ca
  *   out      DEVICE [layers][batch][n_q_heads][head_dim] fp32.  A stream with
  *            no live slot gives a zero row.
  *
- * Supported: head_dim 64 or 128, G in {1, 2, 4, 8}.
+ * Supported: head_dim 64 or 128, G in {1, 2, 4, 8}; streams of up to 12288 / G
+ * strips (strips are 256 to 4096 slots: 786 432 slots at G = 8 in the worst
+ * case), beyond which the call returns UNSUPPORTED.
  * Errors: INVALID_ARG, UNSUPPORTED, CAPACITY (len + 1 > cap on append, or the
  * workspace is too small), DEVICE.  Results are bit-reproducible: no atomics.
  */
