@@ -113,12 +113,16 @@ xkv_status xkv_average_allocations(int32_t n_samples, int32_t n_layers, const in
                                    const int64_t* max_budget, int64_t* budgets_out);
 
 /*
- * Device form of the allocation for XKV_ALLOC_TOTAL_SIZE (Alg. 1, Eq. 17), for
- * score vectors that already live on the device, such as the w_out of
- * xkv_window_importance: same result as xkv_allocate_budgets whenever no two
- * layers have contributions that agree to the last bit at the threshold (the
+ * Device form of the allocation (Alg. 1; Eq. 17 and Eq. 18), for score vectors
+ * that already live on the device, such as the w_out of xkv_window_importance.
+ * XKV_ALLOC_TOTAL_SIZE gives the same result as xkv_allocate_budgets whenever no
+ * two layers have contributions that agree to the last bit at the threshold (the
  * layer sums are added in a different order, which can move such a tie); the
  * retained importance R_avg of the result is the optimum in every case.
+ * XKV_ALLOC_TARGET_RAVG bisects the total-size solver for the smallest total whose
+ * R_avg reaches target_ravg (all tokens if none does); where R_avg of a total
+ * equals the target to within rounding, that total may differ from the host
+ * version's by the tokens whose contributions fall inside that rounding.
  *
  *   w             DEVICE fp32: layer l's len values start at w + l * layer_stride
  *                 (layer_stride >= len); non-negative and finite (not checked:
@@ -127,14 +131,15 @@ xkv_status xkv_average_allocations(int32_t n_samples, int32_t n_layers, const in
  *   workspace     DEVICE, 256-byte aligned, xkv_allocate_device_workspace_bytes
  *
  * Unlike the other device calls this one returns host results: it waits for
- * hip_stream (once per round of bound fixing, usually one or two rounds).
+ * hip_stream (once per round of bound fixing, usually one or two rounds; the
+ * target mode solves about log2(total tokens) total-size problems).
  * Supported: n_layers <= 256.  Errors: INVALID_ARG, INFEASIBLE, UNSUPPORTED,
  * CAPACITY, DEVICE.
  */
 xkv_status xkv_allocate_device_workspace_bytes(int32_t n_layers, int64_t len, size_t* bytes_out);
 xkv_status xkv_allocate_budgets_device(int32_t n_layers, const float* w, int64_t len,
-                                       int64_t layer_stride, int64_t total_size,
-                                       const int64_t* min_budget,
+                                       int64_t layer_stride, int32_t mode, int64_t total_size,
+                                       double target_ravg, const int64_t* min_budget,
                                        const int64_t* max_budget, int64_t* budgets_out,
                                        double* ravg_out, void* workspace, size_t workspace_bytes,
                                        void* hip_stream);

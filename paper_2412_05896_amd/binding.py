@@ -87,8 +87,8 @@ def load():
     lib.xkv_allocate_device_workspace_bytes.argtypes = [C.c_int32, C.c_int64, C.POINTER(C.c_size_t)]
     lib.xkv_allocate_budgets_device.restype = C.c_int32
     lib.xkv_allocate_budgets_device.argtypes = [
-        C.c_int32, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
-        C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
+        C.c_int32, C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int64, C.c_double, C.c_void_p, C.c_void_p,
+        C.c_void_p, C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.xkv_average_allocations.restype = C.c_int32
     lib.xkv_average_allocations.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                             C.c_void_p]
@@ -307,7 +307,8 @@ def xkv_allocate_device_workspace_bytes(n_layers: int, length: int) -> int:
 
 
 def xkv_allocate_budgets_device(w, n_layers: int, length: int, layer_stride: int, total_size: int, workspace,
-                                min_budget=None, max_budget=None, stream=None):
+                                min_budget=None, max_budget=None, stream=None, mode: int = XKV_ALLOC_TOTAL_SIZE,
+                                target_ravg: float = 0.0):
     """w: device fp32 tensor; layer l's `length` values start at element l * layer_stride of it.
     Returns (budgets int64 [n_layers], R_avg).  Waits for the stream."""
     lo = None if min_budget is None else np.ascontiguousarray(min_budget, dtype=np.int64)
@@ -315,7 +316,8 @@ def xkv_allocate_budgets_device(w, n_layers: int, length: int, layer_stride: int
     out = np.zeros(int(n_layers), dtype=np.int64)
     ravg = C.c_double(0.0)
     st = load().xkv_allocate_budgets_device(
-        int(n_layers), _ptr(w), int(length), int(layer_stride), int(total_size), _ptr(lo), _ptr(hi),
+        int(n_layers), _ptr(w), int(length), int(layer_stride), int(mode), int(total_size), float(target_ravg),
+        _ptr(lo), _ptr(hi),
         out.ctypes.data, C.byref(ravg), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     _check(st, "xkv_allocate_budgets_device")

@@ -323,72 +323,14 @@ AllocLayout alloc_layout(int n_layers, int chunks) {
   return L;
 }
 
-}  // namespace
-}  // namespace xkv
-
-extern "C" xkv_status xkv_allocate_device_workspace_bytes(int32_t n_layers, int64_t len, size_t* bytes_out) {
-  using namespace xkv;
-  if (bytes_out == nullptr || n_layers <= 0 || len < 0) return XKV_ERR_INVALID_ARG;
-  if (n_layers > kMaxLayers) return XKV_ERR_UNSUPPORTED;
-  const int64_t chunks = std::max<int64_t>(1, ceil_div(len, kChunkElems));
-  if (chunks > 65535) return XKV_ERR_UNSUPPORTED;
-  *bytes_out = alloc_layout(n_layers, static_cast<int>(chunks)).total;
-  return XKV_OK;
-}
-
-extern "C" xkv_status xkv_allocate_budgets_device(int32_t n_layers, const float* w, int64_t len,
-                                                  int64_t layer_stride, int64_t total_size,
-                                                  const int64_t* min_budget,
-                                                  const int64_t* max_budget, int64_t* budgets_out,
-                                                  double* ravg_out, void* workspace,
-                                                  size_t workspace_bytes, void* hip_stream) {
-  using namespace xkv;
-  if (n_layers <= 0 || len < 0 || layer_stride < len || budgets_out == nullptr ||
-      (len > 0 && w == nullptr) || (reinterpret_cast<uintptr_t>(w) & 3u))
-    return XKV_ERR_INVALID_ARG;
-  if (n_layers > kMaxLayers) return XKV_ERR_UNSUPPORTED;
-  const int64_t chunks64 = std::max<int64_t>(1, ceil_div(len, kChunkElems));
-  if (chunks64 > 65535) return XKV_ERR_UNSUPPORTED;
-  const int chunks = static_cast<int>(chunks64);
-  std::vector<int64_t> lo(n_layers), hi(n_layers);
-  int64_t sum_lo = 0, sum_hi = 0;
-  for (int32_t l = 0; l < n_layers; ++l) {
-    lo[l] = min_budget ? min_budget[l] : 0;
-    hi[l] = max_budget ? std::min<int64_t>(max_budget[l], len) : len;
-    if (lo[l] < 0 || lo[l] > hi[l]) return XKV_ERR_INFEASIBLE;
-    sum_lo += lo[l];
-    sum_hi += hi[l];
-  }
-  if (total_size < sum_lo || total_size > sum_hi) return XKV_ERR_INFEASIBLE;
-  const AllocLayout L = alloc_layout(n_layers, chunks);
-  if (workspace == nullptr || L.total > workspace_bytes) return XKV_ERR_CAPACITY;
-  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return XKV_ERR_INVALID_ARG;
-
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  char* ws = static_cast<char*>(workspace);
-  AllocParams P;
-  P.w = w;
-  P.len = len;
-  P.stride = layer_stride;
-  P.n_layers = n_layers;
-  P.chunks = chunks;
-  P.part_sum = reinterpret_cast<double*>(ws + L.part_sum);
-  P.layer_sum = reinterpret_cast<double*>(ws + L.layer_sum);
-  P.hist = reinterpret_cast<unsigned*>(ws + L.hist);
-  P.state = reinterpret_cast<SelectState*>(ws + L.state);
-  P.part_gt = reinterpret_cast<long long*>(ws + L.part_gt);
-  P.part_eq = reinterpret_cast<long long*>(ws + L.part_eq);
-  P.part_kept = reinterpret_cast<double*>(ws + L.part_kept);
-  P.out_n = reinterpret_cast<long long*>(ws + L.out_n);
-  P.out_r = reinterpret_cast<double*>(ws + L.out_r);
-  for (auto& m : P.free_mask) m = 0ull;
-
-  const dim3 grid(static_cast<unsigned>(chunks), static_cast<unsigned>(n_layers));
-  hipLaunchKernelGGL(alloc_partial_sums, grid, dim3(kThreads), 0, stream, P);
-  hipLaunchKernelGGL(alloc_layer_sums, dim3((n_layers + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, P);
-  if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
-
-  std::vector<int64_t> n(n_layers, 0);
+// The total-size problem for `total_size` tokens on sums already computed:
+// budgets in n, R_avg of the result in *ravg (if not null).
+xkv_status solve_total(AllocParams& P, const dim3& grid, hipStream_t stream, const std::vector<int64_t>& lo,
+                       const std::vector<int64_t>& hi, int64_t total_size, std::vector<int64_t>& n,
+                       double* ravg_out) {
+  const int32_t n_layers = P.n_layers;
+  const int64_t len = P.len;
+  n.assign(n_layers, 0);
   std::vector<char> is_free(n_layers, 1);
   std::vector<long long> got(n_layers);
   for (int round = 0; round <= n_layers; ++round) {
@@ -437,8 +379,6 @@ extern "C" xkv_status xkv_allocate_budgets_device(int32_t n_layers, const float*
       if (under < over && n[l] > hi[l]) { n[l] = hi[l]; is_free[l] = 0; }
     }
   }
-  for (int32_t l = 0; l < n_layers; ++l) budgets_out[l] = n[l];
-
   if (ravg_out != nullptr) {
     // Layers that ended a threshold round hold their retained importance in
     // out_r; the others (fixed at a bound, or taken whole) get it from a
@@ -466,5 +406,103 @@ extern "C" xkv_status xkv_allocate_budgets_device(int32_t n_layers, const float*
     for (int32_t l = 0; l < n_layers; ++l) tot += r[l];
     *ravg_out = tot / n_layers;
   }
+  return XKV_OK;
+}
+
+}  // namespace
+}  // namespace xkv
+
+extern "C" xkv_status xkv_allocate_device_workspace_bytes(int32_t n_layers, int64_t len, size_t* bytes_out) {
+  using namespace xkv;
+  if (bytes_out == nullptr || n_layers <= 0 || len < 0) return XKV_ERR_INVALID_ARG;
+  if (n_layers > kMaxLayers) return XKV_ERR_UNSUPPORTED;
+  const int64_t chunks = std::max<int64_t>(1, ceil_div(len, kChunkElems));
+  if (chunks > 65535) return XKV_ERR_UNSUPPORTED;
+  *bytes_out = alloc_layout(n_layers, static_cast<int>(chunks)).total;
+  return XKV_OK;
+}
+
+extern "C" xkv_status xkv_allocate_budgets_device(int32_t n_layers, const float* w, int64_t len,
+                                                  int64_t layer_stride, int32_t mode,
+                                                  int64_t total_size, double target_ravg,
+                                                  const int64_t* min_budget,
+                                                  const int64_t* max_budget, int64_t* budgets_out,
+                                                  double* ravg_out, void* workspace,
+                                                  size_t workspace_bytes, void* hip_stream) {
+  using namespace xkv;
+  if (n_layers <= 0 || len < 0 || layer_stride < len || budgets_out == nullptr ||
+      (len > 0 && w == nullptr) || (reinterpret_cast<uintptr_t>(w) & 3u))
+    return XKV_ERR_INVALID_ARG;
+  if (mode != XKV_ALLOC_TOTAL_SIZE && mode != XKV_ALLOC_TARGET_RAVG) return XKV_ERR_INVALID_ARG;
+  if (mode == XKV_ALLOC_TARGET_RAVG && !(target_ravg >= 0.0 && target_ravg <= 1.0)) return XKV_ERR_INVALID_ARG;
+  if (n_layers > kMaxLayers) return XKV_ERR_UNSUPPORTED;
+  const int64_t chunks64 = std::max<int64_t>(1, ceil_div(len, kChunkElems));
+  if (chunks64 > 65535) return XKV_ERR_UNSUPPORTED;
+  const int chunks = static_cast<int>(chunks64);
+  std::vector<int64_t> lo(n_layers), hi(n_layers);
+  int64_t sum_lo = 0, sum_hi = 0;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    lo[l] = min_budget ? min_budget[l] : 0;
+    hi[l] = max_budget ? std::min<int64_t>(max_budget[l], len) : len;
+    if (lo[l] < 0 || lo[l] > hi[l]) return XKV_ERR_INFEASIBLE;
+    sum_lo += lo[l];
+    sum_hi += hi[l];
+  }
+  if (mode == XKV_ALLOC_TOTAL_SIZE && (total_size < sum_lo || total_size > sum_hi)) return XKV_ERR_INFEASIBLE;
+  const AllocLayout L = alloc_layout(n_layers, chunks);
+  if (workspace == nullptr || L.total > workspace_bytes) return XKV_ERR_CAPACITY;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return XKV_ERR_INVALID_ARG;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  AllocParams P;
+  P.w = w;
+  P.len = len;
+  P.stride = layer_stride;
+  P.n_layers = n_layers;
+  P.chunks = chunks;
+  P.part_sum = reinterpret_cast<double*>(ws + L.part_sum);
+  P.layer_sum = reinterpret_cast<double*>(ws + L.layer_sum);
+  P.hist = reinterpret_cast<unsigned*>(ws + L.hist);
+  P.state = reinterpret_cast<SelectState*>(ws + L.state);
+  P.part_gt = reinterpret_cast<long long*>(ws + L.part_gt);
+  P.part_eq = reinterpret_cast<long long*>(ws + L.part_eq);
+  P.part_kept = reinterpret_cast<double*>(ws + L.part_kept);
+  P.out_n = reinterpret_cast<long long*>(ws + L.out_n);
+  P.out_r = reinterpret_cast<double*>(ws + L.out_r);
+  for (auto& m : P.free_mask) m = 0ull;
+
+  const dim3 grid(static_cast<unsigned>(chunks), static_cast<unsigned>(n_layers));
+  hipLaunchKernelGGL(alloc_partial_sums, grid, dim3(kThreads), 0, stream, P);
+  hipLaunchKernelGGL(alloc_layer_sums, dim3((n_layers + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, P);
+  if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+
+  std::vector<int64_t> n;
+  xkv_status st = XKV_OK;
+  if (mode == XKV_ALLOC_TOTAL_SIZE) {
+    st = solve_total(P, grid, stream, lo, hi, total_size, n, ravg_out);
+    if (st != XKV_OK) return st;
+  } else {
+    // Eq. 18: the smallest total whose R_avg reaches the target.  R_avg does not
+    // decrease with the total, so the total-size solver is bisected over
+    // [sum of floors, sum of caps]; if even all tokens fall short, all are taken
+    // (the greedy of Alg. 1 ends the same way, with an empty wait list).
+    double r = 0.0;
+    int64_t a = sum_lo, b = sum_hi;
+    st = solve_total(P, grid, stream, lo, hi, a, n, &r);
+    if (st != XKV_OK) return st;
+    if (r < target_ravg) {
+      while (b - a > 1) {                       // invariant: R(a) < target, and b is the answer so far
+        const int64_t mid = a + (b - a) / 2;
+        st = solve_total(P, grid, stream, lo, hi, mid, n, &r);
+        if (st != XKV_OK) return st;
+        if (r >= target_ravg) b = mid; else a = mid;
+      }
+      st = solve_total(P, grid, stream, lo, hi, b, n, &r);
+      if (st != XKV_OK) return st;
+    }
+    if (ravg_out != nullptr) *ravg_out = r;
+  }
+  for (int32_t l = 0; l < n_layers; ++l) budgets_out[l] = n[l];
   return XKV_OK;
 }

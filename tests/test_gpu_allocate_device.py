@@ -125,3 +125,47 @@ def test_window_importance_then_allocate_then_prefill(xkv, dtype, d, G, Hkv):
     torch.cuda.synchronize()
     assert np.array_equal(cache.len.reshape(L, B), budgets)
     assert int(cache.len.sum()) == B * total
+
+
+def retained(curves, n):
+    """R_avg of an allocation, straight from Eq. 4."""
+    return float(np.mean([orc.retention_ratio(curves[l], int(n[l])) for l in range(len(n))]))
+
+
+@pytest.mark.parametrize("L,T,target", [(4, 1000, 0.5), (16, 3000, 0.8), (6, 20001, 0.93), (3, 50, 1.0), (5, 400, 0.0)])
+def test_target_mode_finds_the_smallest_total(xkv, L, T, target):
+    """Eq. 18 on the device: R_avg reaches the target, one token less does not; the total agrees
+    with the oracle's greedy (exactly, unless R_avg sits on the target to within rounding)."""
+    curves = np.stack(wl.zipf_importance_curves(L, T, seed=21 + L))
+    buf = torch.from_numpy(curves).cuda()
+    ws = torch.empty(xkv.xkv_allocate_device_workspace_bytes(L, T), dtype=torch.uint8, device="cuda")
+    got, ravg = xkv.xkv_allocate_budgets_device(buf, L, T, T, 0, ws, mode=xkv.XKV_ALLOC_TARGET_RAVG,
+                                                target_ravg=target)
+    ref, ravg_ref = orc.allocate_budgets([c for c in curves], target_ravg=target)
+    assert abs(ravg - retained(curves, got)) < 1e-9
+    assert ravg >= target - 1e-12
+    total = int(got.sum())
+    if total > 0:
+        less, r_less = xkv.xkv_allocate_budgets_device(buf, L, T, T, total - 1, ws)
+        assert r_less < target + 1e-12
+    assert abs(total - int(np.sum(ref))) <= 1, (total, int(np.sum(ref)))
+    if total == int(np.sum(ref)):
+        assert np.array_equal(got, np.asarray(ref))
+
+
+def test_target_mode_with_floors_and_caps(xkv):
+    r = np.random.default_rng(8)
+    L, T = 7, 900
+    curves = (r.random((L, T)) ** r.uniform(1, 5, size=(L, 1))).astype(np.float32)
+    lo = r.integers(0, 100, size=L).astype(np.int64)
+    hi = (lo + r.integers(50, 700, size=L)).astype(np.int64)
+    buf = torch.from_numpy(curves).cuda()
+    ws = torch.empty(xkv.xkv_allocate_device_workspace_bytes(L, T), dtype=torch.uint8, device="cuda")
+    for target in (0.3, 0.7, 0.999):
+        got, ravg = xkv.xkv_allocate_budgets_device(buf, L, T, T, 0, ws, min_budget=lo, max_budget=hi,
+                                                    mode=xkv.XKV_ALLOC_TARGET_RAVG, target_ravg=target)
+        ref, ravg_ref = orc.allocate_budgets([c for c in curves], target_ravg=target, min_budget=lo, max_budget=hi)
+        assert np.all(got >= lo) and np.all(got <= np.minimum(hi, T))
+        assert abs(int(got.sum()) - int(np.sum(ref))) <= 1
+        if int(got.sum()) == int(np.sum(ref)):
+            assert np.array_equal(got, np.asarray(ref)) and abs(ravg - ravg_ref) < 1e-9

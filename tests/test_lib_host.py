@@ -221,13 +221,15 @@ def test_device_allocator_and_window_importance_argument_errors():
     lo = np.array([10, 10, 10, 10], np.int64)
     hi = np.array([20, 20, 20, 5], np.int64)
     call = lambda *a: lib.xkv_allocate_budgets_device(*a)
-    assert call(4, p, 1000, 1000, 100, None, None, None, None, p, big, None) == -1      # no output
-    assert call(4, p, 1000, 999, 100, None, None, bud.ctypes.data, None, p, big, None) == -1   # stride < len
-    assert call(4, p, 1000, 1000, 4001, None, None, bud.ctypes.data, None, p, big, None) == -2  # more than there is
-    assert call(4, p, 1000, 1000, 30, lo.ctypes.data, None, bud.ctypes.data, None, p, big, None) == -2  # below the floors
-    assert call(4, p, 1000, 1000, 50, lo.ctypes.data, hi.ctypes.data, bud.ctypes.data, None, p, big, None) == -2  # floor > cap
-    assert call(4, p, 1000, 1000, 100, None, None, bud.ctypes.data, None, p, 64, None) == -3
-    assert call(4, p, 1000, 1000, 100, None, None, bud.ctypes.data, None, 0x2010, big, None) == -1
+    assert call(4, p, 1000, 1000, 0, 100, 0.0, None, None, None, None, p, big, None) == -1      # no output
+    assert call(4, p, 1000, 999, 0, 100, 0.0, None, None, bud.ctypes.data, None, p, big, None) == -1   # stride < len
+    assert call(4, p, 1000, 1000, 0, 4001, 0.0, None, None, bud.ctypes.data, None, p, big, None) == -2  # more than there is
+    assert call(4, p, 1000, 1000, 0, 30, 0.0, lo.ctypes.data, None, bud.ctypes.data, None, p, big, None) == -2  # below the floors
+    assert call(4, p, 1000, 1000, 0, 50, 0.0, lo.ctypes.data, hi.ctypes.data, bud.ctypes.data, None, p, big, None) == -2  # floor > cap
+    assert call(4, p, 1000, 1000, 0, 100, 0.0, None, None, bud.ctypes.data, None, p, 64, None) == -3
+    assert call(4, p, 1000, 1000, 0, 100, 0.0, None, None, bud.ctypes.data, None, 0x2010, big, None) == -1
+    assert call(4, p, 1000, 1000, 7, 100, 0.0, None, None, bud.ctypes.data, None, p, big, None) == -1    # unknown mode
+    assert call(4, p, 1000, 1000, 1, 0, 1.5, None, None, bud.ctypes.data, None, p, big, None) == -1     # target > 1
     s, keep = _fake_cache()
     wi = lambda *a: lib.xkv_window_importance(C.byref(s), *a)
     assert wi(0, 2, p, p, 300, None, 8, 7, 0.0, None, p, big, None) == -1               # no output
