@@ -28,8 +28,8 @@ What follows which passage of the paper (arXiv 2412.05896):
                         Pooling over the candidate vector, TopK, EvictByIndex as
                         an ordered gather.
 * ``retention_ratio``   Eq. 4 (R_i), as a fraction.
-* ``allocate_budgets``  Alg. 1 (allocation list + wait list greedy) for the
-                        two problems of Eq. 17 and Eq. 18.
+* ``allocate_budgets``  Alg. 1 (one token at a time to the layer with the largest
+                        next gain) for the two problems of Eq. 17 and Eq. 18.
 * ``average_allocations``  Sec. 4.3 (sampling-based overhead reduction): the
                         average of the allocation lists recorded on sampled
                         tasks, as an integer list for the next task.
@@ -318,95 +318,81 @@ def retention_ratio(w, n: int) -> float:
 # --------------------------------------------------------------------------
 # Alg. 1
 # --------------------------------------------------------------------------
-def _layer_tables(w):
-    """Per layer: values sorted ascending (the listing's Sort(W)) and their sum.
+def _normalised_gains(w):
+    """Per layer: gain[r] = (r+1)-th largest value / the layer's sum, float64.
 
-    The sum is taken in float64 over the ascending values, one after the
-    other, so its value does not depend on who computes it.
+    gain[r] is what L * R_avg grows by when the layer goes from r to r + 1
+    tokens (Eq. 21).  The sum is taken in float64 over the values in ascending
+    order, one after the other, so its value does not depend on who computes
+    it; a layer whose values sum to zero gains nothing from any token.
     """
-    srt, tot = [], []
+    gains = []
     for w_l in w:
         a = np.asarray(w_l, dtype=np.float32)
         if a.ndim != 1:
             raise ValueError("each w_l must be a vector")
         if not np.all(np.isfinite(a)) or np.any(a < 0):
             raise ValueError("w must be finite and non-negative")
-        a = np.sort(a).astype(np.float64)
-        srt.append(a)
-        tot.append(float(np.add.accumulate(a)[-1]) if a.size else 0.0)
-    return srt, tot
+        asc = np.sort(a).astype(np.float64)
+        total = float(np.add.accumulate(asc)[-1]) if asc.size else 0.0
+        desc = asc[::-1]
+        gains.append(desc / total if total != 0.0 else np.zeros_like(desc))
+    return gains
 
 
 def allocate_budgets(w, total_size=None, target_ravg=None, min_budget=None, max_budget=None):
-    """Greedy allocation with an allocation list and a wait list (Alg. 1).
+    """Greedy solver of the two allocation problems (Alg. 1; Eq. 17, Eq. 18).
 
     w            list of L vectors (any order, non-negative)
-    total_size   N of Eq. 17: fill until sum(n_l) = N        (first branch)
-    target_ravg  set value of Eq. 18, a fraction: fill until R_total/L >= it
-                 (second branch); exactly one of the two is given
+    total_size   N of Eq. 17: hand out tokens until sum(n_l) = N
+    target_ravg  set value of Eq. 18, a fraction: hand out tokens until
+                 R_avg >= it; exactly one of the two is given
     min_budget / max_budget  optional per-layer floors and caps
 
-    The wait-list entry of a layer whose current size is n is its (n+1)-th
-    largest value divided by the layer's sum, i.e. what R_avg*L gains from the
-    next token of that layer (Eq. 21); an exhausted layer waits with -inf.
-    Equal maxima go to the lowest layer index.
-    Returns (budgets int64 [L], R_avg fraction).
+    Every layer keeps a cursor n_l into its gains sorted in descending order.
+    One token at a time goes to the layer whose next gain (Eq. 21) is the
+    largest over all layers, the lowest layer index among equals; a layer at its
+    cap no longer takes part.  Returns (budgets int64 [L], R_avg fraction).
     """
     if (total_size is None) == (target_ravg is None):
         raise ValueError("give exactly one of total_size / target_ravg")
-    L = len(w)
-    srt, tot = _layer_tables(w)
-    lens = [a.size for a in srt]
-    lo = [0] * L if min_budget is None else [int(x) for x in min_budget]
-    hi = list(lens) if max_budget is None else [min(int(x), t) for x, t in zip(max_budget, lens)]
+    gains = _normalised_gains(w)
+    L = len(gains)
+    floor = [0] * L if min_budget is None else [int(x) for x in min_budget]
+    cap = [g.size for g in gains] if max_budget is None else \
+        [min(int(x), g.size) for x, g in zip(max_budget, gains)]
+    if any(floor[l] < 0 or floor[l] > cap[l] for l in range(L)):
+        raise ValueError("infeasible: floor above cap")
+
+    n = list(floor)
+    held = 0.0                                # L * R_avg of the current sizes
     for l in range(L):
-        if lo[l] < 0 or lo[l] > hi[l]:
-            raise ValueError("infeasible: floor above cap")
+        for r in range(n[l]):
+            held += gains[l][r]
+    nxt = np.array([gains[l][n[l]] if n[l] < cap[l] else -np.inf for l in range(L)], dtype=np.float64)
 
-    def contribution(l, n):                   # (n+1)-th largest, normalised
-        if n >= hi[l]:
-            return -np.inf
-        if tot[l] == 0.0:
-            return 0.0
-        return srt[l][-(n + 1)] / tot[l]
-
-    list_a = list(lo)                                         # allocation list
-    list_w = [contribution(l, list_a[l]) for l in range(L)]   # wait list
-    r_total = 0.0
-    for l in range(L):                        # importance already held by the floors
-        for r in range(list_a[l]):
-            r_total += (srt[l][-(r + 1)] / tot[l]) if tot[l] != 0.0 else 0.0
-
-    def step():
-        nonlocal r_total
-        maximum = max(list_w)
-        index = list_w.index(maximum)         # first (lowest) layer with the maximum
-        r_total += maximum
-        list_a[index] += 1
-        list_w[index] = contribution(index, list_a[index])
+    def give_one():
+        nonlocal held
+        l = int(np.argmax(nxt))               # first index of the maximum
+        held += nxt[l]
+        n[l] += 1
+        nxt[l] = gains[l][n[l]] if n[l] < cap[l] else -np.inf
 
     if total_size is not None:
         N = int(total_size)
-        if N < sum(lo) or N > sum(hi):
+        if N < sum(floor) or N > sum(cap):
             raise ValueError("infeasible total size")
-        for _ in range(N - sum(lo)):
-            step()
+        for _ in range(N - sum(floor)):
+            give_one()
     else:
         target = float(target_ravg)
-        while r_total / L < target and max(list_w) > -np.inf:
-            step()
+        while held / L < target and np.max(nxt) > -np.inf:
+            give_one()
 
-    ravg = 0.0
-    for l in range(L):
-        if tot[l] != 0.0 and list_a[l] > 0:
-            ravg += float(np.sum(srt[l][::-1][:list_a[l]] / tot[l]))
-    ravg /= L
-    return np.asarray(list_a, dtype=np.int64), ravg
+    ravg = sum(float(np.sum(gains[l][:n[l]])) for l in range(L) if n[l] > 0) / L
+    return np.asarray(n, dtype=np.int64), ravg
 
 
-# --------------------------------------------------------------------------
-# a unit with state, for multi-step runs
-# --------------------------------------------------------------------------
 # --------------------------------------------------------------------------
 # Sec. 4.3: averaged allocation list of sampled tasks
 # --------------------------------------------------------------------------
@@ -455,6 +441,9 @@ def average_allocations(lists, total_size: int, min_budget=None, max_budget=None
     return np.asarray(n, dtype=np.int64)
 
 
+# --------------------------------------------------------------------------
+# a unit with state, for multi-step runs
+# --------------------------------------------------------------------------
 class OracleUnit:
     """State of one (layer, sequence, KV head) across decode steps."""
 

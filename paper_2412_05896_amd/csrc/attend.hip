@@ -154,8 +154,11 @@ __device__ __forceinline__ StripWork locate_stream_block(const PT& P, int bid) {
 // Loads kNB consecutive wave-wide fragments of a stream (rows first_row,
 // first_row + RPW, ...) into registers, without branches: rows at or past n are
 // clamped to row n-1 (in bounds; their logits are masked later and their
-// probabilities are zero), and with append_here the lanes of row n-1 read the
-// token being appended from `newrow` instead of the not yet written slot.
+// probabilities are zero), and with append_here every lane that ends up on row
+// n-1, clamped ones included, reads the token being appended from `newrow`
+// instead of the not yet written slot: whatever that slot holds (the arenas are
+// the caller's; a dead slot may hold any bit pattern, NaN included) never
+// reaches a register, so 0 * V stays 0.
 template <int ROWB, int RPW, int kNB>
 __device__ __forceinline__ void load_rows(uint4 (&reg)[kNB], const char* base, const char* newrow,
                                           int first_row, int n, bool full, bool append_here,
@@ -172,7 +175,7 @@ __device__ __forceinline__ void load_rows(uint4 (&reg)[kNB], const char* base, c
       const int r = first_row + i * RPW;
       const int rc = r < n ? r : n - 1;
       const char* src = base + static_cast<int64_t>(rc) * ROWB + cl * 16;
-      if (append_here && r == n - 1) src = newrow + cl * 16;
+      if (append_here && rc == n - 1) src = newrow + cl * 16;
       reg[i] = load_stream16(src);
     }
   }
@@ -674,7 +677,7 @@ __global__ __launch_bounds__(kThreads) void attend_chunk(const PT P) {
         const int r = row0 + (g0 + gi) * 16 + x16;
         const int rc = r < n ? r : n - 1;
         const char* src = cx.kbase + static_cast<int64_t>(rc) * ROWB + j4 * 16;
-        if (append_here && r == n - 1) src = cx.knew + j4 * 16;
+        if (append_here && rc == n - 1) src = cx.knew + j4 * 16;
 #pragma unroll
         for (int sl = 0; sl < NS; ++sl) kb[gi][sl] = load_stream16(src + sl * 64);
       }

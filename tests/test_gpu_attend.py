@@ -10,7 +10,7 @@ pytestmark = pytest.mark.gpu
 
 
 def run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, append, seed, scale=0.0, layer_range=None, paths=(0, 1, 2),
-             fused_required=False):
+             fused_required=False, poison=False):
     """Runs the case once per attend path: 0 = the library's choice, 1 = streaming
     + finalize kernels, 2 = the fused cooperative launch (which may say that the
     call does not fit; that is accepted unless fused_required)."""
@@ -18,7 +18,7 @@ def run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, append, seed, scale=0.0, layer_
     for path in paths:
         xkv.xkv_configure(xkv.XKV_CFG_ATTEND_PATH, path)
         try:
-            r = _run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, append, seed, scale, layer_range)
+            r = _run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, append, seed, scale, layer_range, poison)
         except xkv.XkvError as e:
             if path == 2 and e.status == -4 and not fused_required:
                 continue
@@ -29,10 +29,16 @@ def run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, append, seed, scale=0.0, layer_
     return worst
 
 
-def _run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, append, seed, scale=0.0, layer_range=None):
+def _run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, append, seed, scale=0.0, layer_range=None, poison=False):
     lens = np.asarray(lens, np.int32).reshape(L, B)
     caps = lens + 2
     cache = xkv.XkvCache(L, B, Hq, Hkv, d, dtype, caps)
+    if poison:
+        # the arenas are the caller's: slots at or beyond len may hold anything
+        cache.k.fill_(float("nan"))
+        cache.v.fill_(float("nan"))
+        cache.score.fill_(float("nan"))
+        cache.pos.fill_(-12345)
     random_fill(cache, lens, seed)
     G = Hq // Hkv
     l0, l1 = layer_range or (0, L)
@@ -91,6 +97,20 @@ def test_fused_launch_is_really_taken(xkv, dtype, d, G):
     print(f"case fused dtype={dtype} d={d} G={G}", flush=True)
     run_case(xkv, dtype, d, 2 * G, 2, 3, 3, lens, True, seed=40 + G, paths=(2,), fused_required=True)
     run_case(xkv, dtype, d, 2 * G, 2, 3, 3, lens, False, seed=50 + G, paths=(2,), fused_required=True)
+
+
+@pytest.mark.parametrize("dtype,d,G", [("bf16", 128, 1), ("f32", 64, 1), ("bf16", 128, 2), ("f32", 128, 2),
+                                       ("f32", 64, 4), ("bf16", 64, 4), ("f32", 64, 8), ("bf16", 128, 4),
+                                       ("bf16", 128, 8)])
+@pytest.mark.parametrize("append", [True, False])
+def test_dead_slots_may_hold_nan(xkv, dtype, d, G, append):
+    """Every slot at or beyond len holds NaN bit patterns (K, V and score) before the
+    call: rows that the kernels clamp onto the last live row must never bring such a
+    slot into a register (0 * NaN would poison the output row).  All streaming
+    kernels: attend_strip (G <= 2), attend_chunk (fp32 / 64 channels), attend_gqa."""
+    lens = [[0, 1, 37], [255, 256, 300], [257, 700, 1029]]
+    print(f"case poison dtype={dtype} d={d} G={G} append={append}", flush=True)
+    run_case(xkv, dtype, d, 2 * G, 2, 3, 3, lens, append, seed=70 + G, poison=True)
 
 
 def test_empty_stream_without_append_gives_zero_row(xkv):
