@@ -187,7 +187,12 @@ xkv_status xkv_workspace_bytes(const xkv_cache* cache, int32_t max_layers_per_ca
  * for each of the G = n_q_heads/n_kv_heads query heads g of KV head h
  *     p_j   = softmax_j( scale * q_g . K_j )      over all len live slots
  *     out_g = sum_j p_j V_j
- * and score[j] += sum_g p_j.  Products are exact, sums are fp32.
+ * and score[j] += sum_g p_j.  Products of stored elements are exact and sums
+ * are fp32, with one exception: for bf16 caches with head_dim 128 and G >= 4 the
+ * output sum runs on the matrix cores, where each unnormalised probability
+ * enters as the sum of two bf16 numbers (its rounded value and the rounded
+ * remainder): a relative error below 2^-16 per term of out.  The scores do not
+ * take that route.
  *
  *   q        DEVICE [layers][batch][n_q_heads][head_dim], cache dtype; query
  *            head hq reads KV head hq / G
@@ -312,10 +317,33 @@ xkv_status xkv_window_importance(const xkv_cache* cache, int32_t layer_begin, in
  *       choice (default; at present the two kernels); 1 = a streaming kernel plus
  *       a finalize kernel; 2 = one fused cooperative launch that keeps the logits
  *       in LDS, or XKV_ERR_UNSUPPORTED when the call does not fit the chip at once.
+ *   XKV_CFG_FUSED_SPIN_LIMIT  polls of the fused launch's grid-wide wait before a
+ *       workgroup gives up (0 .. 2^30; -1 = the default, 2^24, several hundred
+ *       milliseconds).  For tests of the give-up path: with 0 every workgroup but
+ *       the last to arrive gives up at once, and the kernel still ends normally.
  * Errors: INVALID_ARG for an unknown key or value.
  */
-enum { XKV_CFG_ATTEND_PATH = 1 };
+enum { XKV_CFG_ATTEND_PATH = 1, XKV_CFG_FUSED_SPIN_LIMIT = 2 };
 xkv_status xkv_configure(int32_t key, int64_t value);
+
+/*
+ * How a caller learns that a fused launch (XKV_CFG_ATTEND_PATH = 2) gave up.
+ * The fused kernel's workgroups meet once at a grid-wide wait; it completes
+ * whenever all workgroups are resident, which the library ensures by sizing the
+ * grid from the occupancy query.  Should a workgroup nevertheless exhaust its
+ * polls, it raises a flag in the workspace; every workgroup that finds the flag up
+ * after the wait skips the merge: the out rows of the streams it worked on become
+ * NaN, and their scores and the pos of their appended tokens are not written (the
+ * appended K/V rows are in place and len has grown).  The remaining rows are
+ * complete.
+ *
+ * xkv_fused_status waits for the stream of the most recent fused
+ * xkv_decode_attend_score call of this process and stores 1 in gave_up_out if any
+ * of its launches raised the flag, else 0 (also 0 if there was no such call).  Call
+ * it before that call's workspace is used again or freed.
+ * Errors: INVALID_ARG, DEVICE.
+ */
+xkv_status xkv_fused_status(int32_t* gave_up_out);
 
 /*
  * Per-kernel timing for benchmarks.  While enabled, the device calls above record

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     XKV_ALLOC_TARGET_RAVG,
     XKV_ALLOC_TOTAL_SIZE,
     XKV_CFG_ATTEND_PATH,
+    XKV_CFG_FUSED_SPIN_LIMIT,
     XkvCache,
     XkvError,
     load,
@@ -20,6 +21,7 @@ from .binding import (  # noqa: F401
     xkv_configure,
     xkv_decode_attend_score,
     xkv_evict_compact,
+    xkv_fused_status,
     xkv_prefill_evict,
     xkv_prefill_workspace_bytes,
     xkv_probe_stream_read,

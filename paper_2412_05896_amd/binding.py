@@ -18,9 +18,10 @@ EXPORTS = (
     "xkv_decode_attend_score", "xkv_evict_compact", "xkv_profile_enable", "xkv_profile_read",
     "xkv_configure", "xkv_probe_stream_read", "xkv_prefill_workspace_bytes", "xkv_prefill_evict",
     "xkv_window_importance", "xkv_allocate_device_workspace_bytes", "xkv_allocate_budgets_device",
-    "xkv_average_allocations",
+    "xkv_average_allocations", "xkv_fused_status",
 )
 XKV_CFG_ATTEND_PATH = 1
+XKV_CFG_FUSED_SPIN_LIMIT = 2
 
 
 class XkvError(RuntimeError):
@@ -94,6 +95,8 @@ def load():
                                             C.c_void_p]
     lib.xkv_configure.restype = C.c_int32
     lib.xkv_configure.argtypes = [C.c_int32, C.c_int64]
+    lib.xkv_fused_status.restype = C.c_int32
+    lib.xkv_fused_status.argtypes = [C.POINTER(C.c_int32)]
     lib.xkv_probe_stream_read.restype = C.c_int32
     lib.xkv_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                           C.c_void_p]
@@ -326,6 +329,13 @@ def xkv_allocate_budgets_device(w, n_layers: int, length: int, layer_stride: int
 
 def xkv_configure(key: int, value: int):
     _check(load().xkv_configure(int(key), int(value)), "xkv_configure")
+
+
+def xkv_fused_status() -> bool:
+    """True if a launch of the most recent fused decode call gave up its grid-wide wait.  Waits for its stream."""
+    flag = C.c_int32(0)
+    _check(load().xkv_fused_status(C.byref(flag)), "xkv_fused_status")
+    return bool(flag.value)
 
 
 def xkv_probe_stream_read(buffer, non_temporal: bool, store_floats_per_workgroup: int = 0, sink=None,

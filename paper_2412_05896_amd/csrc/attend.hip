@@ -92,6 +92,7 @@ struct AttendCommon {
   int32_t rec_floats;     // floats per strip record in the workspace
   int32_t lds_rows;       // fused kernel: rows of logits a workgroup can hold
   int32_t fin_strips;     // finalize kernel: strips per workgroup
+  uint32_t spin_limit;    // fused kernel: polls of the grid-wide wait before a workgroup gives up
 };
 
 // Geometry of up to kMaxPairs regions inside the kernel arguments: nothing is
@@ -446,23 +447,28 @@ __global__ __launch_bounds__(kThreads) void attend_strip(const PT P) {
 // No cache maintenance is tied to it: what crosses it (the strip records) is
 // written and read with agent-scope accesses that bypass the per-XCD caches, and
 // the barrier before the count makes sure those writes have been acknowledged.
-// The wait is bounded: should the count never fill (it cannot, unless the
-// launch was not resident), the workgroup gives up, raises the flag next to the
-// counter and goes on, so the kernel always ends.
-__device__ __forceinline__ void grid_barrier(unsigned* counter, unsigned n_wgs) {
+// The wait is bounded: should the count not fill within spin_limit polls (it
+// always does, unless the launch was not resident), the workgroup gives up and
+// raises the flag next to the counter, so the kernel always ends.  Returns, to
+// every thread, whether the flag was up when this workgroup left the wait: the
+// strip records may then be incomplete, and the caller must not use them.
+__device__ __forceinline__ bool grid_barrier(unsigned* counter, unsigned n_wgs, unsigned spin_limit,
+                                             int* flag_sh) {
   __syncthreads();
   if (threadIdx.x == 0) {
     __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     unsigned spins = 0;
     while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < n_wgs) {
-      __builtin_amdgcn_s_sleep(4);
-      if (++spins > (1u << 24)) {
+      if (spins++ >= spin_limit) {
         __hip_atomic_store(counter + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         break;
       }
+      __builtin_amdgcn_s_sleep(4);
     }
+    *flag_sh = static_cast<int>(__hip_atomic_load(counter + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
   }
   __syncthreads();
+  return *flag_sh != 0;
 }
 
 // control words of a fused launch: {barrier count, barrier timeout flag, queue head, unused}
@@ -483,6 +489,7 @@ __global__ __launch_bounds__(kThreads) void attend_fused(const AttendParams P) {
   __shared__ float st_sh[G][2];
   __shared__ int held_sh[kMaxHeld];         // queue positions of the strips held
   __shared__ int next_sh;
+  __shared__ int gave_up_sh;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -512,7 +519,18 @@ __global__ __launch_bounds__(kThreads) void attend_fused(const AttendParams P) {
                                });
     ++n_held;
   }
-  grid_barrier(P.barrier, gridDim.x);
+  if (grid_barrier(P.barrier, gridDim.x, P.spin_limit, &gave_up_sh)) {
+    // Some workgroup gave up waiting: records may be missing.  Nothing is merged;
+    // the output rows of the streams this workgroup holds strips of become NaN and
+    // their scores stay as they were.  The host reads the flag with
+    // xkv_fused_status.
+    for (int k = 0; k < n_held; ++k) {
+      const StripWork wk = locate_stream_block(P, held_sh[k]);
+      float* out = P.out + (static_cast<int64_t>(P.pair_base + wk.pair_local) * P.n_kv_heads + wk.h) * G * D;
+      for (int idx = tid; idx < G * D; idx += kThreads) out[idx] = __builtin_nanf("");
+    }
+    return;
+  }
 
   // ---- phase 2: normalise, add to the scores, write the outputs -----------------
   for (int k = 0; k < n_held; ++k) {
@@ -1300,6 +1318,11 @@ int choose_strip_rows(int max_rows, int64_t streams, int64_t total_rows) {
 constexpr size_t kFusedLdsBudget = 72 * 1024;   // logits per workgroup; two workgroups share a compute unit
 
 int g_attend_path = 0;                          // 0 auto, 1 two kernels, 2 fused or error
+constexpr uint32_t kDefaultSpinLimit = 1u << 24; // polls of about 64 cycles each: several hundred ms
+uint32_t g_fused_spin_limit = kDefaultSpinLimit;
+// Control words of the most recent fused call, for xkv_fused_status.
+struct LastFused { const unsigned* control = nullptr; size_t launches = 0; hipStream_t stream = nullptr; };
+LastFused g_last_fused;
 // What "auto" picks.  On the 32k benchmark workload the fused launch is 5 % slower
 // than the two kernels (its grid barrier and second phase cost more than the logit
 // stores it saves), and its larger query groups run on the VALUs; it stays selectable.
@@ -1385,6 +1408,8 @@ xkv_status launch_fused(const xkv_cache* cache, int64_t first, int64_t n_pairs, 
   P.rec_floats = static_cast<int32_t>(seg);
   P.lds_rows = lds_rows;
   P.fin_strips = 1;
+  P.spin_limit = g_fused_spin_limit;
+  g_last_fused = LastFused{control0, 0, stream};
   int64_t strips_done = 0;
   for (size_t gi = 0; gi < groups.size(); ++gi) {
     const Group& gr = groups[gi];
@@ -1428,6 +1453,7 @@ xkv_status launch_fused(const xkv_cache* cache, int64_t first, int64_t n_pairs, 
       return gi == 0 ? XKV_ERR_UNSUPPORTED : XKV_ERR_DEVICE;
     }
     strips_done += gr.strips;
+    g_last_fused.launches = gi + 1;
   }
   return XKV_OK;
 }
@@ -1463,14 +1489,35 @@ extern "C" xkv_status xkv_configure(int32_t key, int64_t value) {
     xkv::g_attend_path = static_cast<int>(value);
     return XKV_OK;
   }
+  if (key == XKV_CFG_FUSED_SPIN_LIMIT && value >= -1 && value <= (int64_t{1} << 30)) {
+    xkv::g_fused_spin_limit = value < 0 ? xkv::kDefaultSpinLimit : static_cast<uint32_t>(value);
+    return XKV_OK;
+  }
   return XKV_ERR_INVALID_ARG;
 }
 
-extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_begin,
-                                              int32_t layer_end, const void* q, const void* k_new,
-                                              const void* v_new, const int32_t* pos_new,
-                                              float softmax_scale, float* out, void* workspace,
-                                              size_t workspace_bytes, void* hip_stream) {
+extern "C" xkv_status xkv_fused_status(int32_t* gave_up_out) {
+  using namespace xkv;
+  if (gave_up_out == nullptr) return XKV_ERR_INVALID_ARG;
+  *gave_up_out = 0;
+  if (g_last_fused.control == nullptr || g_last_fused.launches == 0) return XKV_OK;
+  if (hipStreamSynchronize(g_last_fused.stream) != hipSuccess) return XKV_ERR_DEVICE;
+  std::vector<unsigned> words(4 * g_last_fused.launches);
+  if (hipMemcpy(words.data(), g_last_fused.control, words.size() * sizeof(unsigned), hipMemcpyDeviceToHost) !=
+      hipSuccess)
+    return XKV_ERR_DEVICE;
+  for (size_t i = 0; i < g_last_fused.launches; ++i)
+    if (words[4 * i + 1] != 0) *gave_up_out = 1;
+  return XKV_OK;
+}
+
+// The call behind both entry points.  allow_fused: whether the cooperative launch
+// may be chosen (it needs occupancy queries; the entry point that must not
+// allocate keeps to the two kernels).
+static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t layer_end, const void* q,
+                                const void* k_new, const void* v_new, const int32_t* pos_new,
+                                float softmax_scale, float* out, void* workspace, size_t workspace_bytes,
+                                void* hip_stream, bool allow_fused) {
   using namespace xkv;
   xkv_status st = check_cache(cache);
   if (st != XKV_OK) return st;
@@ -1511,7 +1558,7 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
   P.append = append ? 1 : 0;
 
   // One cooperative launch per group of regions when everything fits on the chip at once.
-  if ((g_attend_path == 2 || (g_attend_path == 0 && kAutoPrefersFused)) && kern.fused != nullptr) {
+  if (allow_fused && (g_attend_path == 2 || (g_attend_path == 0 && kAutoPrefersFused)) && kern.fused != nullptr) {
     const xkv_status fs = launch_fused(cache, first, n_pairs, append, pos_new, P, kern.fused, G, D,
                                        total_rows, workspace, workspace_bytes, stream);
     if (fs == XKV_OK) {
@@ -1547,6 +1594,7 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
   P.lds_rows = 0;
   P.fin_strips = fin_strips;
   P.barrier = nullptr;
+  P.spin_limit = 0;
 
   if (n_pairs > kMaxPairs) {
     // More regions than the kernel arguments hold: the tables go to device memory
@@ -1679,4 +1727,13 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
   if (append)
     for (int64_t i = 0; i < n_pairs; ++i) cache->len[first + i] += 1;
   return XKV_OK;
+}
+
+extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_begin,
+                                              int32_t layer_end, const void* q, const void* k_new,
+                                              const void* v_new, const int32_t* pos_new,
+                                              float softmax_scale, float* out, void* workspace,
+                                              size_t workspace_bytes, void* hip_stream) {
+  return decode_attend(cache, layer_begin, layer_end, q, k_new, v_new, pos_new, softmax_scale, out, workspace,
+                       workspace_bytes, hip_stream, true);
 }

@@ -942,6 +942,26 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
   if (workspace == nullptr || L.total > workspace_bytes) return XKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return XKV_ERR_INVALID_ARG;
 
+  // The selection kernel of the call and its dynamic LDS (the staged candidate
+  // vector of the pooled, register-key variants), settled before anything is
+  // enqueued: if the device refuses that much LDS the variant that keeps its keys
+  // in the workspace takes over.
+  const int tc_all = t - ows;
+  void (*select_fn)(const GatherParams) =
+      tc_all <= 8 * kSelThreads ? prefill_select<8>
+      : tc_all <= kMaxKeyRegs * kSelThreads ? prefill_select<kMaxKeyRegs> : prefill_select<0>;
+  size_t select_lds = 0;
+  if (!use_split && pooled && tc_all <= kMaxKeyRegs * kSelThreads) {
+    select_lds = static_cast<size_t>(tc_all + pool_size) * sizeof(float);
+    if (select_lds > 48 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(select_fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            static_cast<int>(select_lds)) != hipSuccess) {
+      (void)hipGetLastError();
+      select_fn = prefill_select<0>;
+      select_lds = 0;
+    }
+  }
+
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
   float* w_dense = w_out != nullptr ? w_out : reinterpret_cast<float*>(ws + L.w);
@@ -984,19 +1004,6 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
       hipLaunchKernelGGL(split_write, grid, dim3(kSelThreads), 0, stream, Gp);
       if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     } else {
-      auto select_fn = tc <= 8 * kSelThreads ? prefill_select<8>
-                       : tc <= kMaxKeyRegs * kSelThreads ? prefill_select<kMaxKeyRegs> : prefill_select<0>;
-      size_t select_lds = 0;
-      if (pooled && tc <= kMaxKeyRegs * kSelThreads) {
-        select_lds = static_cast<size_t>(tc + pool_size) * sizeof(float);
-        if (select_lds > 48 * 1024 &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(select_fn),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                static_cast<int>(select_lds)) != hipSuccess) {
-          (void)hipGetLastError();
-          return XKV_ERR_DEVICE;
-        }
-      }
       hipLaunchKernelGGL(select_fn, dim3(n_streams), dim3(kSelThreads), select_lds, stream, Gp);
       if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     }

@@ -25,6 +25,8 @@ def run_case(xkv, dtype, d, Hq, Hkv, L, B, lens, append, seed, scale=0.0, layer_
             raise
         finally:
             xkv.xkv_configure(xkv.XKV_CFG_ATTEND_PATH, 0)
+        if path == 2:
+            assert not xkv.xkv_fused_status(), "a fused launch gave up its grid-wide wait"
         worst = (max(worst[0], r[0]), max(worst[1], r[1]))
     return worst
 
@@ -111,6 +113,47 @@ def test_dead_slots_may_hold_nan(xkv, dtype, d, G, append):
     lens = [[0, 1, 37], [255, 256, 300], [257, 700, 1029]]
     print(f"case poison dtype={dtype} d={d} G={G} append={append}", flush=True)
     run_case(xkv, dtype, d, 2 * G, 2, 3, 3, lens, append, seed=70 + G, poison=True)
+
+
+def test_fused_give_up_is_reported(xkv):
+    """Failure handling of the fused launch, forced from the host: with a poll limit of
+    zero every workgroup but the last to arrive gives up its grid-wide wait at once.
+    The kernel must still end normally, the flag must be readable, and no row may
+    hold a merged result of incomplete records: a row is NaN or right."""
+    L, B, Hq, Hkv, d = 2, 2, 4, 2, 128
+    lens = np.array([[3000, 700], [1500, 2600]], np.int32)
+    cache = xkv.XkvCache(L, B, Hq, Hkv, d, "bf16", lens + 2)
+    random_fill(cache, lens, 91)
+    g = torch.Generator(device="cpu").manual_seed(92)
+    q = torch.randn((L, B, Hq, d), generator=g).bfloat16().cuda()
+    out = torch.zeros((L, B, Hq, d), dtype=torch.float32, device="cuda")
+    ws = torch.empty(xkv.xkv_workspace_bytes(cache, L), dtype=torch.uint8, device="cuda")
+    before = {(l, b, h): get_unit(cache, l, b, h) for l in range(L) for b in range(B) for h in range(Hkv)}
+    xkv.xkv_configure(xkv.XKV_CFG_ATTEND_PATH, 2)
+    xkv.xkv_configure(xkv.XKV_CFG_FUSED_SPIN_LIMIT, 0)
+    try:
+        print("case fused give-up, poll limit 0", flush=True)
+        xkv.xkv_decode_attend_score(cache, 0, L, q, None, None, None, out, ws)
+        gave_up = xkv.xkv_fused_status()
+    finally:
+        xkv.xkv_configure(xkv.XKV_CFG_FUSED_SPIN_LIMIT, -1)
+        xkv.xkv_configure(xkv.XKV_CFG_ATTEND_PATH, 0)
+    assert gave_up
+    o_host = out.cpu().numpy()
+    assert np.isnan(o_host).any()
+    for (l, b, h), (K, V, score, pos) in before.items():
+        o, _ = orc.OracleUnit(K, V, score, pos).attend(storage(q[l, b, 2 * h:2 * h + 2]))
+        for gq in range(2):
+            row = o_host[l, b, 2 * h + gq]
+            assert np.isnan(row).all() or rel_err(row, o[gq]) <= TOL["bf16"]
+    # and with the default limit the same call completes
+    xkv.xkv_configure(xkv.XKV_CFG_ATTEND_PATH, 2)
+    try:
+        xkv.xkv_decode_attend_score(cache, 0, L, q, None, None, None, out, ws)
+        assert not xkv.xkv_fused_status()
+    finally:
+        xkv.xkv_configure(xkv.XKV_CFG_ATTEND_PATH, 0)
+    assert np.isfinite(out.cpu().numpy()).all()
 
 
 def test_empty_stream_without_append_gives_zero_row(xkv):
