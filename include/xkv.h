@@ -215,6 +215,33 @@ xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_begin, int32_
                                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * xkv_decode_attend_score for callers that cannot allocate device memory or hand
+ * over a workspace: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments without the workspace, same
+ * kernels (the streaming kernel plus the finalize kernel; never the fused
+ * launch) and bit-identical results; the strip records live in a fixed array of
+ * XKV_NOALLOC_SCRATCH_BYTES inside the library's device image, which every GPU
+ * the library runs on holds until the process ends.  The call makes no hipMalloc,
+ * hipFree or other allocating device call.  (The first call on a device looks up
+ * the array's device address; make that call outside stream capture.)
+ *
+ * Limit: the call's strip records must fit the array; roughly 4 G bytes per live
+ * token per KV head plus 1 KiB per strip (32 MiB hold the 32k-context benchmark
+ * step of 6.7 M token-heads at G = 1).  Beyond it the call returns
+ * XKV_ERR_CAPACITY and does nothing.  Nothing in the array needs clearing between
+ * calls (every record is written before it is read), but all calls on one GPU
+ * share it: calls that overlap on one GPU (different streams, or several host
+ * threads) race, and the caller must order them.
+ * Errors: as xkv_decode_attend_score; DEVICE also when the array's address cannot
+ * be resolved.
+ */
+#define XKV_NOALLOC_SCRATCH_BYTES (32u << 20)
+xkv_status xkv_decode_attend_score_noalloc(xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                           const void* q, const void* k_new, const void* v_new,
+                                           const int32_t* pos_new, float softmax_scale, float* out,
+                                           void* hip_stream);
+
+/*
  * Eviction of layers [layer_begin, layer_end)  (Alg. 2 steps 4-7: Pooling,
  * TopK, EvictByIndex on K and V).
  *

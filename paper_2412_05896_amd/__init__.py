@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     xkv_average_allocations,
     xkv_configure,
     xkv_decode_attend_score,
+    xkv_decode_attend_score_noalloc,
     xkv_evict_compact,
     xkv_fused_status,
     xkv_prefill_evict,

@@ -18,8 +18,9 @@ EXPORTS = (
     "xkv_decode_attend_score", "xkv_evict_compact", "xkv_profile_enable", "xkv_profile_read",
     "xkv_configure", "xkv_probe_stream_read", "xkv_prefill_workspace_bytes", "xkv_prefill_evict",
     "xkv_window_importance", "xkv_allocate_device_workspace_bytes", "xkv_allocate_budgets_device",
-    "xkv_average_allocations", "xkv_fused_status",
+    "xkv_average_allocations", "xkv_fused_status", "xkv_decode_attend_score_noalloc",
 )
+XKV_NOALLOC_SCRATCH_BYTES = 32 << 20
 XKV_CFG_ATTEND_PATH = 1
 XKV_CFG_FUSED_SPIN_LIMIT = 2
 
@@ -68,6 +69,10 @@ def load():
     lib.xkv_decode_attend_score.argtypes = [
         C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
         C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.xkv_decode_attend_score_noalloc.restype = C.c_int32
+    lib.xkv_decode_attend_score_noalloc.argtypes = [
+        C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+        C.c_void_p, C.c_float, C.c_void_p, C.c_void_p]
     lib.xkv_evict_compact.restype = C.c_int32
     lib.xkv_evict_compact.argtypes = [
         C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
@@ -255,6 +260,16 @@ def xkv_decode_attend_score(cache: XkvCache, layer_begin, layer_end, q, k_new, v
         _ptr(pn), float(softmax_scale), _ptr(out), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     _check(st, "xkv_decode_attend_score")
+
+
+def xkv_decode_attend_score_noalloc(cache: XkvCache, layer_begin, layer_end, q, k_new, v_new, pos_new,
+                                    out, softmax_scale: float = 0.0, stream=None):
+    """The same call without a workspace: the library's fixed scratch array is used and nothing is allocated."""
+    pn = None if pos_new is None else np.ascontiguousarray(pos_new, dtype=np.int32)
+    st = load().xkv_decode_attend_score_noalloc(
+        C.byref(cache.struct), int(layer_begin), int(layer_end), _ptr(q), _ptr(k_new), _ptr(v_new),
+        _ptr(pn), float(softmax_scale), _ptr(out), _stream_handle(stream))
+    _check(st, "xkv_decode_attend_score_noalloc")
 
 
 def xkv_evict_compact(cache: XkvCache, layer_begin, layer_end, budgets, workspace, pool_size: int = 1,

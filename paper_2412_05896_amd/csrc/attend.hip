@@ -1737,3 +1737,58 @@ extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_be
   return decode_attend(cache, layer_begin, layer_end, q, k_new, v_new, pos_new, softmax_scale, out, workspace,
                        workspace_bytes, hip_stream, true);
 }
+
+// ---- the entry point that allocates nothing ------------------------------------
+// Its strip records live in a fixed array of the library's own device image
+// instead of a caller's workspace.  In host code the array's name is only a
+// stand-in: the device address of each GPU's copy is looked up once per device
+// and that pointer is what the kernels receive.
+namespace xkv {
+namespace {
+constexpr size_t kStaticScratchBytes = XKV_NOALLOC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+}  // namespace
+}  // namespace xkv
+
+static __device__ __align__(256) unsigned char scratch[xkv::kStaticScratchBytes];
+
+namespace xkv {
+namespace {
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of the current device's copy of `scratch`, resolved on the first
+// call on that device; nullptr (and *err set) if the lookup fails.
+void* static_scratch(xkv_status* err) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    *err = XKV_ERR_DEVICE;
+    return nullptr;
+  }
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+      (void)hipGetLastError();
+      *err = XKV_ERR_DEVICE;
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+}  // namespace xkv
+
+extern "C" xkv_status xkv_decode_attend_score_noalloc(xkv_cache* cache, int32_t layer_begin,
+                                                      int32_t layer_end, const void* q,
+                                                      const void* k_new, const void* v_new,
+                                                      const int32_t* pos_new, float softmax_scale,
+                                                      float* out, void* hip_stream) {
+  xkv_status err = XKV_OK;
+  void* ws = xkv::static_scratch(&err);
+  if (ws == nullptr) return err;
+  // A call that needs more than the array holds is refused with XKV_ERR_CAPACITY by
+  // the same check that guards a caller's workspace.
+  return decode_attend(cache, layer_begin, layer_end, q, k_new, v_new, pos_new, softmax_scale, out, ws,
+                       xkv::kStaticScratchBytes, hip_stream, false);
+}
