@@ -272,6 +272,23 @@ xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, int32_t laye
                              void* hip_stream);
 
 /*
+ * Moves the live tokens of layers [layer_begin, layer_end) of `src` into `dst`, a
+ * cache of the same shape (layers, batch, heads, head_dim, dtype) with arenas and
+ * stream capacities of its own: slot j < len of every stream (l, b, h) of src goes
+ * to slot j of the same stream of dst (K row, V row, score, pos), and dst's len
+ * becomes src's.  This is how the ragged layout follows the allocation list of
+ * Alg. 1: after the first eviction has cut every layer to its budget, the
+ * prompt-sized arena is left for one whose streams hold budget + a few slots.
+ * One launch per 1024 regions on hip_stream, geometry in the kernel arguments;
+ * src is not modified.
+ * Errors: INVALID_ARG (shapes differ, or the arenas of src and dst overlap),
+ * CAPACITY (a stream of dst is shorter than its length in src; nothing is
+ * enqueued), DEVICE.
+ */
+xkv_status xkv_repack(const xkv_cache* src, xkv_cache* dst, int32_t layer_begin, int32_t layer_end,
+                      void* hip_stream);
+
+/*
  * Eviction of the prefill phase for layers [layer_begin, layer_end): Alg. 2 as
  * written (attention weights of the observation window, Select, Merge, Pooling,
  * TopK, EvictByIndex; Eq. 3 and the attention processing module of Sec. 4.1),

@@ -28,6 +28,7 @@ from .binding import (  # noqa: F401
     xkv_probe_stream_read,
     xkv_profile_enable,
     xkv_profile_read,
+    xkv_repack,
     xkv_window_importance,
     xkv_workspace_bytes,
 )

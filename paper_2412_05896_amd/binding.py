@@ -18,7 +18,7 @@ EXPORTS = (
     "xkv_decode_attend_score", "xkv_evict_compact", "xkv_profile_enable", "xkv_profile_read",
     "xkv_configure", "xkv_probe_stream_read", "xkv_prefill_workspace_bytes", "xkv_prefill_evict",
     "xkv_window_importance", "xkv_allocate_device_workspace_bytes", "xkv_allocate_budgets_device",
-    "xkv_average_allocations", "xkv_fused_status", "xkv_decode_attend_score_noalloc",
+    "xkv_average_allocations", "xkv_fused_status", "xkv_decode_attend_score_noalloc", "xkv_repack",
 )
 XKV_NOALLOC_SCRATCH_BYTES = 32 << 20
 XKV_CFG_ATTEND_PATH = 1
@@ -73,6 +73,8 @@ def load():
     lib.xkv_decode_attend_score_noalloc.argtypes = [
         C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
         C.c_void_p, C.c_float, C.c_void_p, C.c_void_p]
+    lib.xkv_repack.restype = C.c_int32
+    lib.xkv_repack.argtypes = [C.POINTER(_CacheStruct), C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p]
     lib.xkv_evict_compact.restype = C.c_int32
     lib.xkv_evict_compact.argtypes = [
         C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
@@ -213,27 +215,14 @@ class XkvCache:
         s.cap = self.cap.ctypes.data
         s.len = self.len.ctypes.data
 
-    def resized(self, caps) -> "XkvCache":
-        """A copy of the live tokens in a new cache whose streams have the
-        capacities ``caps`` [L, B] (each >= the current length).  Plain device
-        copies; used to leave the prompt-sized arena once the first eviction has
+    def resized(self, caps, stream=None) -> "XkvCache":
+        """The live tokens in a new cache whose streams have the capacities
+        ``caps`` [L, B] (each >= the current length): xkv_repack, enqueued on the
+        stream.  Used to leave the prompt-sized arena once the first eviction has
         shrunk every layer to its budget."""
-        import torch
         new = XkvCache(self.n_layers, self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim,
                        self.dtype, caps, device=self.k.device)
-        if np.any(new.cap < self.len):
-            raise ValueError("new capacity below the current length")
-        new.len[:] = self.len
-        for l in range(self.n_layers):
-            for b in range(self.batch):
-                n = self.length(l, b)
-                for h in range(self.n_kv_heads):
-                    a, d = self.stream_slot(l, b, h), new.stream_slot(l, b, h)
-                    new.k[d:d + n] = self.k[a:a + n]
-                    new.v[d:d + n] = self.v[a:a + n]
-                    new.score[d:d + n] = self.score[a:a + n]
-                    new.pos[d:d + n] = self.pos[a:a + n]
-        torch.cuda.synchronize()
+        xkv_repack(self, new, 0, self.n_layers, stream=stream)
         return new
 
     def stream_slot(self, l, b, h) -> int:
@@ -270,6 +259,12 @@ def xkv_decode_attend_score_noalloc(cache: XkvCache, layer_begin, layer_end, q, 
         C.byref(cache.struct), int(layer_begin), int(layer_end), _ptr(q), _ptr(k_new), _ptr(v_new),
         _ptr(pn), float(softmax_scale), _ptr(out), _stream_handle(stream))
     _check(st, "xkv_decode_attend_score_noalloc")
+
+
+def xkv_repack(src: XkvCache, dst: XkvCache, layer_begin, layer_end, stream=None):
+    """Live tokens of src's layers into dst (same shape, other capacities); dst.len follows."""
+    _check(load().xkv_repack(C.byref(src.struct), C.byref(dst.struct), int(layer_begin), int(layer_end),
+                             _stream_handle(stream)), "xkv_repack")
 
 
 def xkv_evict_compact(cache: XkvCache, layer_begin, layer_end, budgets, workspace, pool_size: int = 1,

@@ -3,7 +3,7 @@
 // Select + Merge step of Eq. 3 with the decode query as observation row).
 //
 // A stream (layer, sequence, KV head) is cut into strips of `strip_rows` slots.
-// Two kernels per launch, no atomics, results bit-reproducible:
+// Two or three kernels per call, no atomics, results bit-reproducible:
 //
 //  streaming kernel  one workgroup per (stream, strip).  Reads the strip's K and
 //                    V rows once with 16-byte non-temporal loads and writes, per
@@ -11,7 +11,7 @@
 //                    strip's softmax statistics (max m_s, sum l_s) and partial
 //                    output o_s = sum_j 2^(s_j - m_s) V_j.  The workgroup that
 //                    owns the last slot also stores the appended token.
-//                    Two variants:
+//                    Three variants:
 //                      attend_strip   (G <= 2) every wave runs its own online
 //                                     softmax over interleaved groups of rows,
 //                                     with the next group's loads in flight
@@ -22,21 +22,28 @@
 //                                     output on the matrix cores (bf16 MFMA,
 //                                     fp32 result); each wave runs its own
 //                                     online softmax over tiles of 32 rows; a
-//                                     tile's logits leave as one aligned block.
+//                                     tile's logits leave as one aligned block
+//                                     of 16-bit distances below the tile's
+//                                     reference (see the record layout below).
 //                      attend_chunk   (other G >= 4 cases) strips of 256 slots
 //                                     handled by the whole workgroup in one
 //                                     pass; bf16 logits from MFMA.
-//  attend_finalize   one workgroup per (stream, up to 4096 slots).  Merges the
-//                    strip statistics of its stream into (m, l), adds
-//                    p_j = 2^(s_j - m) / l, summed over the G query heads, to
-//                    score[j] for its own slots, and computes its share of the
-//                    channels of out = sum_s 2^(m_s - m) o_s / l.
+//  attend_finalize   (attend_strip, attend_chunk) one workgroup per (stream, up
+//                    to 4096 slots).  Merges the strip statistics of its stream
+//                    into (m, l), adds p_j = 2^(s_j - m) / l, summed over the G
+//                    query heads, to score[j] for its own slots, and computes
+//                    its share of the channels of out = sum_s 2^(m_s - m) o_s / l.
+//  attend_gqa_merge, attend_gqa_scores   (attend_gqa) the same work as two
+//                    kernels: one workgroup per stream folds the strip records
+//                    into (m, 1/l) and the output rows; then a streaming kernel
+//                    over (stream, 1024 slots) adds the probabilities to the
+//                    scores, reading 2 G bytes per slot.
 //
 // The ragged geometry travels in the kernel arguments: up to kMaxPairs (layer,
 // sequence) regions directly, more through tables that small launches write into
 // the workspace from their own arguments.  Nothing is copied from the host, the
 // launches can be captured in a HIP graph, and a call is one streaming launch and
-// one finalize launch whatever its size.
+// one or two finishing launches whatever its size.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -58,7 +65,12 @@ constexpr int kWaves = kThreads / 64;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kMaxHeld = 64;            // strips one workgroup of the fused kernel can hold
-constexpr int kGqaStripRows = 512;      // strip length of attend_gqa (measured best among 256 .. 4096)
+// Longest strip of attend_gqa.  Every strip costs a record (partial outputs and
+// statistics, G (D + 2) floats) that is stored inside the K/V stream and read again by the
+// merge kernel: measured per decode step of the batched 16k and the 128k GQA workloads,
+// 512 / 1024 / 2048 / 4096 slots: 3.83 / 3.78 / 3.75 / 3.75 ms and 4.90 / 4.77 / 4.66 / 4.61 ms.
+constexpr int kGqaStripRows = 4096;
+constexpr int kGqaScoreRows = 1024;      // slots per workgroup of attend_gqa_scores
 
 struct PairDesc {
   int64_t slot0;    // first slot of the region
@@ -80,6 +92,8 @@ struct AttendCommon {
   int32_t* pos;
   float* out;
   float* ws;              // first strip record of this launch
+  float* stats;           // matrix-core path: (m, 1 / l) per (stream of the call, query head), written by
+                          // attend_gqa_merge and read by attend_gqa_scores
   unsigned* barrier;      // fused kernel: {arrival count, timeout flag, queue head, unused}, zero at launch
   float scale_log2e;      // softmax scale times log2(e): logits live in the base-2 domain
   int32_t n_pairs;
@@ -92,6 +106,7 @@ struct AttendCommon {
   int32_t rec_floats;     // floats per strip record in the workspace
   int32_t lds_rows;       // fused kernel: rows of logits a workgroup can hold
   int32_t fin_strips;     // finalize kernel: strips per workgroup
+  int32_t fin_rows;       // attend_gqa_scores: slots per workgroup (a power of two, any relation to strip_rows)
   uint32_t spin_limit;    // fused kernel: polls of the grid-wide wait before a workgroup gives up
 };
 
@@ -122,6 +137,27 @@ __device__ __forceinline__ int fin_first(const AttendTableParams& P, int i) { re
 // (m, l); padded so that every record starts on a 128-byte line.
 __host__ __device__ inline int64_t record_floats(int group, int head_dim, int strip_rows) {
   return (static_cast<int64_t>(group) * (strip_rows + head_dim + 2) + 31) / 32 * 32;
+}
+
+// Strip record of the matrix-core path (attend_gqa).  A probability leaves the
+// streaming kernel as a 16-bit fixed-point distance d = (m_tile - s) * 2^10 of its
+// base-2 logit s below a reference m_tile that is stored once per tile of 32 slots
+// and query head (the wave's running maximum when it reached the tile), so that
+// p = 2^(m_tile - d / 2^10 - m) / l later: half the bytes of an fp32 logit, a
+// relative error of at most ln 2 * 2^-11 = 3.4e-4 on every probability whatever
+// its size, and distances beyond 64 (probabilities below 2^-64 of the tile's
+// reference) saturate.  In floats: d16[strip_rows][G] (two per float), then
+// m_tile[strip_rows / 32][G], then o[G][D] and (m, l)[G]; padded to a 128-byte line.
+constexpr int kGqaTile = 32;
+constexpr float kLogitFixScale = 1024.0f;
+__host__ __device__ inline int64_t gqa_tilem_offset(int group, int strip_rows) {
+  return static_cast<int64_t>(strip_rows) * group / 2;
+}
+__host__ __device__ inline int64_t gqa_out_offset(int group, int strip_rows) {
+  return gqa_tilem_offset(group, strip_rows) + static_cast<int64_t>(strip_rows / kGqaTile) * group;
+}
+__host__ __device__ inline int64_t gqa_record_floats(int group, int head_dim, int strip_rows) {
+  return (gqa_out_offset(group, strip_rows) + static_cast<int64_t>(group) * (head_dim + 2) + 31) / 32 * 32;
 }
 
 struct StripWork { int pair_local, h, s; };
@@ -868,7 +904,9 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
   typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
   __shared__ float o_sh[kWaves][G][D];
   __shared__ float ml_sh[kWaves][G][2];
-  __shared__ __attribute__((aligned(16))) float lg_sh[kWaves][kTile * G];   // a tile's logits, [row][head]
+  __shared__ __attribute__((aligned(16))) unsigned short d_sh[kWaves][kTile * G];   // a tile's logit distances, [row][head]
+  __shared__ float tm_sh[kGqaStripRows / kTile][G];                         // reference of every tile of the strip
+  static_assert(kTile == kGqaTile, "");
   constexpr int kPitch = ROWB + 16;         // staged K rows, padded against bank conflicts
   __shared__ __attribute__((aligned(16))) char kt_sh[kWaves][kTile * kPitch];
 
@@ -975,7 +1013,6 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         sv[grp * 4 + i] = r + i < r_end ? a[i] * P.scale_log2e : -INFINITY;
-        if (x < G) lg_sh[wave][(grp * 16 + 4 * j + i) * G + x] = sv[grp * 4 + i];
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -998,6 +1035,16 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
       ls += pv[i];
     }
     l_run = fmaf(l_run, alpha, ls);
+    if (x < G) {
+      // What the score update needs of this tile: every logit's distance below the
+      // running maximum, 16-bit fixed point (masked rows saturate; they are never read).
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float dist = fminf((m_new - sv[i]) * kLogitFixScale, 65535.0f);
+        d_sh[wave][((i < 4 ? 0 : 12) + 4 * j + i) * G + x] = static_cast<unsigned short>(__float2uint_rn(dist));
+      }
+      if (j == 0) tm_sh[t][x] = m_new;
+    }
     if (__builtin_amdgcn_ballot_w64(moved) != 0) {
       // Accumulator register i of lane (j, .) belongs to head 4 j + i.
 #pragma unroll
@@ -1033,16 +1080,15 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
     __builtin_amdgcn_sched_barrier(0);
     if (more) issue_v(vb, t + kWaves);
     __builtin_amdgcn_sched_barrier(0);
-    // The tile's logits leave as one contiguous, line-aligned block [row][head]
-    // (the wave's own LDS staging turns them; LDS keeps a wave's accesses in
-    // order).  The store comes after the requests for the next tile: the waits
-    // for those then do not include it.
+    // The tile's distances leave as one contiguous, line-aligned block [row][head]
+    // of 64 G bytes (the wave's own LDS staging turns them; LDS keeps a wave's
+    // accesses in order).  The store comes after the requests for the next tile:
+    // the waits for those then do not include it.
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    if (4 * lane < kTile * G) {
-      const floatx4 lg = *reinterpret_cast<const floatx4*>(&lg_sh[wave][4 * lane]);
-      const float lgv[4] = {lg[0], lg[1], lg[2], lg[3]};
-      store_stream16(rec + static_cast<int64_t>(row0 - r_begin) * G + 4 * lane, lgv);
+    if (8 * lane < kTile * G) {
+      const uint4 dv = *reinterpret_cast<const uint4*>(&d_sh[wave][8 * lane]);
+      store_stream16(reinterpret_cast<char*>(rec) + (static_cast<int64_t>(row0 - r_begin) * G + 8 * lane) * 2, dv);
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -1066,8 +1112,10 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
     }
   }
   __syncthreads();
-  float* rec_o = rec + G * strip_rows;
-  float* rec_ml = rec + G * (strip_rows + D);
+  float* rec_tm = rec + gqa_tilem_offset(G, strip_rows);
+  float* rec_o = rec + gqa_out_offset(G, strip_rows);
+  float* rec_ml = rec_o + G * D;
+  for (int idx = tid; idx < tiles * G; idx += kThreads) store_stream(&rec_tm[idx], tm_sh[idx / G][idx % G]);
   for (int idx = tid; idx < G * (D + 1); idx += kThreads) {
     const int g = idx / (D + 1), ch = idx - g * (D + 1);     // ch == D: the sum l
     float m = ml_sh[0][g][0];
@@ -1089,8 +1137,157 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
 }
 
 // ---------------------------------------------------------------------------
-// kByRow: the record's logits are stored [slot][head] (attend_gqa) instead of [head][slot].
-template <int D, int G, bool kByRow = false, typename PT = AttendParams>
+// Second and third kernel of the matrix-core path.
+//
+// attend_gqa_merge: one workgroup per stream.  Folds the strip statistics into the
+// stream's (m, l) per query head, writes (m, 1 / l) for attend_gqa_scores and the
+// stream's output rows out = sum_s 2^(m_s - m) o_s / l.  Thread t owns channels
+// t, t + 256, ... of the G * D outputs and walks the strips in order, several
+// loads in flight.
+template <int G, typename PT = AttendParams>
+__global__ __launch_bounds__(kThreads) void attend_gqa_merge(const PT P) {
+  constexpr int D = 128, GD = G * D, CPT = GD / kThreads;
+  extern __shared__ float w_sh[];           // [G][nstrips] strip weights 2^(m_s - m) / l
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int lo = blockIdx.x / P.n_kv_heads;
+  const int h = blockIdx.x - lo * P.n_kv_heads;
+  const PairDesc pd = P.pairs[lo];
+  const int n = pd.n;
+  const int strip_rows = P.strip_rows;
+  const int64_t stream_idx = static_cast<int64_t>(P.pair_base + lo) * P.n_kv_heads + h;
+  float* out = P.out + stream_idx * GD;
+  if (n == 0) {
+    for (int idx = tid; idx < GD; idx += kThreads) out[idx] = 0.0f;
+    return;
+  }
+  const int nstrips = (n + strip_rows - 1) / strip_rows;
+  const int64_t REC = P.rec_floats;
+  const float* rec0 = P.ws + (static_cast<int64_t>(pd.strip0) + static_cast<int64_t>(h) * nstrips) * REC +
+                      gqa_out_offset(G, strip_rows);
+  for (int g = wave; g < G; g += kWaves) {
+    const float* ml = rec0 + GD + 2 * g;
+    float m = -INFINITY;
+    for (int c = lane; c < nstrips; c += 64) m = fmaxf(m, ml[static_cast<int64_t>(c) * REC]);
+    m = wave_max(m);
+    float l = 0.0f;
+    for (int c = lane; c < nstrips; c += 64) {
+      const float wgt = fast_exp2(ml[static_cast<int64_t>(c) * REC] - m);
+      w_sh[g * nstrips + c] = wgt;
+      l = fmaf(wgt, ml[static_cast<int64_t>(c) * REC + 1], l);
+    }
+    l = wave_sum(l);
+    const float inv = 1.0f / l;
+    for (int c = lane; c < nstrips; c += 64) w_sh[g * nstrips + c] *= inv;
+    if (lane == 0) {
+      P.stats[(stream_idx * G + g) * 2] = m;
+      P.stats[(stream_idx * G + g) * 2 + 1] = inv;
+    }
+  }
+  __syncthreads();
+  float o[CPT];
+#pragma unroll
+  for (int k = 0; k < CPT; ++k) o[k] = 0.0f;
+#pragma unroll 4
+  for (int c = 0; c < nstrips; ++c) {
+    const float* col = rec0 + static_cast<int64_t>(c) * REC + tid;
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int g = (k * kThreads + tid) / D;
+      o[k] = fmaf(w_sh[g * nstrips + c], col[k * kThreads], o[k]);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < CPT; ++k) out[k * kThreads + tid] = o[k];
+}
+
+// attend_gqa_scores: one workgroup per (stream, fin_rows slots).  A thread takes
+// four slots at a time, a workgroup-width apart so that every load instruction
+// covers whole lines: the slot's G distances (2 G bytes), its tile's references and
+// its score, all requested before the first is used; then
+// score_j += sum_g 2^(m_tile - d / 2^10 - m_g) / l_g, the appended token starting
+// from zero.
+template <int G, typename PT = AttendParams>
+__global__ __launch_bounds__(kThreads) void attend_gqa_scores(const PT P) {
+  constexpr int kBatch = 4;
+  typedef unsigned int uintxg __attribute__((ext_vector_type(G / 2)));   // G distances
+  typedef float floatxg __attribute__((ext_vector_type(G)));
+  const int tid = threadIdx.x;
+  const int bid = blockIdx.x;
+  const int strip_rows = P.strip_rows;
+  const int FR = P.fin_rows;
+  const int64_t REC = P.rec_floats;
+
+  int lo = 0, hi = P.n_pairs - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (fin_first(P, mid) <= bid) lo = mid; else hi = mid - 1;
+  }
+  const PairDesc pd = P.pairs[lo];
+  const int n = pd.n;
+  if (n == 0) return;
+  const int nstrips = (n + strip_rows - 1) / strip_rows;
+  const int nfin = (n + FR - 1) / FR;
+  const int local = bid - fin_first(P, lo);
+  const int h = local / nfin;
+  const int f_own = local - h * nfin;
+  const int64_t stream_idx = static_cast<int64_t>(P.pair_base + lo) * P.n_kv_heads + h;
+  const float* rec0 = P.ws + (static_cast<int64_t>(pd.strip0) + static_cast<int64_t>(h) * nstrips) * REC;
+  const floatxg* st = reinterpret_cast<const floatxg*>(P.stats + stream_idx * G * 2);
+  float m_g[G], inv_g[G];
+  {
+    floatxg a = st[0], b = st[1];           // (m, 1/l) pairs of heads 0 .. G/2-1 and G/2 .. G-1
+#pragma unroll
+    for (int g = 0; g < G / 2; ++g) {
+      m_g[g] = a[2 * g]; inv_g[g] = a[2 * g + 1];
+      m_g[G / 2 + g] = b[2 * g]; inv_g[G / 2 + g] = b[2 * g + 1];
+    }
+  }
+  const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
+  float* score = P.score + stream_slot;
+  const int shift = __ffs(strip_rows) - 1;  // strip lengths are powers of two
+  const int r_begin = f_own * FR;
+  const int rows = min(n, r_begin + FR) - r_begin;
+  const int64_t tm_off = gqa_tilem_offset(G, strip_rows);
+  for (int j0 = tid; j0 < rows; j0 += kBatch * kThreads) {
+    uintxg dv[kBatch];
+    floatxg tm[kBatch];
+    float old[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int j = min(j0 + u * kThreads, rows - 1);         // past the end: a live row again, not stored
+      const int row = r_begin + j;
+      const int js = row & (strip_rows - 1);
+      const float* rec = rec0 + static_cast<int64_t>(row >> shift) * REC;
+      dv[u] = __builtin_nontemporal_load(reinterpret_cast<const uintxg*>(rec) + js);
+      tm[u] = *(reinterpret_cast<const floatxg*>(rec + tm_off) + (js >> 5));
+      old[u] = (P.append && row == n - 1) ? 0.0f : score[row];
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int j = j0 + u * kThreads;
+      if (j < rows) {
+        float add = 0.0f;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          const unsigned word = dv[u][g >> 1];
+          const float dist = static_cast<float>((g & 1) ? (word >> 16) : (word & 0xffffu));
+          add = fmaf(fast_exp2(fmaf(dist, -1.0f / kLogitFixScale, tm[u][g] - m_g[g])), inv_g[g], add);
+        }
+        // Scores left dirty in L2 would be written back under the next launch's K/V
+        // stream: they are written through instead.
+        store_stream(&score[r_begin + j], old[u] + add);
+      }
+    }
+  }
+  if (P.append && f_own == 0 && tid == 0) P.pos[stream_slot + n - 1] = P.pos_new[lo];
+}
+
+// ---------------------------------------------------------------------------
+// Second kernel of the attend_strip / attend_chunk paths (records with fp32 logits
+// [head][slot]).
+template <int D, int G, typename PT = AttendParams>
 __global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
   constexpr int GD = G * D;
   extern __shared__ float w_sh[];           // [G][nstrips] strip weights 2^(m_s - m) / l
@@ -1164,26 +1361,13 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
 #pragma unroll 8
   for (int j = tid; j < rows; j += kThreads) {
     const int js = j & (strip_rows - 1);
-    const float* lg = lg0 + static_cast<int64_t>(j >> shift) * REC + (kByRow ? js * G : js);
+    const float* lg = lg0 + static_cast<int64_t>(j >> shift) * REC + js;
     float add = 0.0f;
-    if constexpr (kByRow) {
-      static_assert(!kByRow || G % 4 == 0, "");
 #pragma unroll
-      for (int g4 = 0; g4 < G / 4; ++g4) {
-        const floatx4 v = *reinterpret_cast<const floatx4*>(lg + 4 * g4);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) add = fmaf(fast_exp2(v[i] - m_g[4 * g4 + i]), inv_g[4 * g4 + i], add);
-      }
-    } else {
-#pragma unroll
-      for (int g = 0; g < G; ++g) add = fmaf(fast_exp2(lg[g * strip_rows] - m_g[g]), inv_g[g], add);
-    }
+    for (int g = 0; g < G; ++g) add = fmaf(fast_exp2(lg[g * strip_rows] - m_g[g]), inv_g[g], add);
     const int row = r_begin + j;
     const float old = (P.append && row == n - 1) ? 0.0f : score[row];
-    // With several launches per call (the GQA workloads) scores left dirty in L2 are
-    // written back under the next launch's K/V stream: there they are written through.
-    if constexpr (kByRow) store_stream(&score[row], old + add);
-    else score[row] = old + add;
+    score[row] = old + add;
   }
   if (P.append && f_own == 0 && tid == 0) P.pos[stream_slot + n - 1] = P.pos_new[lo];
 
@@ -1249,6 +1433,8 @@ struct Kernels {
   KernelFn fused = nullptr;
   TableKernelFn stream_tab = nullptr;      // the same kernels with the geometry tables in device memory
   TableKernelFn finalize_tab = nullptr;
+  KernelFn merge = nullptr;                // matrix-core path: attend_gqa_merge, then `finalize` = attend_gqa_scores
+  TableKernelFn merge_tab = nullptr;
   int max_strip_rows = kChunk;  // longest strip the streaming kernel is given (a power of two)
   bool lds_logits = false;      // the streaming kernel collects the strip's logits in dynamic LDS
 };
@@ -1259,37 +1445,41 @@ bool pick_group(int group, Kernels* k) {
     case 1:
       k->stream = attend_strip<T, D, 1, 8>; k->finalize = attend_finalize<D, 1>;
       k->stream_tab = attend_strip<T, D, 1, 8, AttendTableParams>;
-      k->finalize_tab = attend_finalize<D, 1, false, AttendTableParams>;
+      k->finalize_tab = attend_finalize<D, 1, AttendTableParams>;
       k->max_strip_rows = kMaxStripRows; k->lds_logits = true;
       k->fused = attend_fused<T, D, 1, 8>;
       return true;
     case 2:
       k->stream = attend_strip<T, D, 2, 8>; k->finalize = attend_finalize<D, 2>;
       k->stream_tab = attend_strip<T, D, 2, 8, AttendTableParams>;
-      k->finalize_tab = attend_finalize<D, 2, false, AttendTableParams>;
+      k->finalize_tab = attend_finalize<D, 2, AttendTableParams>;
       k->max_strip_rows = kMaxStripRows; k->lds_logits = true;
       k->fused = attend_fused<T, D, 2, 8>;
       return true;
     case 4:
       k->stream = attend_chunk<T, D, 4>; k->finalize = attend_finalize<D, 4>;
       k->stream_tab = attend_chunk<T, D, 4, AttendTableParams>;
-      k->finalize_tab = attend_finalize<D, 4, false, AttendTableParams>;
+      k->finalize_tab = attend_finalize<D, 4, AttendTableParams>;
       k->fused = attend_fused<T, D, 4, 4>;
       if constexpr (std::is_same<T, BF16>::value && D == 128) {
-        k->stream = attend_gqa<4>; k->finalize = attend_finalize<D, 4, true>; k->max_strip_rows = kGqaStripRows;
+        k->stream = attend_gqa<4>; k->merge = attend_gqa_merge<4>; k->finalize = attend_gqa_scores<4>;
         k->stream_tab = attend_gqa<4, AttendTableParams>;
-        k->finalize_tab = attend_finalize<D, 4, true, AttendTableParams>;
+        k->merge_tab = attend_gqa_merge<4, AttendTableParams>;
+        k->finalize_tab = attend_gqa_scores<4, AttendTableParams>;
+        k->max_strip_rows = kGqaStripRows;
       }
       return true;
     case 8:
       k->stream = attend_chunk<T, D, 8>; k->finalize = attend_finalize<D, 8>;
       k->stream_tab = attend_chunk<T, D, 8, AttendTableParams>;
-      k->finalize_tab = attend_finalize<D, 8, false, AttendTableParams>;
+      k->finalize_tab = attend_finalize<D, 8, AttendTableParams>;
       k->fused = attend_fused<T, D, 8, 2>;
       if constexpr (std::is_same<T, BF16>::value && D == 128) {
-        k->stream = attend_gqa<8>; k->finalize = attend_finalize<D, 8, true>; k->max_strip_rows = kGqaStripRows;
+        k->stream = attend_gqa<8>; k->merge = attend_gqa_merge<8>; k->finalize = attend_gqa_scores<8>;
         k->stream_tab = attend_gqa<8, AttendTableParams>;
-        k->finalize_tab = attend_finalize<D, 8, true, AttendTableParams>;
+        k->merge_tab = attend_gqa_merge<8, AttendTableParams>;
+        k->finalize_tab = attend_gqa_scores<8, AttendTableParams>;
+        k->max_strip_rows = kGqaStripRows;
       }
       return true;
     default: return false;
@@ -1408,6 +1598,7 @@ xkv_status launch_fused(const xkv_cache* cache, int64_t first, int64_t n_pairs, 
   P.rec_floats = static_cast<int32_t>(seg);
   P.lds_rows = lds_rows;
   P.fin_strips = 1;
+  P.fin_rows = 0;
   P.spin_limit = g_fused_spin_limit;
   g_last_fused = LastFused{control0, 0, stream};
   int64_t strips_done = 0;
@@ -1477,8 +1668,10 @@ size_t attend_workspace_bytes(const xkv_cache* c, int32_t layers) {
   std::sort(need.begin(), need.end(), std::greater<size_t>());
   size_t tot = 0;
   for (int32_t l = 0; l < layers && l < c->n_layers; ++l) tot += need[l];
-  // geometry tables of a call with more than kMaxPairs regions
-  tot += static_cast<size_t>(std::min(layers, c->n_layers)) * c->batch * (sizeof(PairDesc) + 12) + 1024;
+  // geometry tables of a call with more than kMaxPairs regions, and the (m, 1/l) pairs
+  // that the matrix-core path hands from its merge kernel to its score kernel
+  const size_t regions = static_cast<size_t>(std::min(layers, c->n_layers)) * c->batch;
+  tot += regions * (sizeof(PairDesc) + 12) + regions * hkv * group * 2 * sizeof(float) + 2048;
   return tot;
 }
 
@@ -1570,14 +1763,18 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
   }
 
   const int strip_rows = choose_strip_rows(kern.max_strip_rows, n_pairs * hkv, total_rows);
-  const int64_t rec = record_floats(G, D, strip_rows);
+  const bool gqa = kern.merge != nullptr;
+  const int64_t rec = gqa ? gqa_record_floats(G, D, strip_rows) : record_floats(G, D, strip_rows);
   int64_t total_strips = 0;
   for (int64_t i = 0; i < n_pairs; ++i) {
     const int64_t n = static_cast<int64_t>(cache->len[first + i]) + (append ? 1 : 0);
     total_strips += std::max<int64_t>(ceil_div(n, strip_rows), 1) * hkv;
   }
-  if (static_cast<uint64_t>(total_strips) * rec * sizeof(float) > workspace_bytes)
-    return XKV_ERR_CAPACITY;
+  // Workspace: the strip records, then (matrix-core path) the streams' (m, 1/l) pairs,
+  // then the geometry tables of a call with more regions than the kernel arguments hold.
+  const size_t rec_bytes = (static_cast<size_t>(total_strips) * rec * sizeof(float) + 255) / 256 * 256;
+  const size_t stats_bytes = gqa ? (static_cast<size_t>(n_pairs) * hkv * G * 2 * sizeof(float) + 255) / 256 * 256 : 0;
+  if (rec_bytes + stats_bytes > workspace_bytes) return XKV_ERR_CAPACITY;
   const int64_t max_strips = std::max<int64_t>(ceil_div(max_n, strip_rows), 1);
   const size_t fin_lds = static_cast<size_t>(max_strips) * G * sizeof(float);
   // A finalize workgroup covers up to kMaxStripRows slots, fewer when the streams are
@@ -1593,8 +1790,10 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
   P.rec_floats = static_cast<int32_t>(rec);
   P.lds_rows = 0;
   P.fin_strips = fin_strips;
+  P.fin_rows = kGqaScoreRows;
   P.barrier = nullptr;
   P.spin_limit = 0;
+  P.stats = reinterpret_cast<float*>(static_cast<char*>(workspace) + rec_bytes);
 
   if (n_pairs > kMaxPairs) {
     // More regions than the kernel arguments hold: the tables go to device memory
@@ -1621,7 +1820,7 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
       const int64_t nstrips = std::max<int64_t>(ceil_div(pd.n, strip_rows), 1);
       strips += nstrips * hkv;
       full += static_cast<int64_t>(pd.n / strip_rows) * hkv;
-      fin_blocks += ceil_div(nstrips, fin_strips) * hkv;
+      fin_blocks += (gqa ? std::max<int64_t>(ceil_div(pd.n, kGqaScoreRows), 1) : ceil_div(nstrips, fin_strips)) * hkv;
       tail_len[i] = pd.n % strip_rows;
       if (tail_len[i] > 0) horder[tails++] = static_cast<int32_t>(i);
     }
@@ -1631,10 +1830,9 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
     if (strips > std::numeric_limits<int32_t>::max() || blocks > std::numeric_limits<int32_t>::max() ||
         fin_blocks > std::numeric_limits<int32_t>::max())
       return XKV_ERR_UNSUPPORTED;
-    const size_t rec_bytes = (static_cast<size_t>(total_strips) * rec * sizeof(float) + 255) / 256 * 256;
     const size_t table_bytes = np * (sizeof(PairDesc) + 12);
-    if (rec_bytes + table_bytes > workspace_bytes) return XKV_ERR_CAPACITY;
-    char* tb = static_cast<char*>(workspace) + rec_bytes;
+    if (rec_bytes + stats_bytes + table_bytes > workspace_bytes) return XKV_ERR_CAPACITY;
+    char* tb = static_cast<char*>(workspace) + rec_bytes + stats_bytes;
     PairDesc* d_pairs = reinterpret_cast<PairDesc*>(tb);
     int32_t* d_pos = reinterpret_cast<int32_t*>(tb + np * sizeof(PairDesc));
     int32_t* d_order = d_pos + np;
@@ -1670,8 +1868,13 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
       profile_end(tok, stream);
       if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     }
-    hipLaunchKernelGGL(kern.finalize_tab, dim3(static_cast<unsigned>(fin_blocks)), dim3(kThreads), fin_lds,
-                       stream, T);
+    if (gqa) {
+      hipLaunchKernelGGL(kern.merge_tab, dim3(static_cast<unsigned>(n_pairs * hkv)), dim3(kThreads), fin_lds, stream, T);
+      hipLaunchKernelGGL(kern.finalize_tab, dim3(static_cast<unsigned>(fin_blocks)), dim3(kThreads), 0, stream, T);
+    } else {
+      hipLaunchKernelGGL(kern.finalize_tab, dim3(static_cast<unsigned>(fin_blocks)), dim3(kThreads), fin_lds,
+                         stream, T);
+    }
     if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     for (int64_t i = 0; append && i < n_pairs; ++i) cache->len[first + i] += 1;
     return XKV_OK;
@@ -1717,10 +1920,16 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
     for (int i = 0; i < np; ++i) {
       PairDesc& pd = P.pairs[i];
       pd.full0 = static_cast<int32_t>(fin_blocks);
-      fin_blocks += ceil_div(std::max<int64_t>(ceil_div(pd.n, strip_rows), 1), fin_strips) * hkv;
+      fin_blocks += (gqa ? std::max<int64_t>(ceil_div(pd.n, kGqaScoreRows), 1)
+                         : ceil_div(std::max<int64_t>(ceil_div(pd.n, strip_rows), 1), fin_strips)) * hkv;
     }
-    hipLaunchKernelGGL(kern.finalize, dim3(static_cast<unsigned>(fin_blocks)), dim3(kThreads), fin_lds,
-                       stream, P);
+    if (gqa) {
+      hipLaunchKernelGGL(kern.merge, dim3(static_cast<unsigned>(np * hkv)), dim3(kThreads), fin_lds, stream, P);
+      hipLaunchKernelGGL(kern.finalize, dim3(static_cast<unsigned>(fin_blocks)), dim3(kThreads), 0, stream, P);
+    } else {
+      hipLaunchKernelGGL(kern.finalize, dim3(static_cast<unsigned>(fin_blocks)), dim3(kThreads), fin_lds,
+                         stream, P);
+    }
     if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     strips_done += strips;
   }

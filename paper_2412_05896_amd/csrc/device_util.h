@@ -52,6 +52,11 @@ __device__ __forceinline__ void store_stream16(float* p, const float (&v)[4]) {
   const f4 t = {v[0], v[1], v[2], v[3]};
   asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(t) : "memory");
 }
+__device__ __forceinline__ void store_stream16(void* p, const uint4& v) {
+  typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+  const u4 t = {v.x, v.y, v.z, v.w};
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(t) : "memory");
+}
 // One DPP move: every lane reads the lane that `kCtrl` names within its row of
 // 16 lanes.  Only controls whose source lane always exists are used here.
 template <int kCtrl>
