@@ -57,6 +57,12 @@ __device__ __forceinline__ void store_stream16(void* p, const uint4& v) {
   const u4 t = {v.x, v.y, v.z, v.w};
   asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(t) : "memory");
 }
+// 16-byte store of a row that this kernel and the next ones do not read back.
+__device__ __forceinline__ void store_nt16(void* p, const uint4& v) {
+  typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+  const u4 t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, static_cast<u4*>(p));
+}
 // One DPP move: every lane reads the lane that `kCtrl` names within its row of
 // 16 lanes.  Only controls whose source lane always exists are used here.
 template <int kCtrl>

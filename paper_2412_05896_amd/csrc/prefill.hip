@@ -55,9 +55,12 @@ struct WindowParams {
   float* stats;           // [streams][nstrips][nq_pad][2]  (max, sum) in the base-2 domain
   float* fin;             // [streams][nq_pad][2]           (max, 1 / sum)
   float* w;               // [streams][t]
+  unsigned short* dlog;   // one-pass variant: [streams][t_pad][NQS] 16-bit logit distances
+  float* tref;            // one-pass variant: [streams][t_pad / 32][NQS] reference of every tile of 32 rows
   float scale_log2e;
   int32_t t, ows, group, n_kv_heads;      // t: rows per stream of k_src and w (the longest prompt)
   int32_t strip_rows, nstrips, nq_pad;
+  int32_t t_pad;                          // t rounded up to a multiple of 32 (one-pass variant)
   int32_t n_seq;                          // entries of t_seq: the batch, or 1 when all prompts have t tokens
   int32_t t_seq[kMaxSeqLens];             // prompt length of sequence b (pair % n_seq)
 };
@@ -250,6 +253,199 @@ __global__ __launch_bounds__(kThreads) void window_pass(const WindowParams P) {
       st[1] = l;
     }
   }
+}
+
+// ---------------------------------------------------------------------------
+// One-pass variant for at most 16 query rows per KV head over bf16 keys: K is read
+// once.  window_stats_store computes the logits like window_pass phase 0 and,
+// besides the strip statistics, stores every logit as a 16-bit fixed-point
+// distance d = (ref - s) * 2^10 below a reference that is kept once per tile of 32
+// rows and query row (the wave's running maximum at that tile): 2 NQS bytes per
+// token next to a K row of 256, against reading K a second time.  window_mass_stored
+// then needs only those: w[j] = sum over the seen query rows of
+// 2^(ref - d / 2^10 - m) / l.  A probability carries a relative error of at most
+// ln 2 * 2^-11 = 3.4e-4, far inside what bf16 inputs allow; fp32 caches keep the
+// two K passes.
+constexpr float kLogitFixScale = 1024.0f;
+constexpr int kStoreTile = 32;
+
+template <int D, int NQS>
+__global__ __launch_bounds__(kThreads) void window_stats_store(const WindowParams P) {
+  using T = BF16;
+  constexpr int ROWB = D * T::kBytes;
+  constexpr int NSL = ROWB / 64;
+  constexpr int kMaxTiles = 1024 / kStoreTile;          // strips have at most 1024 rows
+  __shared__ float ml_sh[kWaves][16][2];
+  __shared__ __attribute__((aligned(16))) char tile_sh[kWaves][2][16 * (ROWB + 16)];
+  __shared__ __attribute__((aligned(16))) unsigned short d_sh[kWaves][kStoreTile * NQS];
+  __shared__ float tref_sh[kMaxTiles][NQS];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int x = lane & 15, j = lane >> 4;
+  const int u = blockIdx.x / P.nstrips;
+  const int s = blockIdx.x - u * P.nstrips;
+  const int pair = u / P.n_kv_heads;
+  const int h = u - pair * P.n_kv_heads;
+  const int t = P.t_seq[pair % P.n_seq], ows = P.ows;
+  const int nq = ows * P.group;
+  const int r_begin = s * P.strip_rows;
+  if (r_begin >= t) return;
+  const int r_end = min(t, r_begin + P.strip_rows);
+  const char* kbase = static_cast<const char*>(P.k_src) + static_cast<int64_t>(u) * P.t * ROWB;
+
+  uint4 qreg[NSL];
+  const bool live = x < nq;
+  const int g = live ? x / ows : 0;
+  const int r = live ? x - g * ows : 0;
+  const int last_col = live ? t - ows + r : -1;         // last position the lane's query row sees
+  {
+    const int64_t qrow = (static_cast<int64_t>(pair) * P.n_kv_heads * P.group + h * P.group + g) * ows + r;
+#pragma unroll
+    for (int sl = 0; sl < NSL; ++sl) {
+      uint4 raw = make_uint4(0, 0, 0, 0);
+      if (live) raw = *reinterpret_cast<const uint4*>(static_cast<const char*>(P.q_win) + qrow * ROWB + sl * 64 + j * 16);
+      qreg[sl] = raw;
+    }
+  }
+  float m_run = -INFINITY;                  // query row x, all rows of this wave so far
+  float l_run = 0.0f;                       // query row x, this lane's rows only
+
+  constexpr int LPR = ROWB / 16, RPI = 64 / LPR, kPitch = ROWB + 16;
+  const int rr = lane / LPR, cx = lane % LPR;
+  auto load_group = [&](uint4 (&kreg)[NSL], int row0) {
+#pragma unroll
+    for (int i = 0; i < NSL; ++i) {
+      const int row = row0 + i * RPI + rr;
+      const int rc = row < t ? row : t - 1;             // rows past the end repeat the last one, masked below
+      kreg[i] = load_stream16(kbase + static_cast<int64_t>(rc) * ROWB + cx * 16);
+    }
+  };
+  // Stages 16 rows in the wave's LDS tile (after which their registers are free again).
+  auto stage = [&](const uint4 (&kraw)[NSL], char* tile) {
+#pragma unroll
+    for (int i = 0; i < NSL; ++i)
+      *reinterpret_cast<uint4*>(tile + (i * RPI + rr) * kPitch + cx * 16) = kraw[i];
+  };
+  // Logits of the 16 staged rows from row0 on: sv[i] belongs to (row0 + 4 j + i, query row x).
+  auto logits = [&](int row0, const char* tile, float (&sv)[4]) {
+    floatx4 a = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int sl = 0; sl < NSL; ++sl) {
+      const uint4 kop = *reinterpret_cast<const uint4*>(tile + x * kPitch + sl * 64 + j * 16);
+      a = mma16<T>(kop, qreg[sl], a);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sv[i] = row0 + 4 * j + i <= last_col ? a[i] * P.scale_log2e : -INFINITY;   // causal
+  };
+
+  // A wave takes tiles wave, wave + 4, ... of the strip.  The rows of its next tile
+  // are requested as soon as the current ones sit in LDS, and the tile's distances
+  // are stored after that request, so that no wait for K rows covers the store.
+  const int tiles = (r_end - r_begin + kStoreTile - 1) / kStoreTile;
+  unsigned short* dl = P.dlog + (static_cast<int64_t>(u) * P.t_pad + r_begin) * NQS;
+  uint4 ka[NSL], kb[NSL];
+  if (wave < tiles) {
+    load_group(ka, r_begin + wave * kStoreTile);
+    load_group(kb, r_begin + wave * kStoreTile + 16);
+  }
+  for (int tt = wave; tt < tiles; tt += kWaves) {
+    const int row0 = r_begin + tt * kStoreTile;
+    stage(ka, tile_sh[wave][0]);
+    stage(kb, tile_sh[wave][1]);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if (tt + kWaves < tiles) {
+      load_group(ka, row0 + kWaves * kStoreTile);
+      load_group(kb, row0 + kWaves * kStoreTile + 16);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    float sa[4], sb[4];
+    logits(row0, tile_sh[wave][0], sa);
+    logits(row0 + 16, tile_sh[wave][1], sb);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    float tm = fmaxf(fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3])), fmaxf(fmaxf(sb[0], sb[1]), fmaxf(sb[2], sb[3])));
+    tm = fmaxf(tm, __shfl_xor(tm, 16));
+    tm = fmaxf(tm, __shfl_xor(tm, 32));
+    const float m_new = fmaxf(m_run, tm);
+    const float m_safe = m_new == -INFINITY ? 0.0f : m_new;     // padding query rows see nothing
+    float ls = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ls += fast_exp2(sa[i] - m_safe) + fast_exp2(sb[i] - m_safe);
+    l_run = fmaf(l_run, fast_exp2(m_run - m_safe), ls);
+    m_run = m_new;
+    if (x < NQS) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float da = fminf((m_safe - sa[i]) * kLogitFixScale, 65535.0f);
+        const float db = fminf((m_safe - sb[i]) * kLogitFixScale, 65535.0f);
+        d_sh[wave][(4 * j + i) * NQS + x] = static_cast<unsigned short>(__float2uint_rn(da));
+        d_sh[wave][(16 + 4 * j + i) * NQS + x] = static_cast<unsigned short>(__float2uint_rn(db));
+      }
+      if (j == 0) tref_sh[tt][x] = m_safe;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (8 * lane < kStoreTile * NQS) {                  // the tile's block [row][query row], 64 NQS bytes, one store
+      const uint4 dv = *reinterpret_cast<const uint4*>(&d_sh[wave][8 * lane]);
+      store_stream16(dl + static_cast<int64_t>(tt) * kStoreTile * NQS + 8 * lane, dv);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  // The waves' statistics: every lane of a wave has the wave's maximum; the sums
+  // of the four row quarters are added, then the waves merged.
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  if (j == 0) {
+    ml_sh[wave][x][0] = m_run;
+    ml_sh[wave][x][1] = l_run;
+  }
+  __syncthreads();
+  if (tid < 16) {
+    float m = ml_sh[0][tid][0], l = ml_sh[0][tid][1];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) merge_ml(m, l, ml_sh[w][tid][0], ml_sh[w][tid][1]);
+    float* st = P.stats + ((static_cast<int64_t>(u) * P.nstrips + s) * P.nq_pad + tid) * 2;
+    st[0] = m;
+    st[1] = l;
+  }
+  float* tr = P.tref + (static_cast<int64_t>(u) * (P.t_pad / kStoreTile) + r_begin / kStoreTile) * NQS;
+  for (int idx = tid; idx < tiles * NQS; idx += kThreads) store_stream(&tr[idx], tref_sh[idx / NQS][idx % NQS]);
+}
+
+// w[j] for 256 positions per workgroup from the stored distances.
+template <int NQS>
+__global__ __launch_bounds__(kThreads) void window_mass_stored(const WindowParams P) {
+  typedef unsigned int uintxq __attribute__((ext_vector_type(NQS / 2)));
+  typedef float floatxq __attribute__((ext_vector_type(NQS)));
+  const int u = blockIdx.y;
+  const int pair = u / P.n_kv_heads;
+  const int t = P.t_seq[pair % P.n_seq], ows = P.ows;
+  const int jpos = blockIdx.x * kThreads + threadIdx.x;
+  if (jpos >= t) return;
+  const int nq = ows * P.group;
+  const uintxq dv = __builtin_nontemporal_load(
+      reinterpret_cast<const uintxq*>(P.dlog + (static_cast<int64_t>(u) * P.t_pad + jpos) * NQS));
+  const floatxq ref = *reinterpret_cast<const floatxq*>(
+      P.tref + (static_cast<int64_t>(u) * (P.t_pad / kStoreTile) + jpos / kStoreTile) * NQS);
+  const float* fin = P.fin + static_cast<int64_t>(u) * P.nq_pad * 2;
+  float acc = 0.0f;
+#pragma unroll
+  for (int qi = 0; qi < NQS; ++qi) {
+    const unsigned word = dv[qi >> 1];
+    const float dist = static_cast<float>((qi & 1) ? (word >> 16) : (word & 0xffffu));
+    const int r = qi % ows;                             // query row qi is head qi / ows, window row qi % ows
+    const bool seen = qi < nq && jpos <= t - ows + r;   // causal
+    const float p = fast_exp2(fmaf(dist, -1.0f / kLogitFixScale, ref[qi] - fin[2 * qi])) * fin[2 * qi + 1];
+    acc += seen ? p : 0.0f;
+  }
+  P.w[static_cast<int64_t>(u) * P.t + jpos] = acc;
 }
 
 // One workgroup per stream: thread (slice, qi) folds every S-th strip of query
@@ -683,14 +879,25 @@ __global__ __launch_bounds__(kThreads) void prefill_gather(const GatherParams P)
   const char* vs = static_cast<const char*>(P.v_src) + u * t * P.row_bytes;
   char* kd = static_cast<char*>(P.k) + stream_slot * P.row_bytes;
   char* vd = static_cast<char*>(P.v) + stream_slot * P.row_bytes;
-  for (int s = first + tid / frags; s < last; s += rows_per_pass) {
-    const int src = idx[s];
-    const int64_t so = static_cast<int64_t>(src) * P.row_bytes + fr * 16;
-    const int64_t dof = static_cast<int64_t>(s) * P.row_bytes + fr * 16;
-    const uint4 a = load_stream16(ks + so);
-    const uint4 b = load_stream16(vs + so);
-    *reinterpret_cast<uint4*>(kd + dof) = a;
-    *reinterpret_cast<uint4*>(vd + dof) = b;
+  // Four passes at a time: their eight loads are requested before the first store.
+  for (int s0 = first + tid / frags; s0 < last; s0 += 4 * rows_per_pass) {
+    uint4 a[4], b[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int s = min(s0 + p * rows_per_pass, last - 1);      // past the end: a kept row again, not stored
+      const int64_t so = static_cast<int64_t>(idx[s]) * P.row_bytes + fr * 16;
+      a[p] = load_stream16(ks + so);
+      b[p] = load_stream16(vs + so);
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int s = s0 + p * rows_per_pass;
+      if (s < last) {
+        const int64_t dof = static_cast<int64_t>(s) * P.row_bytes + fr * 16;
+        store_nt16(kd + dof, a[p]);
+        store_nt16(vd + dof, b[p]);
+      }
+    }
   }
 }
 
@@ -741,7 +948,7 @@ bool pick_window(int dtype, int head_dim, int nb, WindowFn* stats, WindowFn* mas
 
 // Workspace layout for `streams` streams of t tokens; every part starts on a
 // 256-byte boundary.  Returns the total; the offsets are in bytes.
-struct PrefillLayout { size_t stats, fin, w, keys, idx, split, total; };
+struct PrefillLayout { size_t stats, fin, w, keys, idx, split, dlog, tref, total; };
 
 size_t round256(size_t b) { return (b + 255) / 256 * 256; }
 
@@ -751,7 +958,14 @@ int prefill_strip_rows(int64_t streams, int t) {
   return rows;
 }
 
-PrefillLayout prefill_layout(int64_t streams, int t, int nq_pad, bool own_w, bool pooled) {
+// Whether the window masses of a call come from one K pass with stored logit
+// distances (bf16 keys, at most 16 query rows per KV head), and how many query
+// rows are stored per token then.
+bool one_pass_window(int dtype, int nb) { return dtype == XKV_BF16 && nb == 1; }
+int stored_query_rows(int nq) { return nq <= 8 ? 8 : 16; }
+int round32(int t) { return (t + 31) / 32 * 32; }
+
+PrefillLayout prefill_layout(int64_t streams, int t, int nq_pad, bool own_w, bool pooled, int nqs) {
   // The strip length depends on the call; 64 rows is the shortest, so this bounds the statistics.
   PrefillLayout L;
   const int64_t max_strips = ceil_div(t, prefill_strip_rows(streams, t));
@@ -762,6 +976,9 @@ PrefillLayout prefill_layout(int64_t streams, int t, int nq_pad, bool own_w, boo
   L.keys = off;  off += pooled ? round256(static_cast<size_t>(streams) * t * sizeof(uint32_t)) : 0;
   L.idx = off;   off += round256(static_cast<size_t>(streams) * t * sizeof(int32_t));
   L.split = off; off += round256(static_cast<size_t>(streams) * kSplitWords * sizeof(unsigned));
+  // one-pass variant (nqs > 0): 16-bit distances per (token, stored query row), a reference per tile
+  L.dlog = off;  off += nqs > 0 ? round256(static_cast<size_t>(streams) * round32(t) * nqs * 2) : 0;
+  L.tref = off;  off += nqs > 0 ? round256(static_cast<size_t>(streams) * (round32(t) / 32) * nqs * sizeof(float)) : 0;
   L.total = off;
   return L;
 }
@@ -793,36 +1010,49 @@ xkv_status check_prefill_shape(const xkv_cache* cache, int32_t t, int32_t ows, i
 }
 
 // The three launches that turn (q_win, k_src) into the per-stream masses w.
-// W arrives with its sequence lengths filled in and leaves complete.
+// W arrives with its sequence lengths filled in and leaves complete.  nqs > 0
+// selects the one-pass variant with that many stored query rows per token.
 xkv_status launch_window_mass(const xkv_cache* cache, int64_t streams, const void* q_win,
                               const void* k_src, int32_t t, int32_t ows, int nb, float softmax_scale,
-                              WindowFn stats_fn, WindowFn mass_fn, float* stats, float* fin, float* w,
-                              hipStream_t stream, WindowParams& W) {
+                              WindowFn stats_fn, WindowFn mass_fn, char* ws, const PrefillLayout& L, float* w,
+                              int nqs, hipStream_t stream, WindowParams& W) {
   const int D = cache->head_dim;
   const int strip_rows = prefill_strip_rows(streams, t);
   const int64_t nstrips = ceil_div(t, strip_rows);
   if (streams * nstrips > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;
   W.q_win = q_win;
   W.k_src = k_src;
-  W.stats = stats;
-  W.fin = fin;
+  W.stats = reinterpret_cast<float*>(ws + L.stats);
+  W.fin = reinterpret_cast<float*>(ws + L.fin);
   W.w = w;
+  W.dlog = reinterpret_cast<unsigned short*>(ws + L.dlog);
+  W.tref = reinterpret_cast<float*>(ws + L.tref);
   const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt(static_cast<float>(D));
   W.scale_log2e = scale * 1.44269504088896340736f;
   W.t = t; W.ows = ows;
+  W.t_pad = round32(t);
   W.group = cache->n_q_heads / cache->n_kv_heads;
   W.n_kv_heads = cache->n_kv_heads;
   W.strip_rows = strip_rows;
   W.nstrips = static_cast<int32_t>(nstrips);
   W.nq_pad = nb * 16;
   const unsigned grid = static_cast<unsigned>(streams * nstrips);
+  if (nqs > 0) {
+    stats_fn = D == 128 ? (nqs == 8 ? window_stats_store<128, 8> : window_stats_store<128, 16>)
+                        : (nqs == 8 ? window_stats_store<64, 8> : window_stats_store<64, 16>);
+    mass_fn = nqs == 8 ? window_mass_stored<8> : window_mass_stored<16>;
+  }
   const int tok = profile_begin(2, stream);
   hipLaunchKernelGGL(stats_fn, dim3(grid), dim3(kThreads), 0, stream, W);
   profile_end(tok, stream);
   if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
   hipLaunchKernelGGL(window_merge, dim3(static_cast<unsigned>(streams)), dim3(kThreads), 0, stream, W);
   if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
-  hipLaunchKernelGGL(mass_fn, dim3(grid), dim3(kThreads), 0, stream, W);
+  if (nqs > 0)
+    hipLaunchKernelGGL(mass_fn, dim3(static_cast<unsigned>(ceil_div(t, kThreads)), static_cast<unsigned>(streams)),
+                       dim3(kThreads), 0, stream, W);
+  else
+    hipLaunchKernelGGL(mass_fn, dim3(grid), dim3(kThreads), 0, stream, W);
   if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
   return XKV_OK;
 }
@@ -857,15 +1087,15 @@ extern "C" xkv_status xkv_window_importance(const xkv_cache* cache, int32_t laye
   const int64_t streams = n_pairs * cache->n_kv_heads;
   WindowFn stats_fn = nullptr, mass_fn = nullptr;
   if (!pick_window(cache->dtype, cache->head_dim, nb, &stats_fn, &mass_fn)) return XKV_ERR_UNSUPPORTED;
-  const PrefillLayout L = prefill_layout(streams, t, nb * 16, true, false);
+  const int nqs = one_pass_window(cache->dtype, nb) ? stored_query_rows(ows * (cache->n_q_heads / cache->n_kv_heads)) : 0;
+  const PrefillLayout L = prefill_layout(streams, t, nb * 16, true, false, nqs);
   if (workspace == nullptr || L.total > workspace_bytes) return XKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return XKV_ERR_INVALID_ARG;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
   float* w_dense = reinterpret_cast<float*>(ws + L.w);
-  st = launch_window_mass(cache, streams, q_win, k_src, t, ows, nb, softmax_scale, stats_fn, mass_fn,
-                          reinterpret_cast<float*>(ws + L.stats), reinterpret_cast<float*>(ws + L.fin),
-                          w_dense, stream, W);
+  st = launch_window_mass(cache, streams, q_win, k_src, t, ows, nb, softmax_scale, stats_fn, mass_fn, ws, L,
+                          w_dense, nqs, stream, W);
   if (st != XKV_OK) return st;
   const int tc = t - ows;
   if (tc > 0) {
@@ -891,7 +1121,9 @@ extern "C" xkv_status xkv_prefill_workspace_bytes(const xkv_cache* cache, int32_
   size_t worst = 0;
   for (int64_t l = 1; l <= layers; ++l) {
     const int64_t streams = l * cache->batch * cache->n_kv_heads;
-    worst = std::max(worst, prefill_layout(streams, t, nb * 16, true, true).total);
+    worst = std::max(worst, prefill_layout(streams, t, nb * 16, true, true,
+                                           one_pass_window(cache->dtype, nb)
+                                               ? stored_query_rows(ows * (cache->n_q_heads / cache->n_kv_heads)) : 0).total);
   }
   *bytes_out = worst;
   return XKV_OK;
@@ -938,7 +1170,8 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
   const bool pooled = pool_size > 1;
   // Few long streams: the selection of a stream is split over several workgroups.
   const bool use_split = streams < 256 && t - ows >= 4 * kSplitChunk && pool_size <= 63;
-  const PrefillLayout L = prefill_layout(streams, t, nb * 16, w_out == nullptr, pooled || use_split);
+  const int nqs = one_pass_window(cache->dtype, nb) ? stored_query_rows(ows * (cache->n_q_heads / hkv)) : 0;
+  const PrefillLayout L = prefill_layout(streams, t, nb * 16, w_out == nullptr, pooled || use_split, nqs);
   if (workspace == nullptr || L.total > workspace_bytes) return XKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return XKV_ERR_INVALID_ARG;
 
@@ -965,9 +1198,8 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
   float* w_dense = w_out != nullptr ? w_out : reinterpret_cast<float*>(ws + L.w);
-  st = launch_window_mass(cache, streams, q_win, k_src, t, ows, nb, softmax_scale, stats_fn, mass_fn,
-                          reinterpret_cast<float*>(ws + L.stats), reinterpret_cast<float*>(ws + L.fin),
-                          w_dense, stream, W);
+  st = launch_window_mass(cache, streams, q_win, k_src, t, ows, nb, softmax_scale, stats_fn, mass_fn, ws, L,
+                          w_dense, nqs, stream, W);
   if (st != XKV_OK) return st;
 
   GatherParams Gp;
