@@ -30,6 +30,12 @@ What follows which passage of the paper (arXiv 2412.05896):
 * ``retention_ratio``   Eq. 4 (R_i), as a fraction.
 * ``allocate_budgets``  Alg. 1 (one token at a time to the layer with the largest
                         next gain) for the two problems of Eq. 17 and Eq. 18.
+* ``cache_importance``   the attention score distribution vector of a layer taken
+                        from the decode-time cache itself, for re-running Alg. 1
+                        during generation (the dynamic tuning of Sec. 2; same
+                        role as the vector of Sec. 4.1): the retained tokens'
+                        accumulated masses added over the KV heads by original
+                        position.
 * ``average_allocations``  Sec. 4.3 (sampling-based overhead reduction): the
                         average of the allocation lists recorded on sampled
                         tasks, as an integer list for the next task.
@@ -54,6 +60,7 @@ __all__ = [
     "window_importance",
     "prefill_select",
     "prefill_evict",
+    "cache_importance",
     "retention_ratio",
     "allocate_budgets",
     "average_allocations",
@@ -300,6 +307,38 @@ def prefill_evict(q_win, K, V, budget: int, ows: int, pool_size: int = 1, scale=
     w = np.asarray(w, dtype=np.float32)
     keep = prefill_select(w, ows, budget, pool_size)
     return K[keep].copy(), V[keep].copy(), w[keep].copy(), keep.astype(np.int32), w
+
+
+# --------------------------------------------------------------------------
+# Score vector of a layer from the decode-time cache (input of Alg. 1)
+# --------------------------------------------------------------------------
+def cache_importance(pos_per_head, score_per_head, n_pos: int) -> np.ndarray:
+    """Position-indexed score vector of one (layer, sequence).
+
+    pos_per_head[h], score_per_head[h]  original positions (distinct within a
+    head) and fp32 accumulated masses of the tokens that KV head h still holds,
+    in any order.  After per-head eviction the heads hold different tokens, so
+    the vector is indexed by original position:
+
+        w[p] = sum over the heads h that still hold position p of its score,
+
+    added in head order in fp32 (so that the result is defined bit for bit: it
+    decides an integer allocation); a position no head holds has w = 0, and
+    tokens whose position lies outside [0, n_pos) are left out.  Before any
+    eviction this is the head-merged vector of the attention processing module
+    (Sec. 4.1) with a sum as the merge.
+    """
+    w = np.zeros(int(n_pos), dtype=np.float32)
+    for pos, score in zip(pos_per_head, score_per_head):
+        pos = np.asarray(pos, dtype=np.int64)
+        score = np.asarray(score, dtype=np.float32)
+        if pos.shape != score.shape:
+            raise ValueError("one score per position")
+        inside = (pos >= 0) & (pos < n_pos)
+        if np.unique(pos[inside]).size != int(inside.sum()):
+            raise ValueError("positions of a head must be distinct")
+        w[pos[inside]] = (w[pos[inside]] + score[inside]).astype(np.float32)
+    return w
 
 
 # --------------------------------------------------------------------------
