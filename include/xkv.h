@@ -356,6 +356,31 @@ xkv_status xkv_window_importance(const xkv_cache* cache, int32_t layer_begin, in
                                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The attention score distribution vector of every (layer, sequence) of layers
+ * [layer_begin, layer_end) taken from the cache itself, so that the allocation
+ * (Alg. 1) can be run again during generation (the allocation is meant to follow
+ * the task, Sec. 2; Alg. 1 takes one vector per layer, Sec. 4.1).  After per-head
+ * eviction the KV heads of a layer hold different tokens, so the vector is
+ * indexed by original position:
+ *
+ *   w_out[l][b][p], p < n_pos  =  sum over the KV heads h, in index order, fp32,
+ *       of score[j] of the live slot j of stream (l, b, h) with pos[j] = p,
+ *       over the heads that hold such a slot; 0 where none does.
+ *
+ * Positions are expected to be distinct within a stream (they are original token
+ * positions); live slots whose pos lies outside [0, n_pos) are left out.  The
+ * result feeds xkv_allocate_budgets_device (per sequence b: w = w_out + b * n_pos,
+ * layer_stride = batch * n_pos, len = n_pos); the new budgets take effect through
+ * xkv_repack (if a layer is to grow) and xkv_evict_compact.
+ *
+ *   w_out   DEVICE [layers][batch][n_pos] fp32, fully written (zero-filled)
+ * No workspace; one launch per 1024 regions on hip_stream; bit-reproducible.
+ * Errors: INVALID_ARG (NULL, n_pos < 1), DEVICE.
+ */
+xkv_status xkv_cache_importance(const xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                int32_t n_pos, float* w_out, void* hip_stream);
+
+/*
  * Process-wide options, for tests and benchmarks.
  *   XKV_CFG_ATTEND_PATH  how xkv_decode_attend_score runs: 0 = the library's
  *       choice (default; at present the two kernels); 1 = a streaming kernel plus

@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     xkv_allocate_budgets_device,
     xkv_allocate_device_workspace_bytes,
     xkv_average_allocations,
+    xkv_cache_importance,
     xkv_configure,
     xkv_decode_attend_score,
     xkv_decode_attend_score_noalloc,

@@ -18,7 +18,7 @@ EXPORTS = (
     "xkv_decode_attend_score", "xkv_evict_compact", "xkv_profile_enable", "xkv_profile_read",
     "xkv_configure", "xkv_probe_stream_read", "xkv_prefill_workspace_bytes", "xkv_prefill_evict",
     "xkv_window_importance", "xkv_allocate_device_workspace_bytes", "xkv_allocate_budgets_device",
-    "xkv_average_allocations", "xkv_fused_status", "xkv_decode_attend_score_noalloc", "xkv_repack",
+    "xkv_average_allocations", "xkv_fused_status", "xkv_decode_attend_score_noalloc", "xkv_repack", "xkv_cache_importance",
 )
 XKV_NOALLOC_SCRATCH_BYTES = 32 << 20
 XKV_CFG_ATTEND_PATH = 1
@@ -73,6 +73,9 @@ def load():
     lib.xkv_decode_attend_score_noalloc.argtypes = [
         C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
         C.c_void_p, C.c_float, C.c_void_p, C.c_void_p]
+    lib.xkv_cache_importance.restype = C.c_int32
+    lib.xkv_cache_importance.argtypes = [C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                         C.c_void_p]
     lib.xkv_repack.restype = C.c_int32
     lib.xkv_repack.argtypes = [C.POINTER(_CacheStruct), C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p]
     lib.xkv_evict_compact.restype = C.c_int32
@@ -310,6 +313,12 @@ def xkv_window_importance(cache: XkvCache, layer_begin, layer_end, q_win, k_src,
         int(ows), int(pool_size), float(softmax_scale), _ptr(w_out), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     _check(st, "xkv_window_importance")
+
+
+def xkv_cache_importance(cache: XkvCache, layer_begin, layer_end, n_pos: int, w_out, stream=None):
+    """w_out: device fp32 [layers, B, n_pos]: the position-indexed score vector of every (layer, sequence)."""
+    _check(load().xkv_cache_importance(C.byref(cache.struct), int(layer_begin), int(layer_end), int(n_pos),
+                                       _ptr(w_out), _stream_handle(stream)), "xkv_cache_importance")
 
 
 def xkv_allocate_device_workspace_bytes(n_layers: int, length: int) -> int:

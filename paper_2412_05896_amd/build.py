@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libxkv.so")
-SOURCES = ["allocate.cc", "allocate_device.hip", "host_common.hip", "attend.hip", "evict.hip", "prefill.hip", "repack.hip", "probe.hip"]
+SOURCES = ["allocate.cc", "allocate_device.hip", "host_common.hip", "attend.hip", "evict.hip", "prefill.hip", "repack.hip", "importance.hip", "probe.hip"]
 
 
 def hipcc() -> str:
