@@ -225,9 +225,10 @@ xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_begin, int32_
  * hipFree or other allocating device call.  (The first call on a device looks up
  * the array's device address; make that call outside stream capture.)
  *
- * Limit: the call's strip records must fit the array; roughly 4 G bytes per live
- * token per KV head plus 1 KiB per strip (32 MiB hold the 32k-context benchmark
- * step of 6.7 M token-heads at G = 1).  Beyond it the call returns
+ * Limit: the call's strip records must fit the array; roughly 2 G bytes (bf16
+ * caches) or 4 G bytes (fp32 caches) per live token per KV head plus 1 KiB per
+ * strip (the 32k-context benchmark step of 6.7 M token-heads at G = 1 takes
+ * 15 MB of the 32 MiB).  Beyond it the call returns
  * XKV_ERR_CAPACITY and does nothing.  Nothing in the array needs clearing between
  * calls (every record is written before it is read), but all calls on one GPU
  * share it: calls that overlap on one GPU (different streams, or several host

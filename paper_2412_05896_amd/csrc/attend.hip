@@ -160,6 +160,14 @@ __host__ __device__ inline int64_t gqa_record_floats(int group, int head_dim, in
   return (gqa_out_offset(group, strip_rows) + static_cast<int64_t>(group) * (head_dim + 2) + 31) / 32 * 32;
 }
 
+// Strip record of attend_strip over bf16 caches: the logits leave as 16-bit
+// fixed-point distances d = (m_s - s) * 2^10 below the strip's own maximum m_s
+// (which the record holds anyway), two per float, [head][slot]; then o[G][D] and
+// (m, l)[G].  Same precision argument as above; fp32 caches keep fp32 logits.
+__host__ __device__ inline int64_t half_record_floats(int group, int head_dim, int strip_rows) {
+  return (static_cast<int64_t>(group) * (strip_rows / 2 + head_dim + 2) + 31) / 32 * 32;
+}
+
 struct StripWork { int pair_local, h, s; };
 
 // Streaming kernels: full strips first (all the same size), then the partial
@@ -299,7 +307,7 @@ template <typename T, int D, int G, int TPI, typename PT, typename Put>
 __device__ __forceinline__ void segment_pass(const PT& P, const StreamCtx<T, D, G>& cx,
                                              int r_begin, int r_end, float* lg, int lg_stride,
                                              float (*mrg_sh)[G][D + 2], float* rec_o, float* rec_ml,
-                                             Put put) {
+                                             Put put, float* m_out_sh = nullptr) {
   using Ctx = StreamCtx<T, D, G>;
   constexpr int EPL = Ctx::EPL, LPR = Ctx::LPR, RPW = Ctx::RPW, ROWB = Ctx::ROWB;
   constexpr int RPI = TPI * RPW;            // rows per wave per round
@@ -436,6 +444,7 @@ __device__ __forceinline__ void segment_pass(const PT& P, const StreamCtx<T, D, 
     } else {
       put(&rec_ml[2 * g], m);
       put(&rec_ml[2 * g + 1], tot);
+      if (m_out_sh != nullptr) m_out_sh[g] = m;
     }
   }
   __syncthreads();
@@ -446,8 +455,10 @@ __device__ __forceinline__ void segment_pass(const PT& P, const StreamCtx<T, D, 
 // strip's logits are collected in LDS and written in one burst.
 template <typename T, int D, int G, int TPI, typename PT = AttendParams>
 __global__ __launch_bounds__(kThreads) void attend_strip(const PT P) {
+  constexpr bool kHalf = std::is_same<T, BF16>::value;   // 16-bit distances instead of fp32 logits
   extern __shared__ float lg_sh[];          // [G][strip_rows] logits of the strip
   __shared__ float mrg_sh[kWaves][G][D + 2];
+  __shared__ float m_sh[G];                 // the strip's maxima
 
   StreamCtx<T, D, G> cx;
   cx.init(P, locate_stream_block(P, blockIdx.x));
@@ -456,13 +467,29 @@ __global__ __launch_bounds__(kThreads) void attend_strip(const PT P) {
   const int r_end = min(cx.n, r_begin + strip_rows);
   const int rows = r_end - r_begin;
   float* rec = cx.rec;
+  const int lg_floats = kHalf ? strip_rows / 2 : strip_rows;   // floats of logit data per head in the record
   segment_pass<T, D, G, TPI>(P, cx, r_begin, r_end, lg_sh, strip_rows, mrg_sh,
-                             rec + G * strip_rows, rec + G * (strip_rows + D),
-                             [](float* p, float v) { store_stream(p, v); });
+                             rec + G * lg_floats, rec + G * (lg_floats + D),
+                             [](float* p, float v) { store_stream(p, v); }, m_sh);
+  if constexpr (kHalf) {
+    // two slots per 32-bit word; an odd last slot is paired with a saturated distance
 #pragma unroll
-  for (int g = 0; g < G; ++g)
-    for (int j = threadIdx.x; j < rows; j += kThreads)
-      store_stream(&rec[g * strip_rows + j], lg_sh[g * strip_rows + j]);
+    for (int g = 0; g < G; ++g) {
+      const float m = m_sh[g];
+      for (int j = threadIdx.x; 2 * j < rows; j += kThreads) {
+        const float s0 = lg_sh[g * strip_rows + 2 * j];
+        const float s1 = 2 * j + 1 < rows ? lg_sh[g * strip_rows + 2 * j + 1] : -INFINITY;
+        const unsigned d0 = __float2uint_rn(fminf((m - s0) * kLogitFixScale, 65535.0f));
+        const unsigned d1 = __float2uint_rn(fminf((m - s1) * kLogitFixScale, 65535.0f));
+        store_stream(&rec[g * lg_floats + j], __uint_as_float(d0 | (d1 << 16)));
+      }
+    }
+  } else {
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+      for (int j = threadIdx.x; j < rows; j += kThreads)
+        store_stream(&rec[g * strip_rows + j], lg_sh[g * strip_rows + j]);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -1287,7 +1314,9 @@ __global__ __launch_bounds__(kThreads) void attend_gqa_scores(const PT P) {
 // ---------------------------------------------------------------------------
 // Second kernel of the attend_strip / attend_chunk paths (records with fp32 logits
 // [head][slot]).
-template <int D, int G, typename PT = AttendParams>
+// kHalf: the records hold 16-bit distances below the strip's maximum (attend_strip
+// over bf16 caches) instead of fp32 logits.
+template <int D, int G, bool kHalf = false, typename PT = AttendParams>
 __global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
   constexpr int GD = G * D;
   extern __shared__ float w_sh[];           // [G][nstrips] strip weights 2^(m_s - m) / l
@@ -1300,7 +1329,8 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
   const int bid = blockIdx.x;
   const int strip_rows = P.strip_rows;
   const int F = P.fin_strips;
-  const int64_t REC = record_floats(G, D, strip_rows);
+  const int64_t REC = kHalf ? half_record_floats(G, D, strip_rows) : record_floats(G, D, strip_rows);
+  const int lg_floats = kHalf ? strip_rows / 2 : strip_rows;   // floats of logit data per head in a record
 
   // Region: last pair whose first finalize workgroup is <= bid.  An empty stream
   // owns one strip and one workgroup.
@@ -1329,7 +1359,7 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
   // workgroup of the stream repeats this small reduction in the same order, so
   // all agree bit for bit.
   for (int g = wave; g < G; g += kWaves) {
-    const float* ml = rec0 + G * (strip_rows + D) + 2 * g;
+    const float* ml = rec0 + G * (lg_floats + D) + 2 * g;
     float m = -INFINITY;
     for (int c = lane; c < nstrips; c += 64) m = fmaxf(m, ml[static_cast<int64_t>(c) * REC]);
     m = wave_max(m);
@@ -1358,16 +1388,41 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
   const int r_begin = s_begin << shift;
   const int rows = min(n, (s_begin + F) << shift) - r_begin;
   const float* lg0 = rec0 + static_cast<int64_t>(s_begin) * REC;
-#pragma unroll 8
-  for (int j = tid; j < rows; j += kThreads) {
-    const int js = j & (strip_rows - 1);
-    const float* lg = lg0 + static_cast<int64_t>(j >> shift) * REC + js;
-    float add = 0.0f;
+  if constexpr (kHalf) {
+    // p = 2^(-d / 2^10) * [2^(m_s - m) / l], the bracket being the strip's weight w_sh.
+    // A thread takes two neighbouring slots: one word of distances per head.
+#pragma unroll 4
+    for (int j = 2 * tid; j < rows; j += 2 * kThreads) {
+      const int js = j & (strip_rows - 1);
+      const int c = s_begin + (j >> shift);
+      const float* lg = lg0 + static_cast<int64_t>(j >> shift) * REC + (js >> 1);
+      float add0 = 0.0f, add1 = 0.0f;
 #pragma unroll
-    for (int g = 0; g < G; ++g) add = fmaf(fast_exp2(lg[g * strip_rows] - m_g[g]), inv_g[g], add);
-    const int row = r_begin + j;
-    const float old = (P.append && row == n - 1) ? 0.0f : score[row];
-    score[row] = old + add;
+      for (int g = 0; g < G; ++g) {
+        const unsigned word = __float_as_uint(lg[g * lg_floats]);
+        const float wgt = w_sh[g * nstrips + c];
+        add0 = fmaf(fast_exp2(static_cast<float>(word & 0xffffu) * (-1.0f / kLogitFixScale)), wgt, add0);
+        add1 = fmaf(fast_exp2(static_cast<float>(word >> 16) * (-1.0f / kLogitFixScale)), wgt, add1);
+      }
+      const int row = r_begin + j;
+      const bool two = j + 1 < rows;
+      const float old0 = (P.append && row == n - 1) ? 0.0f : score[row];
+      const float old1 = (!two || (P.append && row + 1 == n - 1)) ? 0.0f : score[row + 1];
+      score[row] = old0 + add0;
+      if (two) score[row + 1] = old1 + add1;
+    }
+  } else {
+#pragma unroll 8
+    for (int j = tid; j < rows; j += kThreads) {
+      const int js = j & (strip_rows - 1);
+      const float* lg = lg0 + static_cast<int64_t>(j >> shift) * REC + js;
+      float add = 0.0f;
+#pragma unroll
+      for (int g = 0; g < G; ++g) add = fmaf(fast_exp2(lg[g * strip_rows] - m_g[g]), inv_g[g], add);
+      const int row = r_begin + j;
+      const float old = (P.append && row == n - 1) ? 0.0f : score[row];
+      score[row] = old + add;
+    }
   }
   if (P.append && f_own == 0 && tid == 0) P.pos[stream_slot + n - 1] = P.pos_new[lo];
 
@@ -1385,7 +1440,7 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
     if (slice < S) {
       const int idx = ch_first + tb + ch_l;
       const int g = idx / D;
-      const float* col = rec0 + G * strip_rows + idx;
+      const float* col = rec0 + G * lg_floats + idx;
 #pragma unroll 4
       for (int c = slice; c < nstrips; c += S)
         o = fmaf(w_sh[g * nstrips + c], col[static_cast<int64_t>(c) * REC], o);
@@ -1437,29 +1492,32 @@ struct Kernels {
   TableKernelFn merge_tab = nullptr;
   int max_strip_rows = kChunk;  // longest strip the streaming kernel is given (a power of two)
   bool lds_logits = false;      // the streaming kernel collects the strip's logits in dynamic LDS
+  bool half_records = false;    // attend_strip over bf16: records with 16-bit distances
 };
 
 template <typename T, int D>
 bool pick_group(int group, Kernels* k) {
   switch (group) {
     case 1:
-      k->stream = attend_strip<T, D, 1, 8>; k->finalize = attend_finalize<D, 1>;
+      k->half_records = std::is_same<T, BF16>::value;
+      k->stream = attend_strip<T, D, 1, 8>; k->finalize = attend_finalize<D, 1, std::is_same<T, BF16>::value>;
       k->stream_tab = attend_strip<T, D, 1, 8, AttendTableParams>;
-      k->finalize_tab = attend_finalize<D, 1, AttendTableParams>;
+      k->finalize_tab = attend_finalize<D, 1, std::is_same<T, BF16>::value, AttendTableParams>;
       k->max_strip_rows = kMaxStripRows; k->lds_logits = true;
       k->fused = attend_fused<T, D, 1, 8>;
       return true;
     case 2:
-      k->stream = attend_strip<T, D, 2, 8>; k->finalize = attend_finalize<D, 2>;
+      k->half_records = std::is_same<T, BF16>::value;
+      k->stream = attend_strip<T, D, 2, 8>; k->finalize = attend_finalize<D, 2, std::is_same<T, BF16>::value>;
       k->stream_tab = attend_strip<T, D, 2, 8, AttendTableParams>;
-      k->finalize_tab = attend_finalize<D, 2, AttendTableParams>;
+      k->finalize_tab = attend_finalize<D, 2, std::is_same<T, BF16>::value, AttendTableParams>;
       k->max_strip_rows = kMaxStripRows; k->lds_logits = true;
       k->fused = attend_fused<T, D, 2, 8>;
       return true;
     case 4:
       k->stream = attend_chunk<T, D, 4>; k->finalize = attend_finalize<D, 4>;
       k->stream_tab = attend_chunk<T, D, 4, AttendTableParams>;
-      k->finalize_tab = attend_finalize<D, 4, AttendTableParams>;
+      k->finalize_tab = attend_finalize<D, 4, false, AttendTableParams>;
       k->fused = attend_fused<T, D, 4, 4>;
       if constexpr (std::is_same<T, BF16>::value && D == 128) {
         k->stream = attend_gqa<4>; k->merge = attend_gqa_merge<4>; k->finalize = attend_gqa_scores<4>;
@@ -1472,7 +1530,7 @@ bool pick_group(int group, Kernels* k) {
     case 8:
       k->stream = attend_chunk<T, D, 8>; k->finalize = attend_finalize<D, 8>;
       k->stream_tab = attend_chunk<T, D, 8, AttendTableParams>;
-      k->finalize_tab = attend_finalize<D, 8, AttendTableParams>;
+      k->finalize_tab = attend_finalize<D, 8, false, AttendTableParams>;
       k->fused = attend_fused<T, D, 8, 2>;
       if constexpr (std::is_same<T, BF16>::value && D == 128) {
         k->stream = attend_gqa<8>; k->merge = attend_gqa_merge<8>; k->finalize = attend_gqa_scores<8>;
@@ -1764,7 +1822,8 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
 
   const int strip_rows = choose_strip_rows(kern.max_strip_rows, n_pairs * hkv, total_rows);
   const bool gqa = kern.merge != nullptr;
-  const int64_t rec = gqa ? gqa_record_floats(G, D, strip_rows) : record_floats(G, D, strip_rows);
+  const int64_t rec = gqa ? gqa_record_floats(G, D, strip_rows)
+                          : kern.half_records ? half_record_floats(G, D, strip_rows) : record_floats(G, D, strip_rows);
   int64_t total_strips = 0;
   for (int64_t i = 0; i < n_pairs; ++i) {
     const int64_t n = static_cast<int64_t>(cache->len[first + i]) + (append ? 1 : 0);

@@ -73,7 +73,7 @@ def test_noalloc_refuses_what_does_not_fit(xkv):
     """More strip records than the fixed array holds: XKV_ERR_CAPACITY, nothing enqueued, lengths untouched."""
     lib = xkv.load()
     L, B, Hq, Hkv, d = 1, 1, 32, 32, 128
-    n = 400000                                  # 32 heads x 400 k slots x 4 bytes of logits > 32 MiB
+    n = 800000                                  # 32 heads x 800 k slots x 2 bytes of logit records > 32 MiB
     cache = xkv.XkvCache(L, B, Hq, Hkv, d, "bf16", [[n + 8]])
     cache.len[:] = n
     q = torch.zeros((L, B, Hq, d), dtype=torch.bfloat16, device="cuda")
