@@ -1354,6 +1354,36 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
     return;
   }
   const float* rec0 = P.ws + (static_cast<int64_t>(pd.strip0) + static_cast<int64_t>(h) * nstrips) * REC;
+  const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
+  float* score = P.score + stream_slot;
+  const int shift = __ffs(strip_rows) - 1;  // strip lengths are powers of two
+  const int s_begin = f_own * F;
+  const int r_begin = s_begin << shift;
+  const int rows = min(n, (s_begin + F) << shift) - r_begin;
+  const float* lg0 = rec0 + static_cast<int64_t>(s_begin) * REC;
+
+  // With 16-bit records a thread's share of the workgroup's slots (at most
+  // kMaxStripRows / 2 pairs over 256 threads) fits in registers: their distance
+  // words and old scores are requested now, before the statistics below need
+  // their own round trip to memory.
+  constexpr int kPre = kHalf ? kMaxStripRows / (2 * kThreads) : 1;
+  unsigned wpre[kPre][G];
+  float old0[kPre], old1[kPre];
+  if constexpr (kHalf) {
+#pragma unroll
+    for (int it = 0; it < kPre; ++it) {
+      const int j = 2 * (tid + it * kThreads);
+      const int jc = j < rows ? j : 0;            // past the end: slot 0 again, not used
+      const int js = jc & (strip_rows - 1);
+      const float* lg = lg0 + static_cast<int64_t>(jc >> shift) * REC + (js >> 1);
+#pragma unroll
+      for (int g = 0; g < G; ++g) wpre[it][g] = __float_as_uint(lg[g * lg_floats]);
+      const int row = r_begin + jc;
+      const bool two = jc + 1 < rows;
+      old0[it] = (P.append && row == n - 1) ? 0.0f : score[row];            // the appended token starts from zero
+      old1[it] = (!two || (P.append && row + 1 == n - 1)) ? 0.0f : score[row + 1];
+    }
+  }
 
   // Stream statistics from the strip statistics, one wave per query head.  Every
   // workgroup of the stream repeats this small reduction in the same order, so
@@ -1375,43 +1405,33 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
     if (lane == 0) { m_sh[g] = m; inv_sh[g] = inv; }
   }
   __syncthreads();
-  float m_g[G], inv_g[G];
-#pragma unroll
-  for (int g = 0; g < G; ++g) { m_g[g] = m_sh[g]; inv_g[g] = inv_sh[g]; }
 
-  // score_j += sum_g 2^(s_gj - m_g) / l_g for the slots of this workgroup's
-  // strips; the appended token starts from zero.
-  const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
-  float* score = P.score + stream_slot;
-  const int shift = __ffs(strip_rows) - 1;  // strip lengths are powers of two
-  const int s_begin = f_own * F;
-  const int r_begin = s_begin << shift;
-  const int rows = min(n, (s_begin + F) << shift) - r_begin;
-  const float* lg0 = rec0 + static_cast<int64_t>(s_begin) * REC;
+  // score_j += sum_g p_gj for the slots of this workgroup's strips.
   if constexpr (kHalf) {
     // p = 2^(-d / 2^10) * [2^(m_s - m) / l], the bracket being the strip's weight w_sh.
-    // A thread takes two neighbouring slots: one word of distances per head.
-#pragma unroll 4
-    for (int j = 2 * tid; j < rows; j += 2 * kThreads) {
-      const int js = j & (strip_rows - 1);
-      const int c = s_begin + (j >> shift);
-      const float* lg = lg0 + static_cast<int64_t>(j >> shift) * REC + (js >> 1);
-      float add0 = 0.0f, add1 = 0.0f;
+    // A thread takes pairs of neighbouring slots: one word of distances per head.
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const unsigned word = __float_as_uint(lg[g * lg_floats]);
-        const float wgt = w_sh[g * nstrips + c];
-        add0 = fmaf(fast_exp2(static_cast<float>(word & 0xffffu) * (-1.0f / kLogitFixScale)), wgt, add0);
-        add1 = fmaf(fast_exp2(static_cast<float>(word >> 16) * (-1.0f / kLogitFixScale)), wgt, add1);
+    for (int it = 0; it < kPre; ++it) {
+      const int j = 2 * (tid + it * kThreads);
+      if (j < rows) {
+        const int c = s_begin + (j >> shift);
+        float add0 = 0.0f, add1 = 0.0f;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          const unsigned word = wpre[it][g];
+          const float wgt = w_sh[g * nstrips + c];
+          add0 = fmaf(fast_exp2(static_cast<float>(word & 0xffffu) * (-1.0f / kLogitFixScale)), wgt, add0);
+          add1 = fmaf(fast_exp2(static_cast<float>(word >> 16) * (-1.0f / kLogitFixScale)), wgt, add1);
+        }
+        const int row = r_begin + j;
+        score[row] = old0[it] + add0;
+        if (j + 1 < rows) score[row + 1] = old1[it] + add1;
       }
-      const int row = r_begin + j;
-      const bool two = j + 1 < rows;
-      const float old0 = (P.append && row == n - 1) ? 0.0f : score[row];
-      const float old1 = (!two || (P.append && row + 1 == n - 1)) ? 0.0f : score[row + 1];
-      score[row] = old0 + add0;
-      if (two) score[row + 1] = old1 + add1;
     }
   } else {
+    float m_g[G], inv_g[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) { m_g[g] = m_sh[g]; inv_g[g] = inv_sh[g]; }
 #pragma unroll 8
     for (int j = tid; j < rows; j += kThreads) {
       const int js = j & (strip_rows - 1);
