@@ -156,6 +156,17 @@ def test_fused_give_up_is_reported(xkv):
     assert np.isfinite(out.cpu().numpy()).all()
 
 
+@pytest.mark.parametrize("dtype,d,G", [("bf16", 128, 1), ("bf16", 128, 2), ("bf16", 128, 4), ("bf16", 128, 8),
+                                       ("f32", 64, 1)])
+def test_sharply_peaked_softmax(xkv, dtype, d, G):
+    """A logit scale of 4 spreads the base-2 logits over far more than 64 units: for bf16 caches the
+    16-bit logit distances of most slots saturate (their probabilities are below 2^-64 of the reference
+    and must come out as nothing), while the few slots near the maximum carry everything."""
+    lens = [[3000, 517], [4100, 33]]
+    print(f"case peaked dtype={dtype} d={d} G={G}", flush=True)
+    run_case(xkv, dtype, d, 2 * G, 2, 2, 2, lens, True, seed=80 + G, scale=4.0, paths=(0, 1))
+
+
 def test_empty_stream_without_append_gives_zero_row(xkv):
     cache = xkv.XkvCache(1, 1, 2, 2, 64, "f32", [[4]])
     q = torch.randn((1, 1, 2, 64), device="cuda")
