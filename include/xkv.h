@@ -325,6 +325,16 @@ xkv_status xkv_repack(const xkv_cache* src, xkv_cache* dst, int32_t layer_begin,
  *
  * Supported: ows * G <= 64, t - ows <= 262144, batch <= 256 when t_per_seq is given.  Errors: INVALID_ARG, UNSUPPORTED,
  * CAPACITY (k' > cap or the workspace is too small), DEVICE.  Bit-reproducible.
+ *
+ * A call with few, long streams (more than 8192 candidates each, and no more
+ * (8192-candidate chunk, stream) pairs than workgroups the chip holds at once)
+ * runs TopK as one launch whose workgroups wait for each other between the
+ * digits of the radix select.  The waits are bounded (XKV_CFG_FUSED_SPIN_LIMIT,
+ * at most 2^16 polls); they complete whenever the launch is resident, which the
+ * occupancy check ensures on an otherwise idle GPU.  Should one run out, the
+ * regions of the streams concerned keep what they held before the call (their
+ * len is still set to k'), the other streams are complete, and
+ * xkv_fused_status reports it.
  */
 xkv_status xkv_prefill_workspace_bytes(const xkv_cache* cache, int32_t max_layers_per_call,
                                        int32_t t, int32_t ows, size_t* bytes_out);
@@ -391,6 +401,8 @@ xkv_status xkv_cache_importance(const xkv_cache* cache, int32_t layer_begin, int
  *       workgroup gives up (0 .. 2^30; -1 = the default, 2^24, several hundred
  *       milliseconds).  For tests of the give-up path: with 0 every workgroup but
  *       the last to arrive gives up at once, and the kernel still ends normally.
+ *       The waits of xkv_prefill_evict's one-launch TopK take the same limit,
+ *       capped at 2^16 (their polls are slower); with 0 they give up unpolled.
  * Errors: INVALID_ARG for an unknown key or value.
  */
 enum { XKV_CFG_ATTEND_PATH = 1, XKV_CFG_FUSED_SPIN_LIMIT = 2 };
@@ -407,10 +419,11 @@ xkv_status xkv_configure(int32_t key, int64_t value);
  * appended K/V rows are in place and len has grown).  The remaining rows are
  * complete.
  *
- * xkv_fused_status waits for the stream of the most recent fused
- * xkv_decode_attend_score call of this process and stores 1 in gave_up_out if any
- * of its launches raised the flag, else 0 (also 0 if there was no such call).  Call
- * it before that call's workspace is used again or freed.
+ * xkv_fused_status waits for the stream of the most recent call of this process
+ * that launched a kernel with such waits (a fused xkv_decode_attend_score, or an
+ * xkv_prefill_evict whose TopK ran as one launch) and stores 1 in gave_up_out if
+ * any of its launches raised the flag, else 0 (also 0 if there was no such call).
+ * Call it before that call's workspace is used again or freed.
  * Errors: INVALID_ARG, DEVICE.
  */
 xkv_status xkv_fused_status(int32_t* gave_up_out);

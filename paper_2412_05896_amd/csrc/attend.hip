@@ -1732,6 +1732,12 @@ xkv_status launch_fused(const xkv_cache* cache, int64_t first, int64_t n_pairs, 
 
 }  // namespace
 
+void note_waiting_launch(const unsigned* control, void* stream) {
+  g_last_fused = LastFused{control, control != nullptr ? size_t{1} : size_t{0}, static_cast<hipStream_t>(stream)};
+}
+
+uint32_t fused_spin_limit() { return g_fused_spin_limit; }
+
 size_t attend_workspace_bytes(const xkv_cache* c, int32_t layers) {
   // Upper bound over every strip length a call may choose: logits for cap slots
   // plus one padded strip, and one (o, m, l) block per kChunk slots.

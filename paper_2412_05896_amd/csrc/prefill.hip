@@ -44,7 +44,11 @@ constexpr int kMaxWalkRows = 256;          // prefill_select without register ke
 constexpr int kSplitKeys = 8;
 constexpr int kSplitChunk = kSplitKeys * kSelThreads;
 constexpr int kSplitMaxChunks = kMaxWalkRows * kSelThreads / kSplitChunk;
-constexpr int kSplitWords = 4 * 256 + 2 + 2 * kSplitMaxChunks;
+constexpr int kSplitCounts = 4 * 256 + 2;                     // first (gt, eq) pair
+constexpr int kSplitFlag = kSplitCounts + 2 * kSplitMaxChunks;  // one-launch variant: some wait of the stream gave up
+constexpr int kSplitWords = kSplitFlag + 2;
+constexpr unsigned kSplitSpinLimit = 1u << 16;              // most polls (some microseconds each) of a wait of the one-launch selection
+constexpr unsigned kSplitValid = 0x80000000u;               // a chunk's packed (gt, eq) word has been published
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -57,6 +61,8 @@ struct WindowParams {
   float* w;               // [streams][t]
   unsigned short* dlog;   // one-pass variant: [streams][t_pad][NQS] 16-bit logit distances
   float* tref;            // one-pass variant: [streams][t_pad / 32][NQS] reference of every tile of 32 rows
+  unsigned* split;        // [streams][kSplitWords] state of the selection that follows, zeroed by window_merge (or null)
+  unsigned* call_flag;    // with split: the call's 4 control words, zeroed with it
   float scale_log2e;
   int32_t t, ows, group, n_kv_heads;      // t: rows per stream of k_src and w (the longest prompt)
   int32_t strip_rows, nstrips, nq_pad;
@@ -419,6 +425,33 @@ __global__ __launch_bounds__(kThreads) void window_stats_store(const WindowParam
   for (int idx = tid; idx < tiles * NQS; idx += kThreads) store_stream(&tr[idx], tref_sh[idx / NQS][idx % NQS]);
 }
 
+// Final (max, 1 / sum) of query row tid of stream u, for tid < nq_pad, from the
+// strips' stats: thread (slice, qi) folds every S-th strip of query row qi, then
+// the slices are folded in order.  Every thread of the workgroup calls it; has a
+// barrier.
+__device__ __forceinline__ void stream_fin(const WindowParams& P, int u, float (*part_sh)[2], float& m_out,
+                                           float& inv_l_out) {
+  const int tid = threadIdx.x;
+  const int nq = P.nq_pad;                    // 16, 32, 48 or 64
+  const int S = kThreads / nq;
+  const int qi = tid % nq, slice = tid / nq;
+  const int t = P.t_seq[(u / P.n_kv_heads) % P.n_seq];
+  const int nstrips = (t + P.strip_rows - 1) / P.strip_rows;   // the strips this sequence's prompt has
+  float m = -INFINITY, l = 0.0f;
+  if (slice < S)
+    for (int s = slice; s < nstrips; s += S) {
+      const float* st = P.stats + ((static_cast<int64_t>(u) * P.nstrips + s) * nq + qi) * 2;
+      merge_ml(m, l, st[0], st[1]);
+    }
+  part_sh[tid][0] = m;
+  part_sh[tid][1] = l;
+  __syncthreads();
+  if (tid < nq)
+    for (int sl = 1; sl < S; ++sl) merge_ml(m, l, part_sh[sl * nq + tid][0], part_sh[sl * nq + tid][1]);
+  m_out = m == -INFINITY ? 0.0f : m;          // padding rows: any finite value, they are never seen
+  inv_l_out = l > 0.0f ? 1.0f / l : 0.0f;
+}
+
 // w[j] for 256 positions per workgroup from the stored distances.
 template <int NQS>
 __global__ __launch_bounds__(kThreads) void window_mass_stored(const WindowParams P) {
@@ -448,31 +481,22 @@ __global__ __launch_bounds__(kThreads) void window_mass_stored(const WindowParam
   P.w[static_cast<int64_t>(u) * P.t + jpos] = acc;
 }
 
-// One workgroup per stream: thread (slice, qi) folds every S-th strip of query
-// row qi, then the slices are folded in order.
+// One workgroup per stream: the final stats of every query row; it also clears the
+// state words of the selection that follows (if one does).
 __global__ __launch_bounds__(kThreads) void window_merge(const WindowParams P) {
   __shared__ float part_sh[kThreads][2];
   const int u = blockIdx.x;
-  const int tid = threadIdx.x;
-  const int nq = P.nq_pad;                    // 16, 32, 48 or 64
-  const int S = kThreads / nq;
-  const int qi = tid % nq, slice = tid / nq;
-  const int t = P.t_seq[(u / P.n_kv_heads) % P.n_seq];
-  const int nstrips = (t + P.strip_rows - 1) / P.strip_rows;   // the strips this sequence's prompt has
-  float m = -INFINITY, l = 0.0f;
-  if (slice < S)
-    for (int s = slice; s < nstrips; s += S) {
-      const float* st = P.stats + ((static_cast<int64_t>(u) * P.nstrips + s) * nq + qi) * 2;
-      merge_ml(m, l, st[0], st[1]);
-    }
-  part_sh[tid][0] = m;
-  part_sh[tid][1] = l;
-  __syncthreads();
-  if (tid < nq) {
-    for (int sl = 1; sl < S; ++sl) merge_ml(m, l, part_sh[sl * nq + tid][0], part_sh[sl * nq + tid][1]);
-    float* f = P.fin + (static_cast<int64_t>(u) * nq + tid) * 2;
-    f[0] = m == -INFINITY ? 0.0f : m;         // padding rows: any finite value, they are never seen
-    f[1] = l > 0.0f ? 1.0f / l : 0.0f;
+  if (P.split != nullptr) {
+    unsigned* st = P.split + static_cast<int64_t>(u) * kSplitWords;
+    for (int i = threadIdx.x; i < kSplitWords; i += kThreads) st[i] = 0u;
+    if (u == 0 && threadIdx.x < 4) P.call_flag[threadIdx.x] = 0u;
+  }
+  float fm, fil;
+  stream_fin(P, u, part_sh, fm, fil);
+  if (threadIdx.x < P.nq_pad) {
+    float* f = P.fin + (static_cast<int64_t>(u) * P.nq_pad + threadIdx.x) * 2;
+    f[0] = fm;
+    f[1] = fil;
   }
 }
 
@@ -495,6 +519,9 @@ struct GatherParams {
   uint32_t* keys;        // [streams][t] pooled keys (only used when pool > 1)
   int32_t* idx;          // [streams][t] kept positions, ascending
   unsigned* split;       // [streams][kSplitWords]: state of the selection split over several workgroups
+  unsigned* call_flag;   // 4 control words of the call (word 1: some wait of split_fused gave up), zeroed by window_merge
+  int32_t check_flag;    // the gather skips streams whose selection gave up
+  uint32_t spin_limit;   // polls of a wait of split_fused before it gives up
   int32_t t, ows, pool, n_kv_heads, row_bytes;   // t: rows per stream of the dense arrays
   int32_t stream0;       // index of this launch's first stream within the call
   GatherPair pairs[kMaxPairs];
@@ -711,11 +738,6 @@ __device__ __forceinline__ void split_load_keys(const GatherParams& P, const Spl
   }
 }
 
-__global__ void split_zero(const GatherParams P) {
-  unsigned* st = P.split + (static_cast<int64_t>(P.stream0) + blockIdx.x) * kSplitWords;
-  for (int i = threadIdx.x; i < kSplitWords; i += blockDim.x) st[i] = 0u;
-}
-
 __global__ __launch_bounds__(kSelThreads) void split_keys(const GatherParams P) {
   __shared__ unsigned hist_sh[256];
   __shared__ float wpad_sh[kSplitChunk + 64];
@@ -849,6 +871,219 @@ __global__ __launch_bounds__(kSelThreads) void split_write(const GatherParams P)
     }
 }
 
+// ---- the same selection in one launch -------------------------------------------
+// When all workgroups (chunk, stream) of the selection are resident at once (the
+// host checks the grid against the occupancy), the launches above become steps
+// of one kernel.  The keys stay in registers throughout.  What the workgroups of
+// a stream exchange lives in the stream's state words, is added to with
+// agent-scope atomics and read with agent-scope loads (nothing that crosses a
+// step goes through the per-XCD caches), and tells by itself when it is
+// complete: the histogram of a digit is complete when its bins add up to the
+// number of keys that match the digits picked so far (all candidates for the
+// first digit, the count of the picked bin afterwards), and a chunk's packed
+// (gt, eq) word carries a valid bit.  So a step is: add, then poll until
+// complete.  The polls are bounded: a workgroup that runs out of them raises the
+// stream's flag (and the call's, for xkv_fused_status); every workgroup of the
+// stream that sees the flag stops, and the gather copies nothing of a flagged
+// stream.  Integer atomics only: the result does not depend on the order.
+struct SplitShared {
+  int scan[4];
+  unsigned sel_bin, sel_need, sel_cnt;
+  unsigned flag;
+  unsigned chunk_word[kSplitMaxChunks];
+};
+
+__device__ __forceinline__ void split_raise_flag(const SplitCtx& x, unsigned* call_flag) {
+  __hip_atomic_store(x.st + kSplitFlag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(call_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Polls the stream's histogram of digit `pass` until its bins add up to
+// `expected`, then picks the bin in which the running count, from the top bin
+// down, reaches `need` (as radix_pick_bin does).  Returns true, to every thread,
+// if the stream was flagged or the polls ran out.
+__device__ __forceinline__ bool split_poll_pick(const SplitCtx& x, int pass, unsigned expected, unsigned need,
+                                                unsigned spin_limit, unsigned* call_flag, SplitShared& sh, unsigned& bin,
+                                                unsigned& need_out, unsigned& cnt_out) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const unsigned* hist = x.st + pass * 256;
+  for (unsigned spins = 0;; ++spins) {
+    if (spins >= spin_limit) {
+      if (tid == 0) split_raise_flag(x, call_flag);
+      return true;
+    }
+    unsigned cnt = 0, incl = 0;
+    if (tid < 256) {
+      cnt = __hip_atomic_load(hist + 255 - tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      incl = cnt;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const unsigned y = __shfl_up(incl, off);
+        if (lane >= off) incl += y;
+      }
+      if (lane == 63) sh.scan[wave] = static_cast<int>(incl);
+    } else if (tid == 256) {
+      sh.flag = __hip_atomic_load(x.st + kSplitFlag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    const unsigned total = static_cast<unsigned>(sh.scan[0] + sh.scan[1] + sh.scan[2] + sh.scan[3]);
+    const bool flagged = sh.flag != 0u;
+    if (total == expected && !flagged) {
+      if (tid < 256) {
+        for (int w = 0; w < wave; ++w) incl += static_cast<unsigned>(sh.scan[w]);
+        const unsigned before = incl - cnt;
+        if (before < need && need <= incl) {
+          sh.sel_bin = 255u - static_cast<unsigned>(tid);
+          sh.sel_need = need - before;
+          sh.sel_cnt = cnt;
+        }
+      }
+      __syncthreads();
+      bin = sh.sel_bin;
+      need_out = sh.sel_need;
+      cnt_out = sh.sel_cnt;
+      __syncthreads();
+      return false;
+    }
+    if (flagged) return true;
+    __syncthreads();                              // everyone has read sh before the next poll rewrites it
+    __builtin_amdgcn_s_sleep(2);
+  }
+}
+
+__global__ __launch_bounds__(kSelThreads) void split_fused(const GatherParams P) {
+  unsigned* call_flag = P.call_flag + 1;
+  __shared__ unsigned hist_sh[256];
+  __shared__ SplitShared sh;
+  __shared__ float wpad_sh[kSplitChunk + 64];
+  __shared__ unsigned cnt_sh[2];
+  __shared__ int eq_sh[kSplitKeys * kSelWaves], keep_sh[kSplitKeys * kSelWaves];
+  __shared__ int tot_sh[kSelWaves + 1];
+
+  const SplitCtx x = split_ctx(P);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  int32_t* idx = P.idx + x.u * x.t;
+  if (x.c == 0)
+    for (int r = tid; r < P.ows; r += kSelThreads) idx[max(x.kc, 0) + r] = x.tc + r;
+  if (x.n <= 0 || x.kc <= 0) return;              // no candidates in this chunk, or none to keep
+  if (x.kc >= x.tc) {                             // every candidate stays
+    for (int jl = tid; jl < x.n; jl += kSelThreads) idx[x.first + jl] = x.first + jl;
+    return;
+  }
+
+  // ---- keys of this chunk, in registers ---------------------------------------------
+  const float* w = P.w + x.u * x.t;
+  const int half = P.pool >> 1;                   // pool <= 63 on this path (checked on the host)
+  for (int i = tid; i < x.n + 2 * half; i += kSelThreads) {
+    const int cnd = x.first - half + i;
+    wpad_sh[i] = (cnd >= 0 && cnd < x.tc) ? w[cnd] : 0.0f;
+  }
+  __syncthreads();
+  unsigned kreg[kSplitKeys];
+#pragma unroll
+  for (int i = 0; i < kSplitKeys; ++i) {
+    const int jl = i * kSelThreads + tid;
+    unsigned key = 0u;
+    if (jl < x.n) {
+      float acc = wpad_sh[jl];                    // window sum, fp32, left to right
+      for (int q = 1; q < P.pool; ++q) acc = acc + wpad_sh[jl + q];
+      key = __float_as_uint(acc);
+    }
+    kreg[i] = key;
+  }
+
+  // ---- four digits: add to the stream's histogram, poll until complete, pick the bin --------
+  unsigned prefix = 0, mask = 0, need = static_cast<unsigned>(x.kc);
+  unsigned expected = static_cast<unsigned>(x.tc);
+  for (int pass = 0; pass < 4; ++pass) {
+    split_add_hist(x, kreg, pass, prefix, mask, hist_sh);
+    unsigned bin;
+    if (split_poll_pick(x, pass, expected, need, P.spin_limit, call_flag, sh, bin, need, expected)) return;
+    prefix |= bin << (24 - 8 * pass);
+    mask |= 255u << (24 - 8 * pass);
+  }
+  const unsigned thr = prefix;
+
+  // ---- keys above and equal to the threshold per chunk ---------------------------------
+  if (tid < 2) cnt_sh[tid] = 0u;
+  __syncthreads();
+  unsigned gt = 0, eq = 0;
+#pragma unroll
+  for (int i = 0; i < kSplitKeys; ++i)
+    if (i * kSelThreads + tid < x.n) {
+      gt += kreg[i] > thr;
+      eq += kreg[i] == thr;
+    }
+  if (gt) atomicAdd(&cnt_sh[0], gt);
+  if (eq) atomicAdd(&cnt_sh[1], eq);
+  __syncthreads();
+  if (tid == 0)                                   // both counts are at most kSplitChunk = 2^13
+    __hip_atomic_store(x.st + kSplitCounts + x.c, kSplitValid | (cnt_sh[0] << 14) | cnt_sh[1], __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+  // the words of the chunks before this one
+  for (unsigned spins = 0;; ++spins) {
+    if (spins >= P.spin_limit) {
+      if (tid == 0) split_raise_flag(x, call_flag);
+      return;
+    }
+    unsigned word = kSplitValid;
+    if (tid < x.c)
+      word = __hip_atomic_load(x.st + kSplitCounts + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else if (tid == 256)
+      sh.flag = __hip_atomic_load(x.st + kSplitFlag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid < x.c) sh.chunk_word[tid] = word;
+    const int complete = __syncthreads_and((word & kSplitValid) != 0u);
+    const bool flagged = sh.flag != 0u;
+    if (complete && !flagged) break;
+    if (flagged) return;
+    __syncthreads();
+    __builtin_amdgcn_s_sleep(2);
+  }
+
+  // ---- ranks at the start of this chunk, then the ordered walk inside it -----------------
+  int eq_before = 0, keep_before = 0;
+  for (int cc = 0; cc < x.c; ++cc) {
+    const unsigned word = sh.chunk_word[cc];
+    const int g = static_cast<int>((word >> 14) & 0x3fffu);
+    const int e = static_cast<int>(word & 0x3fffu);
+    keep_before += g + min(max(static_cast<int>(need) - eq_before, 0), e);
+    eq_before += e;
+  }
+  const int rows = (x.n + kSelThreads - 1) / kSelThreads;
+#pragma unroll
+  for (int i = 0; i < kSplitKeys; ++i)
+    if (i < rows) {
+      const bool is_eq = i * kSelThreads + tid < x.n && kreg[i] == thr;
+      const unsigned long long v_eq = __ballot(is_eq);
+      if (lane == 0) eq_sh[i * kSelWaves + wave] = __popcll(v_eq);
+    }
+  block_exclusive_scan<kSelThreads>(eq_sh, rows * kSelWaves, tot_sh);
+  auto kept = [&](int i) -> bool {
+    const bool live = i * kSelThreads + tid < x.n;
+    const bool is_eq = live && kreg[i] == thr;
+    const unsigned long long v_eq = __ballot(is_eq);
+    const int eq_rank = eq_before + eq_sh[i * kSelWaves + wave] + rank_in_wave(v_eq);
+    return live && (kreg[i] > thr || (is_eq && eq_rank < static_cast<int>(need)));
+  };
+#pragma unroll
+  for (int i = 0; i < kSplitKeys; ++i)
+    if (i < rows) {
+      const unsigned long long v_k = __ballot(kept(i));
+      if (lane == 0) keep_sh[i * kSelWaves + wave] = __popcll(v_k);
+    }
+  block_exclusive_scan<kSelThreads>(keep_sh, rows * kSelWaves, tot_sh);
+#pragma unroll
+  for (int i = 0; i < kSplitKeys; ++i)
+    if (i < rows) {
+      const bool keep = kept(i);
+      const unsigned long long v_k = __ballot(keep);
+      if (keep)
+        idx[keep_before + keep_sh[i * kSelWaves + wave] + rank_in_wave(v_k)] = x.first + i * kSelThreads + tid;
+    }
+}
+
 // EvictByIndex as a gather: workgroup (chunk, stream) copies kept tokens
 // [256 chunk, 256 chunk + 256) of the stream; a wave moves four rows of up to
 // 256 bytes per instruction.
@@ -862,6 +1097,10 @@ __global__ __launch_bounds__(kThreads) void prefill_gather(const GatherParams P)
   if (first >= pd.k) return;
   const int64_t u = static_cast<int64_t>(P.stream0) + ul;
   const int t = P.t;
+  // A selection that gave up a wait leaves no trustworthy index list: nothing of that stream is copied.
+  if (P.check_flag &&
+      __hip_atomic_load(P.split + u * kSplitWords + kSplitFlag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)
+    return;
   const int32_t* idx = P.idx + u * t;
   const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
   const int last = min(pd.k, first + kThreads);
@@ -946,9 +1185,26 @@ bool pick_window(int dtype, int head_dim, int nb, WindowFn* stats, WindowFn* mas
   return false;
 }
 
+// Workgroups of split_fused that are resident at once (0 if unknown).
+int split_fused_capacity() {
+  static int cap = -1;
+  if (cap < 0) {
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(split_fused), kSelThreads, 0) ==
+            hipSuccess)
+      cap = per_cu * cus;
+    else
+      cap = 0;
+    (void)hipGetLastError();
+  }
+  return cap;
+}
+
 // Workspace layout for `streams` streams of t tokens; every part starts on a
 // 256-byte boundary.  Returns the total; the offsets are in bytes.
-struct PrefillLayout { size_t stats, fin, w, keys, idx, split, dlog, tref, total; };
+struct PrefillLayout { size_t stats, fin, w, keys, idx, split, flag, dlog, tref, total; };
 
 size_t round256(size_t b) { return (b + 255) / 256 * 256; }
 
@@ -976,6 +1232,7 @@ PrefillLayout prefill_layout(int64_t streams, int t, int nq_pad, bool own_w, boo
   L.keys = off;  off += pooled ? round256(static_cast<size_t>(streams) * t * sizeof(uint32_t)) : 0;
   L.idx = off;   off += round256(static_cast<size_t>(streams) * t * sizeof(int32_t));
   L.split = off; off += round256(static_cast<size_t>(streams) * kSplitWords * sizeof(unsigned));
+  L.flag = off;  off += 256;
   // one-pass variant (nqs > 0): 16-bit distances per (token, stored query row), a reference per tile
   L.dlog = off;  off += nqs > 0 ? round256(static_cast<size_t>(streams) * round32(t) * nqs * 2) : 0;
   L.tref = off;  off += nqs > 0 ? round256(static_cast<size_t>(streams) * (round32(t) / 32) * nqs * sizeof(float)) : 0;
@@ -1015,7 +1272,7 @@ xkv_status check_prefill_shape(const xkv_cache* cache, int32_t t, int32_t ows, i
 xkv_status launch_window_mass(const xkv_cache* cache, int64_t streams, const void* q_win,
                               const void* k_src, int32_t t, int32_t ows, int nb, float softmax_scale,
                               WindowFn stats_fn, WindowFn mass_fn, char* ws, const PrefillLayout& L, float* w,
-                              int nqs, hipStream_t stream, WindowParams& W) {
+                              int nqs, bool selection_follows, hipStream_t stream, WindowParams& W) {
   const int D = cache->head_dim;
   const int strip_rows = prefill_strip_rows(streams, t);
   const int64_t nstrips = ceil_div(t, strip_rows);
@@ -1027,6 +1284,8 @@ xkv_status launch_window_mass(const xkv_cache* cache, int64_t streams, const voi
   W.w = w;
   W.dlog = reinterpret_cast<unsigned short*>(ws + L.dlog);
   W.tref = reinterpret_cast<float*>(ws + L.tref);
+  W.split = selection_follows ? reinterpret_cast<unsigned*>(ws + L.split) : nullptr;
+  W.call_flag = reinterpret_cast<unsigned*>(ws + L.flag);
   const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt(static_cast<float>(D));
   W.scale_log2e = scale * 1.44269504088896340736f;
   W.t = t; W.ows = ows;
@@ -1095,7 +1354,7 @@ extern "C" xkv_status xkv_window_importance(const xkv_cache* cache, int32_t laye
   char* ws = static_cast<char*>(workspace);
   float* w_dense = reinterpret_cast<float*>(ws + L.w);
   st = launch_window_mass(cache, streams, q_win, k_src, t, ows, nb, softmax_scale, stats_fn, mass_fn, ws, L,
-                          w_dense, nqs, stream, W);
+                          w_dense, nqs, false, stream, W);
   if (st != XKV_OK) return st;
   const int tc = t - ows;
   if (tc > 0) {
@@ -1199,7 +1458,7 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
   char* ws = static_cast<char*>(workspace);
   float* w_dense = w_out != nullptr ? w_out : reinterpret_cast<float*>(ws + L.w);
   st = launch_window_mass(cache, streams, q_win, k_src, t, ows, nb, softmax_scale, stats_fn, mass_fn, ws, L,
-                          w_dense, nqs, stream, W);
+                          w_dense, nqs, true, stream, W);
   if (st != XKV_OK) return st;
 
   GatherParams Gp;
@@ -1209,6 +1468,15 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
   Gp.keys = reinterpret_cast<uint32_t*>(ws + L.keys);
   Gp.idx = reinterpret_cast<int32_t*>(ws + L.idx);
   Gp.split = reinterpret_cast<unsigned*>(ws + L.split);
+  Gp.call_flag = reinterpret_cast<unsigned*>(ws + L.flag);
+  Gp.check_flag = 0;
+  Gp.spin_limit = std::min<uint32_t>(fused_spin_limit(), kSplitSpinLimit);
+  // The selection as one launch of (chunk, stream) workgroups with waits between its steps,
+  // whenever a stream has at least two chunks and the whole grid is resident at once.
+  const int64_t sel_chunks = ceil_div(t - ows, kSplitChunk);
+  const bool fused_sel_possible = pool_size <= 63 && sel_chunks >= 2 && sel_chunks <= kSplitMaxChunks;
+  bool any_fused_sel = false;
+  note_waiting_launch(nullptr, stream);           // xkv_fused_status speaks of this call from here on
   Gp.t = t; Gp.ows = ows; Gp.pool = pool_size; Gp.n_kv_heads = hkv;
   Gp.row_bytes = D * (cache->dtype == XKV_F32 ? 4 : 2);
   for (int64_t g0 = 0; g0 < n_pairs; g0 += kMaxPairs) {
@@ -1226,9 +1494,15 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
     Gp.stream0 = static_cast<int32_t>(g0 * hkv);
     const int tc = t - ows;
     const unsigned n_streams = static_cast<unsigned>(np * hkv);
-    if (use_split) {
+    Gp.check_flag = 0;
+    if (fused_sel_possible && sel_chunks * n_streams <= split_fused_capacity()) {
+      const dim3 grid(static_cast<unsigned>(sel_chunks), n_streams);
+      hipLaunchKernelGGL(split_fused, grid, dim3(kSelThreads), 0, stream, Gp);
+      if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+      Gp.check_flag = 1;
+      any_fused_sel = true;
+    } else if (use_split) {
       const dim3 grid(static_cast<unsigned>(ceil_div(tc, kSplitChunk)), n_streams);
-      hipLaunchKernelGGL(split_zero, dim3(n_streams), dim3(kThreads), 0, stream, Gp);
       hipLaunchKernelGGL(split_keys, grid, dim3(kSelThreads), 0, stream, Gp);
       for (int pass = 1; pass < 4; ++pass)
         hipLaunchKernelGGL(split_hist, grid, dim3(kSelThreads), 0, stream, Gp, pass);
@@ -1244,6 +1518,7 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
                        dim3(kThreads), 0, stream, Gp);
     if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
   }
+  if (any_fused_sel) note_waiting_launch(Gp.call_flag, stream);
   for (int64_t i = 0; i < n_pairs; ++i)
     cache->len[first + i] = static_cast<int32_t>(std::min<int64_t>(budgets[i], seq_len(i)));
   return XKV_OK;

@@ -27,6 +27,13 @@ xkv_status check_layers(const xkv_cache* c, int32_t layer_begin, int32_t layer_e
 size_t attend_workspace_bytes(const xkv_cache* c, int32_t layers);
 size_t evict_workspace_bytes(const xkv_cache* c, int32_t layers);
 
+// Remembers the control words of the most recent launch that waits inside a kernel
+// (word 1: some workgroup gave up its wait), for xkv_fused_status; null: the most
+// recent call had no such launch.
+void note_waiting_launch(const unsigned* control, void* stream);
+// XKV_CFG_FUSED_SPIN_LIMIT as it stands.
+uint32_t fused_spin_limit();
+
 // Per-kernel event timing (xkv_profile_*).  begin() returns a token >= 0 when
 // timing is on and records the start event on the stream; end() records the
 // stop event.  Both are no-ops when timing is off.

@@ -58,6 +58,7 @@ def run_prefill(xkv, dtype, d, Hq, Hkv, L, B, t, ows, ps, budgets, seed, scale=0
     xkv.xkv_prefill_evict(cache, l0, l1, q_win, k_src, v_src, t, ows, budgets[l0:l1], ws, pool_size=ps,
                           softmax_scale=scale, w_out=w_out, t_per_seq=t_per_seq)
     torch.cuda.synchronize()
+    assert not xkv.xkv_fused_status()           # no wait of a one-launch selection gave up
     w_dev = w_out.cpu().numpy() if with_w else None
     worst = 0.0
     for l in range(L):
@@ -219,6 +220,47 @@ def test_long_streams_split_selection_random_scores(xkv):
     o = run_prefill(xkv, "bf16", 128, 4, 2, 1, 2, 50003, 8, 7, [[12345, 49000]], seed=41)
     print("split selection w rel err", o, flush=True)
     run_prefill(xkv, "f32", 64, 2, 2, 1, 1, 33000, 8, 1, [[8]], seed=42)        # window only
+
+
+def test_one_launch_selection_give_up_is_reported(xkv):
+    """Failure handling of the one-launch selection, forced from the host: with a poll limit of
+    zero every workgroup gives up its first wait unpolled.  The kernels must still end normally,
+    the status call must report it, the regions of the streams concerned keep what they held,
+    and a stream that needs no selection (budget >= prompt) is filled all the same.  With the
+    default limit the same call then completes and matches the oracle."""
+    t, ows, ps, d = 20000, 8, 7, 64
+    budgets = np.array([[5000, 20000]], np.int32)
+    cache = xkv.XkvCache(1, 2, 1, 1, d, "f32", budgets + 2)
+    g = torch.Generator(device="cpu").manual_seed(97)
+    k_src = torch.randn((1, 2, 1, t, d), generator=g).cuda()
+    v_src = torch.randn((1, 2, 1, t, d), generator=g).cuda()
+    q_win = torch.randn((1, 2, 1, ows, d), generator=g).cuda()
+    ws = torch.empty(xkv.xkv_prefill_workspace_bytes(cache, 1, t, ows), dtype=torch.uint8, device="cuda")
+    cache.k.fill_(7.0)
+    cache.pos.fill_(-5)
+    xkv.xkv_configure(xkv.XKV_CFG_FUSED_SPIN_LIMIT, 0)
+    try:
+        print("case one-launch selection give-up, poll limit 0", flush=True)
+        xkv.xkv_prefill_evict(cache, 0, 1, q_win, k_src, v_src, t, ows, budgets, ws, pool_size=ps)
+        gave_up = xkv.xkv_fused_status()
+    finally:
+        xkv.xkv_configure(xkv.XKV_CFG_FUSED_SPIN_LIMIT, -1)
+    assert gave_up
+    assert cache.length(0, 0) == 5000 and cache.length(0, 1) == 20000
+    K0, _, _, p0 = get_unit(cache, 0, 0, 0)
+    assert np.all(K0 == 7.0) and np.all(p0 == -5)                     # untouched
+    K1, V1, _, p1 = get_unit(cache, 0, 1, 0)
+    assert np.array_equal(p1, np.arange(t)) and np.array_equal(K1, storage(k_src[0, 1, 0]))
+    assert np.array_equal(V1, storage(v_src[0, 1, 0]))
+    w_out = torch.empty((1, 2, 1, t), dtype=torch.float32, device="cuda")
+    xkv.xkv_prefill_evict(cache, 0, 1, q_win, k_src, v_src, t, ows, budgets, ws, pool_size=ps, w_out=w_out)
+    assert not xkv.xkv_fused_status()
+    wd = w_out.cpu().numpy()[0, 0, 0]
+    K0, V0, s0, p0 = get_unit(cache, 0, 0, 0)
+    ref = orc.prefill_select(wd, ows, 5000, ps)
+    assert np.array_equal(p0, ref)
+    assert np.array_equal(K0, storage(k_src[0, 0, 0])[ref]) and np.array_equal(V0, storage(v_src[0, 0, 0])[ref])
+    assert np.array_equal(s0, wd[ref])
 
 
 @pytest.mark.parametrize("dtype,d,G", [("bf16", 128, 4), ("f32", 64, 1), ("bf16", 128, 1)])
