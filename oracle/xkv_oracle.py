@@ -207,7 +207,35 @@ def evict_compact(K, V, score, pos, budget: int, pool_size: int = 1, n_protect: 
 # --------------------------------------------------------------------------
 # Alg. 2 as written, for the prefill phase (Sec. 4.1, attention processing)
 # --------------------------------------------------------------------------
-def window_attention_mass(q_win, K, scale=None) -> np.ndarray:
+def window_row_lse(q_win, K, scale=None) -> np.ndarray:
+    """Natural logarithm of the softmax normaliser (Eq. 2) of every window row.
+
+    q_win [G, ows, d], K [t, d] as for ``window_attention_mass``.  Returns
+    lse [G, ows] in float64 with
+    lse[g][r] = ln sum_{j <= t - ows + r} exp(scale * q_win[g][r] . K[j]):
+    what an attention forward pass over the prompt leaves behind for its last
+    ows query rows, so that W_attn[g][t - ows + r][j] = exp(logit - lse[g][r]).
+    """
+    q_win = as_f64(q_win)
+    K = as_f64(K)
+    G, ows, d = q_win.shape
+    t = K.shape[0]
+    if ows < 1 or ows > t:
+        raise ValueError("need 1 <= ows <= t")
+    if scale is None:
+        scale = 1.0 / np.sqrt(float(d))
+    scale = float(scale)
+    lse = np.zeros((G, ows), dtype=np.float64)
+    for g in range(G):
+        for r in range(ows):
+            last = t - ows + r
+            s = scale * (K[:last + 1] @ q_win[g, r])
+            top = np.max(s)
+            lse[g, r] = top + np.log(np.sum(np.exp(s - top)))
+    return lse
+
+
+def window_attention_mass(q_win, K, scale=None, lse=None) -> np.ndarray:
     """Attention mass that the observation window puts on every prompt token.
 
     q_win  [G, ows, d]  queries of the last ``ows`` prompt positions, for the G
@@ -221,6 +249,10 @@ def window_attention_mass(q_win, K, scale=None) -> np.ndarray:
     entries are the Select block merged over the window rows and the heads
     (sum; the paper's mean is this divided by the constant ows); the last ows
     entries are the mass the window puts on itself.  sum(w) = G * ows.
+
+    lse [G, ows] (optional): the rows' normalisers as the caller has them
+    (``window_row_lse``); the weights are then exp(logit - lse[g][r]), whatever
+    lse holds, and the softmax is not normalised again.
     """
     q_win = as_f64(q_win)
     K = as_f64(K)
@@ -231,13 +263,20 @@ def window_attention_mass(q_win, K, scale=None) -> np.ndarray:
     if scale is None:
         scale = 1.0 / np.sqrt(float(d))
     scale = float(scale)
+    if lse is not None:
+        lse = as_f64(lse)
+        if lse.shape != (G, ows):
+            raise ValueError("lse must be [G, ows]")
     w = np.zeros(t, dtype=np.float64)
     for g in range(G):
         for r in range(ows):
             last = t - ows + r                # the row's own position
             s = scale * (K[:last + 1] @ q_win[g, r])
-            e = np.exp(s - np.max(s))
-            w[:last + 1] += e / np.sum(e)
+            if lse is None:
+                e = np.exp(s - np.max(s))
+                w[:last + 1] += e / np.sum(e)
+            else:
+                w[:last + 1] += np.exp(s - lse[g, r])
     return w
 
 

@@ -154,3 +154,50 @@ def test_window_importance_merges_heads_then_pools():
     w1 = orc.window_importance(Q[:, :, t - ows:, :], K, 1)
     own = sum(orc.window_attention_mass(Q[h, :, t - ows:, :], K[h])[t - ows:].sum() for h in range(Hkv))
     assert abs(w1.sum() + own - Hkv * G * ows) < 1e-9
+
+
+# ---- the window rows' normalisers (Eq. 2), for callers that already hold them ----
+
+@pytest.mark.parametrize("t,ows,G,d", [(9, 3, 1, 4), (20, 8, 2, 8), (33, 1, 4, 16), (12, 12, 1, 4)])
+def test_row_lse_against_the_full_logit_matrix(t, ows, G, d):
+    """lse of window row r = logsumexp of row t - ows + r of the causally masked
+    t x t logit matrix, built independently and reduced with SciPy's routine."""
+    from scipy.special import logsumexp
+    r = np.random.default_rng(t * 7 + ows)
+    Q = r.normal(size=(G, t, d)).astype(np.float32)
+    K = (3.0 * r.normal(size=(t, d))).astype(np.float32)
+    scale = 0.37
+    lse = orc.window_row_lse(Q[:, t - ows:, :], K, scale)
+    for g in range(G):
+        S = scale * (Q[g].astype(np.float64) @ K.astype(np.float64).T)
+        S[np.triu_indices(t, k=1)] = -np.inf
+        assert np.allclose(lse[g], logsumexp(S[t - ows:], axis=1), rtol=1e-13, atol=1e-13)
+
+
+def test_row_lse_closed_forms():
+    """Zero keys: every logit is 0 and row r sees t - ows + r + 1 of them.  And the
+    hand example (keys 0, ln 2, ln 3; queries 1): normalisers 3 and 6."""
+    t, ows, d = 10, 4, 4
+    q = np.random.default_rng(1).normal(size=(2, ows, d)).astype(np.float32)
+    lse = orc.window_row_lse(q, np.zeros((t, d), np.float32))
+    assert np.allclose(lse, np.log(np.arange(t - ows + 1, t + 1))[None, :].repeat(2, 0), atol=1e-15)
+    K = np.array([[0.0], [np.log(2.0)], [np.log(3.0)]])
+    assert np.allclose(orc.window_row_lse(np.ones((1, 2, 1)), K, scale=1.0), [[np.log(3.0), np.log(6.0)]], atol=1e-15)
+
+
+def test_mass_with_given_normalisers():
+    """With the rows' own lse the masses are the softmax masses; with every lse
+    raised by ln 2 they are halved (the given normaliser is used as it is); and a
+    large common shift of the logits changes nothing (no overflow in lse)."""
+    r = np.random.default_rng(9)
+    G, ows, t, d = 2, 5, 60, 8
+    q = r.normal(size=(G, ows, d)).astype(np.float32)
+    K = r.normal(size=(t, d)).astype(np.float32)
+    w = orc.window_attention_mass(q, K)
+    lse = orc.window_row_lse(q, K)
+    assert np.allclose(orc.window_attention_mass(q, K, lse=lse), w, rtol=1e-12, atol=1e-16)
+    assert np.allclose(orc.window_attention_mass(q, K, lse=lse + np.log(2.0)), 0.5 * w, rtol=1e-12, atol=1e-16)
+    big = orc.window_row_lse(1000.0 * q, K, scale=1.0)
+    assert np.all(np.isfinite(big))
+    with pytest.raises(ValueError):
+        orc.window_attention_mass(q, K, lse=lse[:, :2])
