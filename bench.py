@@ -27,6 +27,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import statistics
 import sys
@@ -590,25 +591,41 @@ def prefill_leg(xkv, wl, w, budgets, torch, np, stream, layers_per_call=(1, 4)):
         xkv.xkv_prefill_evict(dst, 0, lpc, q_win, k_src, v_src, w.context, ows, bud_p[0:lpc], ws_p, pool_size=ps,
                               stream=stream)                                 # warm-up
         torch.cuda.synchronize()
+        def timed(call):
+            reps = []
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for l in range(0, L, lpc):
+                    call(l)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                reps.append(e0.elapsed_time(e1) * 1e-3)
+            if xkv.xkv_fused_status():
+                raise RuntimeError("a wait of the one-launch selection gave up during the prefill leg")
+            return statistics.median(reps)
+
         xkv.xkv_profile_enable(True)
-        reps = []
-        for _ in range(3):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            for l in range(0, L, lpc):
-                xkv.xkv_prefill_evict(dst, l, l + lpc, q_win, k_src, v_src, w.context, ows, bud_p[l:l + lpc], ws_p,
-                                      pool_size=ps, stream=stream)
-            e1.record(stream)
-            torch.cuda.synchronize()
-            reps.append(e0.elapsed_time(e1) * 1e-3)
-        dt = statistics.median(reps)
+        dt = timed(lambda l: xkv.xkv_prefill_evict(dst, l, l + lpc, q_win, k_src, v_src, w.context, ows,
+                                                   bud_p[l:l + lpc], ws_p, pool_size=ps, stream=stream))
         n_stats, ms_stats = xkv.xkv_profile_read(2)
         xkv.xkv_profile_enable(False)
+        # The same with the window rows' normalisers given, as an attention forward pass over the prompt
+        # leaves them (computed here with torch, outside the timed region): K is read once.
+        lse = window_row_lse_torch(torch, q_win, k_src, w.n_q_heads // w.n_kv_heads)
+        xkv.xkv_prefill_evict_lse(dst, 0, lpc, q_win, k_src, v_src, w.context, ows, bud_p[0:lpc], lse, ws_p,
+                                  pool_size=ps, stream=stream)
+        torch.cuda.synchronize()
+        dt_lse = timed(lambda l: xkv.xkv_prefill_evict_lse(dst, l, l + lpc, q_win, k_src, v_src, w.context, ows,
+                                                           bud_p[l:l + lpc], lse, ws_p, pool_size=ps, stream=stream))
+        del lse
         leg = {"layers_per_call": lpc, "ms_per_layer": dt / L * 1e3, "layers_per_s": L / dt,
                "hbm_gbs": pre_bytes / dt / 1e9, "hbm_frac": pre_bytes / dt / 1e9 / HBM_PEAK_GBS,
                "first_k_pass_avg_ms": ms_stats / n_stats if n_stats else None,
                "first_k_pass_hbm_frac": (lpc * k_pass_bytes / (ms_stats / n_stats * 1e-3) / 1e9 / HBM_PEAK_GBS)
-               if n_stats else None}
+               if n_stats else None,
+               "with_given_row_normalisers": {"ms_per_layer": dt_lse / L * 1e3,
+                                              "hbm_frac": pre_bytes / dt_lse / 1e9 / HBM_PEAK_GBS}}
         if out is None:
             out = {"ows": ows, "pool_size": ps, "algorithmic_bytes_per_layer": pre_bytes / L,
                    "note": "the same dense layers are the source for every call; budgets differ per layer; "
@@ -619,6 +636,23 @@ def prefill_leg(xkv, wl, w, budgets, torch, np, stream, layers_per_call=(1, 4)):
     best = max(out["by_layers_per_call"], key=lambda x: x["hbm_frac"])
     out.update({k: best[k] for k in ("layers_per_call", "ms_per_layer", "layers_per_s", "hbm_gbs", "hbm_frac")})
     del dst
+    return out
+
+
+def window_row_lse_torch(torch, q_win, k_src, group):
+    """ln of the softmax row sums of the window rows, [layers, B, Hq, ows] fp32, with torch ops: stands in
+    for what the model's attention forward pass over the prompt hands over (input preparation, untimed)."""
+    nl, B, Hq, ows, d = q_win.shape
+    t = k_src.shape[3]
+    out = torch.empty((nl, B, Hq, ows), dtype=torch.float32, device=q_win.device)
+    col = torch.arange(t, device=q_win.device)
+    seen = col[None, :] <= (t - ows + torch.arange(ows, device=q_win.device))[:, None]          # [ows, t]
+    for l in range(nl):
+        for b in range(B):
+            q = q_win[l, b].float().reshape(Hq // group, group * ows, d)
+            logits = torch.bmm(q, k_src[l, b].float().transpose(1, 2)) / math.sqrt(d)          # [Hkv, G ows, t]
+            logits = logits.reshape(Hq, ows, t).masked_fill(~seen[None], float("-inf"))
+            out[l, b] = torch.logsumexp(logits, dim=-1)
     return out
 
 

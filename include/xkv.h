@@ -346,6 +346,30 @@ xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, int32_t laye
                              size_t workspace_bytes, void* hip_stream);
 
 /*
+ * xkv_prefill_evict for a caller that already holds the softmax normalisers of the
+ * observation window's rows (Eq. 2): an attention forward pass over the prompt
+ * leaves, for every query row, the logarithm of its row sum; Alg. 2 takes the
+ * window's attention weights from that pass.  With them given the statistics pass
+ * over K is not needed and K is read once.
+ *
+ *   lse_win  DEVICE [layers][batch][n_q_heads][ows] fp32, natural logarithm:
+ *            lse = ln sum_{j <= tc + r} exp(scale * q_r . K_j) for window row r
+ *            (its causal range, sequence b's own t_b), the same scale as
+ *            softmax_scale
+ *
+ * Everything else as xkv_prefill_evict, with p_rj = exp(scale * q_r . K_j - lse):
+ * the result is that of xkv_prefill_evict up to rounding when lse_win holds the
+ * rows' true normalisers, and whatever the formula gives otherwise (the library
+ * cannot check them).  Both dtypes; same workspace size.
+ * Errors: as xkv_prefill_evict; INVALID_ARG for a NULL or misaligned lse_win.
+ */
+xkv_status xkv_prefill_evict_lse(xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                 const void* q_win, const void* k_src, const void* v_src, int32_t t,
+                                 const int32_t* t_per_seq, int32_t ows, int32_t pool_size,
+                                 const int32_t* budgets, float softmax_scale, const float* lse_win,
+                                 float* w_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * The attention processing module of the mini-prefill (Sec. 4.1, Eq. 3) for
  * layers [layer_begin, layer_end) of a cache geometry: the attention score
  * distribution vector of every (layer, sequence), ready for the allocator.
@@ -365,6 +389,17 @@ xkv_status xkv_window_importance(const xkv_cache* cache, int32_t layer_begin, in
                                  const void* q_win, const void* k_src, int32_t t,
                                  const int32_t* t_per_seq, int32_t ows, int32_t pool_size, float softmax_scale, float* w_out,
                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * xkv_window_importance with the window rows' normalisers given (lse_win as for
+ * xkv_prefill_evict_lse): K is read once.
+ * Errors: as xkv_window_importance; INVALID_ARG for a NULL or misaligned lse_win.
+ */
+xkv_status xkv_window_importance_lse(const xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                     const void* q_win, const void* k_src, int32_t t,
+                                     const int32_t* t_per_seq, int32_t ows, int32_t pool_size,
+                                     float softmax_scale, const float* lse_win, float* w_out,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * The attention score distribution vector of every (layer, sequence) of layers

@@ -25,11 +25,13 @@ from .binding import (  # noqa: F401
     xkv_evict_compact,
     xkv_fused_status,
     xkv_prefill_evict,
+    xkv_prefill_evict_lse,
     xkv_prefill_workspace_bytes,
     xkv_probe_stream_read,
     xkv_profile_enable,
     xkv_profile_read,
     xkv_repack,
     xkv_window_importance,
+    xkv_window_importance_lse,
     xkv_workspace_bytes,
 )

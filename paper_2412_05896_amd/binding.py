@@ -19,6 +19,7 @@ EXPORTS = (
     "xkv_configure", "xkv_probe_stream_read", "xkv_prefill_workspace_bytes", "xkv_prefill_evict",
     "xkv_window_importance", "xkv_allocate_device_workspace_bytes", "xkv_allocate_budgets_device",
     "xkv_average_allocations", "xkv_fused_status", "xkv_decode_attend_score_noalloc", "xkv_repack", "xkv_cache_importance",
+    "xkv_prefill_evict_lse", "xkv_window_importance_lse",
 )
 XKV_NOALLOC_SCRATCH_BYTES = 32 << 20
 XKV_CFG_ATTEND_PATH = 1
@@ -90,6 +91,15 @@ def load():
         C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
         C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t,
         C.c_void_p]
+    lib.xkv_prefill_evict_lse.restype = C.c_int32
+    lib.xkv_prefill_evict_lse.argtypes = [
+        C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+        C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+        C.c_void_p]
+    lib.xkv_window_importance_lse.restype = C.c_int32
+    lib.xkv_window_importance_lse.argtypes = [
+        C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+        C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.xkv_window_importance.restype = C.c_int32
     lib.xkv_window_importance.argtypes = [
         C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
@@ -301,6 +311,32 @@ def xkv_prefill_evict(cache: XkvCache, layer_begin, layer_end, q_win, k_src, v_s
         _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     _check(st, "xkv_prefill_evict")
+
+
+def xkv_prefill_evict_lse(cache: XkvCache, layer_begin, layer_end, q_win, k_src, v_src, t: int, ows: int,
+                          budgets, lse_win, workspace, pool_size: int = 1, softmax_scale: float = 0.0, w_out=None,
+                          stream=None, t_per_seq=None):
+    """xkv_prefill_evict with the window rows' normalisers given: lse_win device fp32 [layers, B, Hq, ows]."""
+    bud = None if budgets is None else np.ascontiguousarray(budgets, dtype=np.int32)
+    tps = None if t_per_seq is None else np.ascontiguousarray(t_per_seq, dtype=np.int32)
+    st = load().xkv_prefill_evict_lse(
+        C.byref(cache.struct), int(layer_begin), int(layer_end), _ptr(q_win), _ptr(k_src), _ptr(v_src),
+        int(t), _ptr(tps), int(ows), int(pool_size), _ptr(bud), float(softmax_scale), _ptr(lse_win), _ptr(w_out),
+        _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    _check(st, "xkv_prefill_evict_lse")
+
+
+def xkv_window_importance_lse(cache: XkvCache, layer_begin, layer_end, q_win, k_src, t: int, ows: int, lse_win,
+                              w_out, workspace, pool_size: int = 1, softmax_scale: float = 0.0, stream=None,
+                              t_per_seq=None):
+    """xkv_window_importance with the window rows' normalisers given: lse_win device fp32 [layers, B, Hq, ows]."""
+    tps = None if t_per_seq is None else np.ascontiguousarray(t_per_seq, dtype=np.int32)
+    st = load().xkv_window_importance_lse(
+        C.byref(cache.struct), int(layer_begin), int(layer_end), _ptr(q_win), _ptr(k_src), int(t), _ptr(tps),
+        int(ows), int(pool_size), float(softmax_scale), _ptr(lse_win), _ptr(w_out), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    _check(st, "xkv_window_importance_lse")
 
 
 def xkv_window_importance(cache: XkvCache, layer_begin, layer_end, q_win, k_src, t: int, ows: int, w_out,

@@ -56,6 +56,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 struct WindowParams {
   const void* q_win;      // [pairs][Hq][ows][D]
   const void* k_src;      // [pairs][Hkv][t][D]
+  const float* lse;       // [pairs][Hq][ows] natural-log normalisers of the window rows from the caller, or null
   float* stats;           // [streams][nstrips][nq_pad][2]  (max, sum) in the base-2 domain
   float* fin;             // [streams][nq_pad][2]           (max, 1 / sum)
   float* w;               // [streams][t]
@@ -481,8 +482,9 @@ __global__ __launch_bounds__(kThreads) void window_mass_stored(const WindowParam
   P.w[static_cast<int64_t>(u) * P.t + jpos] = acc;
 }
 
-// One workgroup per stream: the final stats of every query row; it also clears the
-// state words of the selection that follows (if one does).
+// One workgroup per stream: the final stats of every query row, folded from the
+// strips' or taken from the caller's normalisers; it also clears the state words of
+// the selection that follows (if one does).
 __global__ __launch_bounds__(kThreads) void window_merge(const WindowParams P) {
   __shared__ float part_sh[kThreads][2];
   const int u = blockIdx.x;
@@ -492,7 +494,17 @@ __global__ __launch_bounds__(kThreads) void window_merge(const WindowParams P) {
     if (u == 0 && threadIdx.x < 4) P.call_flag[threadIdx.x] = 0u;
   }
   float fm, fil;
-  stream_fin(P, u, part_sh, fm, fil);
+  if (P.lse != nullptr) {
+    // The caller's normalisers: 2^(s - lse log2 e), nothing to divide by.
+    const int qi = threadIdx.x, nq = P.ows * P.group;
+    const bool live = qi < nq;
+    const int g = live ? qi / P.ows : 0, r = live ? qi - g * P.ows : 0;
+    const int64_t row = (static_cast<int64_t>(u) * P.group + g) * P.ows + r;     // (pair, KV head, g) = (pair, query head)
+    fm = live && qi < P.nq_pad ? P.lse[row] * 1.44269504088896340736f : 0.0f;
+    fil = live ? 1.0f : 0.0f;
+  } else {
+    stream_fin(P, u, part_sh, fm, fil);
+  }
   if (threadIdx.x < P.nq_pad) {
     float* f = P.fin + (static_cast<int64_t>(u) * P.nq_pad + threadIdx.x) * 2;
     f[0] = fm;
@@ -1272,13 +1284,15 @@ xkv_status check_prefill_shape(const xkv_cache* cache, int32_t t, int32_t ows, i
 xkv_status launch_window_mass(const xkv_cache* cache, int64_t streams, const void* q_win,
                               const void* k_src, int32_t t, int32_t ows, int nb, float softmax_scale,
                               WindowFn stats_fn, WindowFn mass_fn, char* ws, const PrefillLayout& L, float* w,
-                              int nqs, bool selection_follows, hipStream_t stream, WindowParams& W) {
+                              int nqs, bool selection_follows, const float* lse_win, hipStream_t stream,
+                              WindowParams& W) {
   const int D = cache->head_dim;
   const int strip_rows = prefill_strip_rows(streams, t);
   const int64_t nstrips = ceil_div(t, strip_rows);
   if (streams * nstrips > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;
   W.q_win = q_win;
   W.k_src = k_src;
+  W.lse = lse_win;
   W.stats = reinterpret_cast<float*>(ws + L.stats);
   W.fin = reinterpret_cast<float*>(ws + L.fin);
   W.w = w;
@@ -1301,6 +1315,15 @@ xkv_status launch_window_mass(const xkv_cache* cache, int64_t streams, const voi
                         : (nqs == 8 ? window_stats_store<64, 8> : window_stats_store<64, 16>);
     mass_fn = nqs == 8 ? window_mass_stored<8> : window_mass_stored<16>;
   }
+  if (lse_win != nullptr) {
+    // The rows' normalisers are given: no statistics pass, K is read once.
+    hipLaunchKernelGGL(window_merge, dim3(static_cast<unsigned>(streams)), dim3(kThreads), 0, stream, W);
+    if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+    const int tok = profile_begin(2, stream);
+    hipLaunchKernelGGL(mass_fn, dim3(grid), dim3(kThreads), 0, stream, W);
+    profile_end(tok, stream);
+    return hipGetLastError() == hipSuccess ? XKV_OK : XKV_ERR_DEVICE;
+  }
   const int tok = profile_begin(2, stream);
   hipLaunchKernelGGL(stats_fn, dim3(grid), dim3(kThreads), 0, stream, W);
   profile_end(tok, stream);
@@ -1316,16 +1339,10 @@ xkv_status launch_window_mass(const xkv_cache* cache, int64_t streams, const voi
   return XKV_OK;
 }
 
-}  // namespace
-}  // namespace xkv
-
-extern "C" xkv_status xkv_window_importance(const xkv_cache* cache, int32_t layer_begin,
-                                            int32_t layer_end, const void* q_win, const void* k_src,
-                                            int32_t t, const int32_t* t_per_seq, int32_t ows,
-                                            int32_t pool_size,
-                                            float softmax_scale, float* w_out, void* workspace,
-                                            size_t workspace_bytes, void* hip_stream) {
-  using namespace xkv;
+xkv_status window_importance_impl(const xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                  const void* q_win, const void* k_src, int32_t t, const int32_t* t_per_seq,
+                                  int32_t ows, int32_t pool_size, float softmax_scale, const float* lse_win,
+                                  float* w_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
   xkv_status st = check_cache(cache);
   if (st != XKV_OK) return st;
   st = check_layers(cache, layer_begin, layer_end);
@@ -1346,7 +1363,8 @@ extern "C" xkv_status xkv_window_importance(const xkv_cache* cache, int32_t laye
   const int64_t streams = n_pairs * cache->n_kv_heads;
   WindowFn stats_fn = nullptr, mass_fn = nullptr;
   if (!pick_window(cache->dtype, cache->head_dim, nb, &stats_fn, &mass_fn)) return XKV_ERR_UNSUPPORTED;
-  const int nqs = one_pass_window(cache->dtype, nb) ? stored_query_rows(ows * (cache->n_q_heads / cache->n_kv_heads)) : 0;
+  const int nqs = lse_win == nullptr && one_pass_window(cache->dtype, nb)
+                      ? stored_query_rows(ows * (cache->n_q_heads / cache->n_kv_heads)) : 0;
   const PrefillLayout L = prefill_layout(streams, t, nb * 16, true, false, nqs);
   if (workspace == nullptr || L.total > workspace_bytes) return XKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return XKV_ERR_INVALID_ARG;
@@ -1354,7 +1372,7 @@ extern "C" xkv_status xkv_window_importance(const xkv_cache* cache, int32_t laye
   char* ws = static_cast<char*>(workspace);
   float* w_dense = reinterpret_cast<float*>(ws + L.w);
   st = launch_window_mass(cache, streams, q_win, k_src, t, ows, nb, softmax_scale, stats_fn, mass_fn, ws, L,
-                          w_dense, nqs, false, stream, W);
+                          w_dense, nqs, false, lse_win, stream, W);
   if (st != XKV_OK) return st;
   const int tc = t - ows;
   if (tc > 0) {
@@ -1365,36 +1383,11 @@ extern "C" xkv_status xkv_window_importance(const xkv_cache* cache, int32_t laye
   return XKV_OK;
 }
 
-extern "C" xkv_status xkv_prefill_workspace_bytes(const xkv_cache* cache, int32_t max_layers_per_call,
-                                                  int32_t t, int32_t ows, size_t* bytes_out) {
-  using namespace xkv;
-  xkv_status st = check_cache(cache);
-  if (st != XKV_OK) return st;
-  if (bytes_out == nullptr || max_layers_per_call <= 0) return XKV_ERR_INVALID_ARG;
-  int nb = 0;
-  st = check_prefill_shape(cache, t, ows, &nb);
-  if (st != XKV_OK) return st;
-  const int64_t layers = std::min<int64_t>(max_layers_per_call, cache->n_layers);
-  // A call on fewer layers has fewer streams and may pick shorter strips: take
-  // the largest need over the possible layer counts' strip lengths.
-  size_t worst = 0;
-  for (int64_t l = 1; l <= layers; ++l) {
-    const int64_t streams = l * cache->batch * cache->n_kv_heads;
-    worst = std::max(worst, prefill_layout(streams, t, nb * 16, true, true,
-                                           one_pass_window(cache->dtype, nb)
-                                               ? stored_query_rows(ows * (cache->n_q_heads / cache->n_kv_heads)) : 0).total);
-  }
-  *bytes_out = worst;
-  return XKV_OK;
-}
-
-extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
-                                        const void* q_win, const void* k_src, const void* v_src,
-                                        int32_t t, const int32_t* t_per_seq, int32_t ows,
-                                        int32_t pool_size,
-                                        const int32_t* budgets, float softmax_scale, float* w_out,
-                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
-  using namespace xkv;
+xkv_status prefill_evict_impl(xkv_cache* cache, int32_t layer_begin, int32_t layer_end, const void* q_win,
+                              const void* k_src, const void* v_src, int32_t t, const int32_t* t_per_seq,
+                              int32_t ows, int32_t pool_size, const int32_t* budgets, float softmax_scale,
+                              const float* lse_win, float* w_out, void* workspace, size_t workspace_bytes,
+                              void* hip_stream) {
   xkv_status st = check_cache(cache);
   if (st != XKV_OK) return st;
   st = check_layers(cache, layer_begin, layer_end);
@@ -1429,7 +1422,8 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
   const bool pooled = pool_size > 1;
   // Few long streams: the selection of a stream is split over several workgroups.
   const bool use_split = streams < 256 && t - ows >= 4 * kSplitChunk && pool_size <= 63;
-  const int nqs = one_pass_window(cache->dtype, nb) ? stored_query_rows(ows * (cache->n_q_heads / hkv)) : 0;
+  const int nqs = lse_win == nullptr && one_pass_window(cache->dtype, nb)
+                      ? stored_query_rows(ows * (cache->n_q_heads / hkv)) : 0;
   const PrefillLayout L = prefill_layout(streams, t, nb * 16, w_out == nullptr, pooled || use_split, nqs);
   if (workspace == nullptr || L.total > workspace_bytes) return XKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return XKV_ERR_INVALID_ARG;
@@ -1458,7 +1452,7 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
   char* ws = static_cast<char*>(workspace);
   float* w_dense = w_out != nullptr ? w_out : reinterpret_cast<float*>(ws + L.w);
   st = launch_window_mass(cache, streams, q_win, k_src, t, ows, nb, softmax_scale, stats_fn, mass_fn, ws, L,
-                          w_dense, nqs, true, stream, W);
+                          w_dense, nqs, true, lse_win, stream, W);
   if (st != XKV_OK) return st;
 
   GatherParams Gp;
@@ -1522,4 +1516,72 @@ extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, i
   for (int64_t i = 0; i < n_pairs; ++i)
     cache->len[first + i] = static_cast<int32_t>(std::min<int64_t>(budgets[i], seq_len(i)));
   return XKV_OK;
+}
+
+}  // namespace
+}  // namespace xkv
+
+extern "C" xkv_status xkv_prefill_workspace_bytes(const xkv_cache* cache, int32_t max_layers_per_call,
+                                                  int32_t t, int32_t ows, size_t* bytes_out) {
+  using namespace xkv;
+  xkv_status st = check_cache(cache);
+  if (st != XKV_OK) return st;
+  if (bytes_out == nullptr || max_layers_per_call <= 0) return XKV_ERR_INVALID_ARG;
+  int nb = 0;
+  st = check_prefill_shape(cache, t, ows, &nb);
+  if (st != XKV_OK) return st;
+  const int64_t layers = std::min<int64_t>(max_layers_per_call, cache->n_layers);
+  // A call on fewer layers has fewer streams and may pick shorter strips: take
+  // the largest need over the possible layer counts' strip lengths.
+  size_t worst = 0;
+  for (int64_t l = 1; l <= layers; ++l) {
+    const int64_t streams = l * cache->batch * cache->n_kv_heads;
+    worst = std::max(worst, prefill_layout(streams, t, nb * 16, true, true,
+                                           one_pass_window(cache->dtype, nb)
+                                               ? stored_query_rows(ows * (cache->n_q_heads / cache->n_kv_heads)) : 0).total);
+  }
+  *bytes_out = worst;
+  return XKV_OK;
+}
+
+extern "C" xkv_status xkv_window_importance(const xkv_cache* cache, int32_t layer_begin,
+                                            int32_t layer_end, const void* q_win, const void* k_src,
+                                            int32_t t, const int32_t* t_per_seq, int32_t ows,
+                                            int32_t pool_size,
+                                            float softmax_scale, float* w_out, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream) {
+  return xkv::window_importance_impl(cache, layer_begin, layer_end, q_win, k_src, t, t_per_seq, ows, pool_size,
+                                     softmax_scale, nullptr, w_out, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" xkv_status xkv_window_importance_lse(const xkv_cache* cache, int32_t layer_begin,
+                                                int32_t layer_end, const void* q_win, const void* k_src,
+                                                int32_t t, const int32_t* t_per_seq, int32_t ows,
+                                                int32_t pool_size, float softmax_scale, const float* lse_win,
+                                                float* w_out, void* workspace, size_t workspace_bytes,
+                                                void* hip_stream) {
+  if (lse_win == nullptr || (reinterpret_cast<uintptr_t>(lse_win) & 3u)) return XKV_ERR_INVALID_ARG;
+  return xkv::window_importance_impl(cache, layer_begin, layer_end, q_win, k_src, t, t_per_seq, ows, pool_size,
+                                     softmax_scale, lse_win, w_out, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" xkv_status xkv_prefill_evict(xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                        const void* q_win, const void* k_src, const void* v_src,
+                                        int32_t t, const int32_t* t_per_seq, int32_t ows,
+                                        int32_t pool_size,
+                                        const int32_t* budgets, float softmax_scale, float* w_out,
+                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return xkv::prefill_evict_impl(cache, layer_begin, layer_end, q_win, k_src, v_src, t, t_per_seq, ows, pool_size,
+                                 budgets, softmax_scale, nullptr, w_out, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" xkv_status xkv_prefill_evict_lse(xkv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                            const void* q_win, const void* k_src, const void* v_src,
+                                            int32_t t, const int32_t* t_per_seq, int32_t ows,
+                                            int32_t pool_size, const int32_t* budgets, float softmax_scale,
+                                            const float* lse_win, float* w_out, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream) {
+  if (lse_win == nullptr || (reinterpret_cast<uintptr_t>(lse_win) & 3u)) return XKV_ERR_INVALID_ARG;
+  return xkv::prefill_evict_impl(cache, layer_begin, layer_end, q_win, k_src, v_src, t, t_per_seq, ows, pool_size,
+                                 budgets, softmax_scale, lse_win, w_out, workspace, workspace_bytes, hip_stream);
 }

@@ -29,9 +29,27 @@ def check_selection_is_valid_for(w_ref, kept_pos, t, ows, ps, tol):
     assert key[kept].min() >= key[~kept].max() - 2 * slack
 
 
+def window_lse_of(q_win, k_src, G, tb, scale, units=None):
+    """The oracle's row normalisers of every stream as the fp32 tensor the lse entry points take
+    ([layers, B, Hq, ows]); streams outside `units` get NaN (the test does not look at them)."""
+    nl, B, Hq, ows, _ = q_win.shape
+    Hkv = Hq // G
+    out = np.full((nl, B, Hq, ows), np.nan, np.float32)
+    for l in range(nl):
+        for b in range(B):
+            for h in range(Hkv):
+                if units is not None and (l, b, h) not in units:
+                    continue
+                K = storage(k_src[l, b, h])[:int(tb[b])]
+                q = storage(q_win[l, b, h * G:(h + 1) * G])
+                out[l, b, h * G:(h + 1) * G] = orc.window_row_lse(q, K, None if scale == 0.0 else scale)
+    return out
+
+
 def run_prefill(xkv, dtype, d, Hq, Hkv, L, B, t, ows, ps, budgets, seed, scale=0.0, layer_range=None,
-                heavy=True, with_w=True, check_units=None, t_per_seq=None):
-    """t_per_seq: prompt length of every sequence (rows beyond it hold NaN: they must never be read)."""
+                heavy=True, with_w=True, check_units=None, t_per_seq=None, given_lse=False):
+    """t_per_seq: prompt length of every sequence (rows beyond it hold NaN: they must never be read).
+    given_lse: the call takes the window rows' normalisers from the oracle (xkv_prefill_evict_lse)."""
     budgets = np.asarray(budgets, np.int32).reshape(L, B)
     tb = np.full(B, t, np.int64) if t_per_seq is None else np.asarray(t_per_seq, np.int64)
     caps = np.minimum(budgets, tb[None, :]) + 3
@@ -55,8 +73,14 @@ def run_prefill(xkv, dtype, d, Hq, Hkv, L, B, t, ows, ps, budgets, seed, scale=0
     ws = torch.empty(xkv.xkv_prefill_workspace_bytes(cache, L, t, ows), dtype=torch.uint8, device="cuda")
     w_out = torch.full((nl, B, Hkv, t), float("nan"), dtype=torch.float32, device="cuda") if with_w else None
     cache.len[:] = 1                            # whatever was there is overwritten
-    xkv.xkv_prefill_evict(cache, l0, l1, q_win, k_src, v_src, t, ows, budgets[l0:l1], ws, pool_size=ps,
-                          softmax_scale=scale, w_out=w_out, t_per_seq=t_per_seq)
+    if given_lse:
+        assert layer_range is None
+        lse = torch.from_numpy(window_lse_of(q_win, k_src, G, tb, scale)).cuda()
+        xkv.xkv_prefill_evict_lse(cache, l0, l1, q_win, k_src, v_src, t, ows, budgets[l0:l1], lse, ws,
+                                  pool_size=ps, softmax_scale=scale, w_out=w_out, t_per_seq=t_per_seq)
+    else:
+        xkv.xkv_prefill_evict(cache, l0, l1, q_win, k_src, v_src, t, ows, budgets[l0:l1], ws, pool_size=ps,
+                              softmax_scale=scale, w_out=w_out, t_per_seq=t_per_seq)
     torch.cuda.synchronize()
     assert not xkv.xkv_fused_status()           # no wait of a one-launch selection gave up
     w_dev = w_out.cpu().numpy() if with_w else None
@@ -192,6 +216,16 @@ def test_full_size_layer_of_the_128k_gqa_workload(xkv):
     print("128k layer w rel err", e, flush=True)
 
 
+def test_full_size_layers_with_given_normalisers(xkv):
+    """The same two full-size layers through xkv_prefill_evict_lse (one K pass)."""
+    e = run_prefill(xkv, "bf16", 128, 32, 32, 1, 1, 32768, 8, 7, [[6554]], seed=31,
+                    check_units={(0, 0, h) for h in (3, 30)}, given_lse=True)
+    print("32k layer, given normalisers, w rel err", e, flush=True)
+    e = run_prefill(xkv, "bf16", 128, 64, 8, 1, 1, 131072, 8, 7, [[19661]], seed=33,
+                    check_units={(0, 0, 2), (0, 0, 7)}, given_lse=True)
+    print("128k layer, given normalisers, w rel err", e, flush=True)
+
+
 @pytest.mark.parametrize("ps", [1, 5])
 def test_long_stream_selection_split_over_workgroups_with_bulk_ties(xkv, ps):
     """Few long streams take the selection that is split over several workgroups.  Equal keys
@@ -220,6 +254,46 @@ def test_long_streams_split_selection_random_scores(xkv):
     o = run_prefill(xkv, "bf16", 128, 4, 2, 1, 2, 50003, 8, 7, [[12345, 49000]], seed=41)
     print("split selection w rel err", o, flush=True)
     run_prefill(xkv, "f32", 64, 2, 2, 1, 1, 33000, 8, 1, [[8]], seed=42)        # window only
+
+
+@pytest.mark.parametrize("dtype,d,G,ows", [("bf16", 128, 1, 8), ("bf16", 128, 4, 8), ("f32", 64, 2, 5),
+                                          ("bf16", 64, 8, 8), ("f32", 128, 1, 16)])
+def test_given_row_normalisers_read_k_once(xkv, dtype, d, G, ows):
+    """xkv_prefill_evict_lse: the masses from the caller's normalisers (here the oracle's) must be
+    the softmax masses, ragged prompts and a non-default scale included."""
+    print(f"case lse dtype={dtype} d={d} G={G} ows={ows}", flush=True)
+    run_prefill(xkv, dtype, d, 2 * G, 2, 2, 3, 1203, ows, 7, [[300, 1203, 40], [ows, 700, 999]], seed=120 + G,
+                given_lse=True, t_per_seq=[1203, 900, ows + 1])
+    run_prefill(xkv, dtype, d, 2 * G, 2, 1, 1, 700, ows, 1, [[100]], seed=130 + G, scale=0.21, given_lse=True,
+                with_w=False)
+
+
+def test_given_row_normalisers_are_used_as_they_are(xkv):
+    """Normalisers raised by ln 2 halve every mass (the library does not normalise again), and
+    the importance vectors of the mini-prefill take them the same way."""
+    L, B, Hq, Hkv, d, t, ows, ps = 1, 2, 4, 2, 128, 900, 8, 5
+    G = Hq // Hkv
+    cache = xkv.XkvCache(L, B, Hq, Hkv, d, "bf16", [[8, 8]])
+    g = torch.Generator(device="cpu").manual_seed(140)
+    k_src = torch.randn((L, B, Hkv, t, d), generator=g).bfloat16().cuda()
+    q_win = torch.randn((L, B, Hq, ows, d), generator=g).bfloat16().cuda()
+    lse = window_lse_of(q_win, k_src, G, [t, t], 0.0)
+    ws = torch.empty(xkv.xkv_prefill_workspace_bytes(cache, L, t, ows), dtype=torch.uint8, device="cuda")
+    w_a = torch.empty((L, B, t - ows), dtype=torch.float32, device="cuda")
+    w_b = torch.empty_like(w_a)
+    w_c = torch.empty_like(w_a)
+    xkv.xkv_window_importance(cache, 0, L, q_win, k_src, t, ows, w_a, ws, pool_size=ps)
+    xkv.xkv_window_importance_lse(cache, 0, L, q_win, k_src, t, ows, torch.from_numpy(lse).cuda(), w_b, ws,
+                                  pool_size=ps)
+    xkv.xkv_window_importance_lse(cache, 0, L, q_win, k_src, t, ows,
+                                  torch.from_numpy(lse + np.float32(np.log(2.0))).cuda(), w_c, ws, pool_size=ps)
+    torch.cuda.synchronize()
+    a, b, c = (x.cpu().numpy() for x in (w_a, w_b, w_c))
+    for s in range(B):
+        q = storage(q_win[0, s]).reshape(Hkv, G, ows, d)
+        ref = orc.window_importance(q, storage(k_src[0, s]), ps)
+        assert rel_err(a[0, s], ref) <= TOL["bf16"] and rel_err(b[0, s], ref) <= TOL["bf16"]
+        assert rel_err(c[0, s], 0.5 * ref) <= TOL["bf16"]
 
 
 def test_one_launch_selection_give_up_is_reported(xkv):
