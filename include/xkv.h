@@ -327,11 +327,11 @@ xkv_status xkv_repack(const xkv_cache* src, xkv_cache* dst, int32_t layer_begin,
  * CAPACITY (k' > cap or the workspace is too small), DEVICE.  Bit-reproducible.
  *
  * A call with few, long streams (more than 8192 candidates each, and no more
- * (8192-candidate chunk, stream) pairs than workgroups the chip holds at once)
- * runs TopK as one launch whose workgroups wait for each other between the
- * digits of the radix select.  The waits are bounded (XKV_CFG_FUSED_SPIN_LIMIT,
- * at most 2^16 polls); they complete whenever the launch is resident, which the
- * occupancy check ensures on an otherwise idle GPU.  Should one run out, the
+ * (8192-candidate chunk, stream) pairs than the GPU has compute units) runs TopK
+ * as one launch whose workgroups wait for each other between the digits of the
+ * radix select.  The waits are bounded (XKV_CFG_FUSED_SPIN_LIMIT, at most 2^16
+ * polls); they complete whenever the launch is resident, which one workgroup per
+ * compute unit is on an otherwise idle GPU.  Should one run out, the
  * regions of the streams concerned keep what they held before the call (their
  * len is still set to k'), the other streams are complete, and
  * xkv_fused_status reports it.

@@ -703,26 +703,34 @@ __device__ __forceinline__ bool split_idle(const SplitCtx& x) {   // nothing to 
 }
 
 // Adds the chunk's keys that match (mask, prefix) to the stream's histogram of digit `pass`.
+// The top digits of attention masses take few values, and one LDS atomic per key
+// would serialise on those bins: per key row a wave first counts, with two votes,
+// the lanes that share the bin of its first and of its next unserved lane (one
+// atomic each); whoever is left adds for itself.
 __device__ __forceinline__ void split_add_hist(const SplitCtx& x, const unsigned (&kreg)[kSplitKeys], int pass,
                                                unsigned prefix, unsigned mask, unsigned* hist_sh) {
   const int tid = threadIdx.x;
+  const int lane = tid & 63;
   const int shift = 24 - 8 * pass;
   if (tid < 256) hist_sh[tid] = 0;
   __syncthreads();
-  unsigned run_bin = 0, run_len = 0;
 #pragma unroll
   for (int i = 0; i < kSplitKeys; ++i) {
-    if (i * kSelThreads + tid < x.n && (kreg[i] & mask) == prefix) {
-      const unsigned bin = (kreg[i] >> shift) & 255u;
-      if (bin != run_bin && run_len != 0) {
-        atomicAdd(&hist_sh[run_bin], run_len);
-        run_len = 0;
-      }
-      run_bin = bin;
-      ++run_len;
+    bool todo = i * kSelThreads + tid < x.n && (kreg[i] & mask) == prefix;
+    const unsigned bin = (kreg[i] >> shift) & 255u;
+#pragma unroll
+    for (int round = 0; round < 2; ++round) {
+      const unsigned long long v_todo = __ballot(todo);
+      if (v_todo == 0) break;
+      const int leader = __ffsll(static_cast<long long>(v_todo)) - 1;
+      const unsigned lead_bin = __shfl(bin, leader);
+      const bool same = todo && bin == lead_bin;
+      const unsigned long long v_same = __ballot(same);
+      if (lane == leader) atomicAdd(&hist_sh[lead_bin], static_cast<unsigned>(__popcll(v_same)));
+      todo = todo && !same;
     }
+    if (todo) atomicAdd(&hist_sh[bin], 1u);
   }
-  if (run_len != 0) atomicAdd(&hist_sh[run_bin], run_len);
   __syncthreads();
   if (tid < 256 && hist_sh[tid] != 0) atomicAdd(&x.st[pass * 256 + tid], hist_sh[tid]);
 }
@@ -988,9 +996,21 @@ __global__ __launch_bounds__(kSelThreads) void split_fused(const GatherParams P)
   // ---- keys of this chunk, in registers ---------------------------------------------
   const float* w = P.w + x.u * x.t;
   const int half = P.pool >> 1;                   // pool <= 63 on this path (checked on the host)
-  for (int i = tid; i < x.n + 2 * half; i += kSelThreads) {
-    const int cnd = x.first - half + i;
-    wpad_sh[i] = (cnd >= 0 && cnd < x.tc) ? w[cnd] : 0.0f;
+  {
+    // candidates first - half .. first + n + half, zeros outside the candidate vector; all requested
+    // before the first is stored
+    float wv[kSplitKeys + 1];
+#pragma unroll
+    for (int k = 0; k <= kSplitKeys; ++k) {
+      const int i = k * kSelThreads + tid;
+      const int cnd = x.first - half + i;
+      wv[k] = (i < x.n + 2 * half && cnd >= 0 && cnd < x.tc) ? w[cnd] : 0.0f;
+    }
+#pragma unroll
+    for (int k = 0; k <= kSplitKeys; ++k) {
+      const int i = k * kSelThreads + tid;
+      if (i < x.n + 2 * half) wpad_sh[i] = wv[k];
+    }
   }
   __syncthreads();
   unsigned kreg[kSplitKeys];
@@ -1028,8 +1048,15 @@ __global__ __launch_bounds__(kSelThreads) void split_fused(const GatherParams P)
       gt += kreg[i] > thr;
       eq += kreg[i] == thr;
     }
-  if (gt) atomicAdd(&cnt_sh[0], gt);
-  if (eq) atomicAdd(&cnt_sh[1], eq);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    gt += __shfl_xor(gt, off);
+    eq += __shfl_xor(eq, off);
+  }
+  if (lane == 0) {
+    if (gt) atomicAdd(&cnt_sh[0], gt);
+    if (eq) atomicAdd(&cnt_sh[1], eq);
+  }
   __syncthreads();
   if (tid == 0)                                   // both counts are at most kSplitChunk = 2^13
     __hip_atomic_store(x.st + kSplitCounts + x.c, kSplitValid | (cnt_sh[0] << 14) | cnt_sh[1], __ATOMIC_RELAXED,
@@ -1197,7 +1224,11 @@ bool pick_window(int dtype, int head_dim, int nb, WindowFn* stats, WindowFn* mas
   return false;
 }
 
-// Workgroups of split_fused that are resident at once (0 if unknown).
+// Largest grid of split_fused: one workgroup per compute unit (0 if the kernel does
+// not fit a compute unit, or on an error).  The occupancy query allows two per unit,
+// but measured launches of more than one per unit run in rounds of that many
+// (54 us for 512 workgroups against 26 us for 128 to 256), and then one workgroup per
+// stream (prefill_select) or the launch-per-step split are as fast or faster.
 int split_fused_capacity() {
   static int cap = -1;
   if (cap < 0) {
@@ -1206,7 +1237,7 @@ int split_fused_capacity() {
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
         hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(split_fused), kSelThreads, 0) ==
             hipSuccess)
-      cap = per_cu * cus;
+      cap = per_cu >= 1 ? cus : 0;
     else
       cap = 0;
     (void)hipGetLastError();
@@ -1466,7 +1497,7 @@ xkv_status prefill_evict_impl(xkv_cache* cache, int32_t layer_begin, int32_t lay
   Gp.check_flag = 0;
   Gp.spin_limit = std::min<uint32_t>(fused_spin_limit(), kSplitSpinLimit);
   // The selection as one launch of (chunk, stream) workgroups with waits between its steps,
-  // whenever a stream has at least two chunks and the whole grid is resident at once.
+  // whenever a stream has at least two chunks and the grid is at most one workgroup per compute unit.
   const int64_t sel_chunks = ceil_div(t - ows, kSplitChunk);
   const bool fused_sel_possible = pool_size <= 63 && sel_chunks >= 2 && sel_chunks <= kSplitMaxChunks;
   bool any_fused_sel = false;
