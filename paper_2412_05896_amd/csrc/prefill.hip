@@ -146,10 +146,23 @@ __global__ __launch_bounds__(kThreads) void window_pass(const WindowParams P) {
       qreg[nb][sl] = raw;
     }
     if (kPhase == 1) {
-      const float* f = P.fin + (static_cast<int64_t>(u) * P.nq_pad + qi) * 2;
-      m_fin[nb] = f[0];
-      inv_fin[nb] = f[1];
+      if (P.lse != nullptr) {
+        // The caller's normalisers: 2^(s - lse log2 e), nothing to divide by.
+        const int64_t row = (static_cast<int64_t>(u) * P.group + g) * ows + r;   // (pair, KV head, g) = (pair, query head)
+        m_fin[nb] = live ? P.lse[row] * 1.44269504088896340736f : 0.0f;
+        inv_fin[nb] = live ? 1.0f : 0.0f;
+      } else {
+        const float* f = P.fin + (static_cast<int64_t>(u) * P.nq_pad + qi) * 2;
+        m_fin[nb] = f[0];
+        inv_fin[nb] = f[1];
+      }
     }
+  }
+  if (kPhase == 1 && P.lse != nullptr && P.split != nullptr && s == 0) {
+    // No merge kernel runs on this path: the stream's first strip clears the state words of the selection.
+    unsigned* st = P.split + static_cast<int64_t>(u) * kSplitWords;
+    for (int i = tid; i < kSplitWords; i += kThreads) st[i] = 0u;
+    if (u == 0 && tid < 4) P.call_flag[tid] = 0u;
   }
 
   float m_run[NB], l_run[NB];
@@ -483,8 +496,8 @@ __global__ __launch_bounds__(kThreads) void window_mass_stored(const WindowParam
 }
 
 // One workgroup per stream: the final stats of every query row, folded from the
-// strips' or taken from the caller's normalisers; it also clears the state words of
-// the selection that follows (if one does).
+// strips'; it also clears the state words of the selection that follows (if one
+// does).  (With the caller's normalisers the single K pass does both itself.)
 __global__ __launch_bounds__(kThreads) void window_merge(const WindowParams P) {
   __shared__ float part_sh[kThreads][2];
   const int u = blockIdx.x;
@@ -494,17 +507,7 @@ __global__ __launch_bounds__(kThreads) void window_merge(const WindowParams P) {
     if (u == 0 && threadIdx.x < 4) P.call_flag[threadIdx.x] = 0u;
   }
   float fm, fil;
-  if (P.lse != nullptr) {
-    // The caller's normalisers: 2^(s - lse log2 e), nothing to divide by.
-    const int qi = threadIdx.x, nq = P.ows * P.group;
-    const bool live = qi < nq;
-    const int g = live ? qi / P.ows : 0, r = live ? qi - g * P.ows : 0;
-    const int64_t row = (static_cast<int64_t>(u) * P.group + g) * P.ows + r;     // (pair, KV head, g) = (pair, query head)
-    fm = live && qi < P.nq_pad ? P.lse[row] * 1.44269504088896340736f : 0.0f;
-    fil = live ? 1.0f : 0.0f;
-  } else {
-    stream_fin(P, u, part_sh, fm, fil);
-  }
+  stream_fin(P, u, part_sh, fm, fil);
   if (threadIdx.x < P.nq_pad) {
     float* f = P.fin + (static_cast<int64_t>(u) * P.nq_pad + threadIdx.x) * 2;
     f[0] = fm;
@@ -1347,9 +1350,7 @@ xkv_status launch_window_mass(const xkv_cache* cache, int64_t streams, const voi
     mass_fn = nqs == 8 ? window_mass_stored<8> : window_mass_stored<16>;
   }
   if (lse_win != nullptr) {
-    // The rows' normalisers are given: no statistics pass, K is read once.
-    hipLaunchKernelGGL(window_merge, dim3(static_cast<unsigned>(streams)), dim3(kThreads), 0, stream, W);
-    if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
+    // The rows' normalisers are given: no statistics pass and no merge, K is read once.
     const int tok = profile_begin(2, stream);
     hipLaunchKernelGGL(mass_fn, dim3(grid), dim3(kThreads), 0, stream, W);
     profile_end(tok, stream);
