@@ -2,9 +2,10 @@
 """Benchmark of the XKV decode hot path on one MI355X.
 
 A *step* is one decode step of the whole path over every layer: append the new
-token, attention over the ragged cache with per-token scoring
-(xkv_decode_attend_score), then top-budget eviction and compaction
-(xkv_evict_compact).  The cache starts from the full prompt; the first warm-up
+token, attention over the ragged cache with per-token scoring, then top-budget
+eviction and compaction: xkv_decode_step, which is xkv_decode_attend_score
+followed by xkv_evict_compact as one call (--two-calls times the two calls
+instead).  The cache starts from the full prompt; the first warm-up
 step therefore evicts context+1 -> budget in every layer (`step0_ms`), the live
 tokens then move into an arena sized by the budgets (xkv_repack), and the timed
 steps run in the steady state budget+1 -> budget.
@@ -63,6 +64,8 @@ def parse():
                     help="0 library's choice, 1 streaming + finalize kernels, 2 fused cooperative launch")
     ap.add_argument("--no-graph", action="store_true", help="skip the graph-replay figure")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill-phase eviction leg")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="a step is xkv_decode_attend_score then xkv_evict_compact instead of xkv_decode_step")
     ap.add_argument("--no-settle", action="store_true", help="do not wait for the freed prompt arena to be cleared")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of 1 GiB x 10 (reference point for HBM byte counters)")
@@ -305,6 +308,7 @@ def warm_kernels(xkv, wl, w, torch, np, stream):
     for bud in (200, 10 ** 6):
         xkv.xkv_decode_attend_score(c, 0, 2, q, kn, kn, pn, o, ws, stream=stream)
         xkv.xkv_evict_compact(c, 0, 2, np.full((2, w.batch), bud, np.int32), ws, stream=stream)
+    xkv.xkv_decode_step(c, 0, 2, q, kn, kn, pn, o, c.len.reshape(2, w.batch).copy(), ws, stream=stream)   # one in, one out
     c2 = c.resized(lens + 8, stream=stream)
     torch.cuda.synchronize()
     del c, c2, ws
@@ -348,10 +352,15 @@ def run_workload(xkv, wl, w, args, K, W, R, full, pool=None):
         c = state["cache"]
         pos_step[:] = w.context + t
         alg_bytes[0] += algorithmic_bytes(w, c.len + 1)
-        xkv.xkv_decode_attend_score(c, 0, L, q[i], kn[i], vn[i], pos_step, out, state["ws"], stream=stream)
-        if (t + 1) % every == 0:
+        if (t + 1) % every != 0:
+            xkv.xkv_decode_attend_score(c, 0, L, q[i], kn[i], vn[i], pos_step, out, state["ws"], stream=stream)
+        elif args.two_calls:
+            xkv.xkv_decode_attend_score(c, 0, L, q[i], kn[i], vn[i], pos_step, out, state["ws"], stream=stream)
             xkv.xkv_evict_compact(c, 0, L, budgets, state["ws"], pool_size=pool_size, n_protect=n_protect,
                                   stream=stream)
+        else:
+            xkv.xkv_decode_step(c, 0, L, q[i], kn[i], vn[i], pos_step, out, budgets, state["ws"],
+                                pool_size=pool_size, n_protect=n_protect, stream=stream)
         state["t"] = t + 1
 
     def timed(n):
@@ -423,6 +432,7 @@ def run_workload(xkv, wl, w, args, K, W, R, full, pool=None):
         alg_bytes_step = alg_bytes[0] / K
         launches, total_ms = xkv.xkv_profile_read(0)
         sel_launches, sel_ms = xkv.xkv_profile_read(1)
+        se_launches, se_ms = xkv.xkv_profile_read(3)
         xkv.xkv_profile_enable(False)
         launches_per_step = launches / K
         bytes_per_launch = alg_bytes_step / launches_per_step
@@ -442,7 +452,8 @@ def run_workload(xkv, wl, w, args, K, W, R, full, pool=None):
                               " (K/V streaming kernel of xkv_decode_attend_score)",
                     "avg_launch_ms": total_ms / launches,
                     "launches_per_step": launches_per_step, "algorithmic_bytes_per_launch": bytes_per_launch,
-                    "evict_select_avg_ms": (sel_ms / sel_launches) if sel_launches else None}
+                    "evict_select_avg_ms": (sel_ms / sel_launches) if sel_launches else None,
+                    "score_and_evict_avg_ms": (se_ms / se_launches) if se_launches else None}
 
     res = {
         "workload": w.name, "ms_per_step": ms_per_step, "layer_steps_per_s": L / (ms_per_step * 1e-3),
@@ -487,9 +498,13 @@ def run_workload(xkv, wl, w, args, K, W, R, full, pool=None):
         pos_step[:] = w.context + state["t"]
         with torch.cuda.stream(side):
             with torch.cuda.graph(gr, stream=side):
-                xkv.xkv_decode_attend_score(cache, 0, L, q[i], kn[i], vn[i], pos_step, out, ws, stream=side)
-                xkv.xkv_evict_compact(cache, 0, L, budgets, ws, pool_size=pool_size, n_protect=n_protect,
-                                      stream=side)
+                if args.two_calls:
+                    xkv.xkv_decode_attend_score(cache, 0, L, q[i], kn[i], vn[i], pos_step, out, ws, stream=side)
+                    xkv.xkv_evict_compact(cache, 0, L, budgets, ws, pool_size=pool_size, n_protect=n_protect,
+                                          stream=side)
+                else:
+                    xkv.xkv_decode_step(cache, 0, L, q[i], kn[i], vn[i], pos_step, out, budgets, ws,
+                                        pool_size=pool_size, n_protect=n_protect, stream=side)
         torch.cuda.current_stream().wait_stream(side)
         gr.replay()
         torch.cuda.synchronize()
@@ -737,6 +752,7 @@ def main():
                    "arena": "prompt-sized" if args.keep_prompt_arena else "budget-sized after the first eviction",
                    "kv_arena_bytes": res["kv_arena_bytes"], "steady_state": res["steady_state"]},
         "timing": "median of `reps` repetitions of `steps` steps, each between HIP events on the launch stream",
+        "step_call": "xkv_decode_attend_score + xkv_evict_compact" if args.two_calls else "xkv_decode_step",
         "reps": res["reps"], "ms_per_step_reps": res["ms_per_step_reps"], "ms_per_step_spread": res["ms_per_step_spread"],
         "host_clock_ms_per_step": res["host_clock_ms_per_step"],
         "step0_ms": res["step0_ms"], "step0_host_clock_ms": res["step0_host_clock_ms"], "repack_ms": res["repack_ms"],

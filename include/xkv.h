@@ -273,6 +273,33 @@ xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, int32_t laye
                              void* hip_stream);
 
 /*
+ * One decode step of layers [layer_begin, layer_end): xkv_decode_attend_score
+ * followed by xkv_evict_compact with the same arguments, as one call (Sec. 4.1,
+ * generation phase: every new token is appended, attended to and scored, and the
+ * cache is cut back to its budget; Eq. 1-3, Alg. 2 steps 4-7).  The cache, out
+ * and kept_idx_out end up exactly as after the two calls (scores, kept indices
+ * and moved rows bit for bit; out up to the order of its fp32 sums).
+ *
+ * In the steady state of decoding (every stream of the call holds at most 16384
+ * tokens after the append and evicts at most 8 of them, pool_size 1, n_protect 0,
+ * at most 128 (layer, sequence) regions, and a query group the split-K kernels
+ * serve without the matrix cores) the eviction runs inside the kernel that updates
+ * the scores, on the scores it has just computed: one launch less and no second
+ * pass over the scores.  Any other call runs the two calls' kernels one after the
+ * other.
+ *
+ *   arguments   as for xkv_decode_attend_score and xkv_evict_compact; budgets apply
+ *               to the lengths after the append; workspace at least
+ *               xkv_workspace_bytes
+ * Errors: those of the two calls, all detected before anything is enqueued.
+ */
+xkv_status xkv_decode_step(xkv_cache* cache, int32_t layer_begin, int32_t layer_end, const void* q,
+                           const void* k_new, const void* v_new, const int32_t* pos_new,
+                           float softmax_scale, float* out, const int32_t* budgets, int32_t pool_size,
+                           int32_t n_protect, int32_t* kept_idx_out, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+
+/*
  * Moves the live tokens of layers [layer_begin, layer_end) of `src` into `dst`, a
  * cache of the same shape (layers, batch, heads, head_dim, dtype) with arenas and
  * stream capacities of its own: slot j < len of every stream (l, b, h) of src goes
@@ -467,8 +494,10 @@ xkv_status xkv_fused_status(int32_t* gave_up_out);
  * Per-kernel timing for benchmarks.  While enabled, the device calls above record
  * HIP events around their dominant kernel (the K/V streaming kernel of
  * xkv_decode_attend_score, kernel index 0, the selection kernel of
- * xkv_evict_compact, kernel index 1, and the first K pass of xkv_prefill_evict,
- * kernel index 2) on the stream they launch on.
+ * xkv_evict_compact, kernel index 1, the first K pass of xkv_prefill_evict,
+ * kernel index 2, and the kernel of xkv_decode_step that updates the scores and
+ * evicts, kernel index 3: it is recorded only when the step took that kernel) on
+ * the stream they launch on.
  * xkv_profile_read waits for those events, returns the number of launches and
  * their summed duration in milliseconds since the last xkv_profile_enable(1),
  * and keeps them until the next enable.  Off by default; not for use under

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     xkv_cache_importance,
     xkv_configure,
     xkv_decode_attend_score,
+    xkv_decode_step,
     xkv_decode_attend_score_noalloc,
     xkv_evict_compact,
     xkv_fused_status,

@@ -19,7 +19,7 @@ EXPORTS = (
     "xkv_configure", "xkv_probe_stream_read", "xkv_prefill_workspace_bytes", "xkv_prefill_evict",
     "xkv_window_importance", "xkv_allocate_device_workspace_bytes", "xkv_allocate_budgets_device",
     "xkv_average_allocations", "xkv_fused_status", "xkv_decode_attend_score_noalloc", "xkv_repack", "xkv_cache_importance",
-    "xkv_prefill_evict_lse", "xkv_window_importance_lse",
+    "xkv_prefill_evict_lse", "xkv_window_importance_lse", "xkv_decode_step",
 )
 XKV_NOALLOC_SCRATCH_BYTES = 32 << 20
 XKV_CFG_ATTEND_PATH = 1
@@ -79,6 +79,10 @@ def load():
                                          C.c_void_p]
     lib.xkv_repack.restype = C.c_int32
     lib.xkv_repack.argtypes = [C.POINTER(_CacheStruct), C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p]
+    lib.xkv_decode_step.restype = C.c_int32
+    lib.xkv_decode_step.argtypes = [
+        C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float,
+        C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.xkv_evict_compact.restype = C.c_int32
     lib.xkv_evict_compact.argtypes = [
         C.POINTER(_CacheStruct), C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
@@ -272,6 +276,20 @@ def xkv_decode_attend_score_noalloc(cache: XkvCache, layer_begin, layer_end, q, 
         C.byref(cache.struct), int(layer_begin), int(layer_end), _ptr(q), _ptr(k_new), _ptr(v_new),
         _ptr(pn), float(softmax_scale), _ptr(out), _stream_handle(stream))
     _check(st, "xkv_decode_attend_score_noalloc")
+
+
+def xkv_decode_step(cache: XkvCache, layer_begin, layer_end, q, k_new, v_new, pos_new, out, budgets, workspace,
+                    pool_size: int = 1, n_protect: int = 0, kept_idx_out=None, softmax_scale: float = 0.0,
+                    stream=None):
+    """xkv_decode_attend_score followed by xkv_evict_compact as one call."""
+    pn = None if pos_new is None else np.ascontiguousarray(pos_new, dtype=np.int32)
+    bud = None if budgets is None else np.ascontiguousarray(budgets, dtype=np.int32)
+    st = load().xkv_decode_step(
+        C.byref(cache.struct), int(layer_begin), int(layer_end), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(pn),
+        float(softmax_scale), _ptr(out), _ptr(bud), int(pool_size), int(n_protect), _ptr(kept_idx_out),
+        _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+        _stream_handle(stream))
+    _check(st, "xkv_decode_step")
 
 
 def xkv_repack(src: XkvCache, dst: XkvCache, layer_begin, layer_end, stream=None):

@@ -128,6 +128,14 @@ struct AttendTableParams : AttendCommon {
   const int32_t* fin0;           // first finalize workgroup of each region
 };
 
+// The finalize kernel that also evicts (xkv_decode_step): the attention geometry plus,
+// per region, the number of tokens to keep.
+struct StepParams : AttendParams {
+  int32_t keep[kMaxPairs];   // min(budget, n) of every region
+  int32_t* kept_idx;         // may be null
+  int32_t row_bytes;
+};
+
 // First finalize workgroup of region i: with the tables in the arguments the host
 // rewrites full0 between the two launches.
 __device__ __forceinline__ int fin_first(const AttendParams& P, int i) { return P.pairs[i].full0; }
@@ -1477,6 +1485,238 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
 }
 
 // ---------------------------------------------------------------------------
+// attend_finalize and the steady-state eviction in one kernel (xkv_decode_step):
+// one workgroup per stream.  It does what attend_finalize does
+// for the whole stream (statistics, score update, output) with the same
+// arithmetic in the same order, keeps the updated scores of its slots in
+// registers, finds the at most kStepEvict tokens to evict by repeated minimum
+// search over them (the smallest (score, -slot) first: equal scores go to the
+// higher slot, as in the selection kernel), and moves the kept tokens of the
+// slots at or beyond the budget into the holes.  The host takes this kernel only
+// when every stream of the call has at most kStepMaxRows slots and evicts at most
+// kStepEvict tokens, without pooling or protected tokens.
+// Three workgroup sizes, the smallest that holds the call's longest stream: the kernel is a chain of
+// dependent steps, and the more workgroups are resident at once the sooner the call is through.
+constexpr int kStepMaxRows = 16384;
+constexpr int kStepEvict = 8;
+struct StepShape { int threads, slots; };
+constexpr StepShape kStepShapes[3] = {{256, 20}, {512, 16}, {1024, 16}};
+
+template <int D, int G, bool kHalf, int kStepThreads, int kSlots>
+__global__ __launch_bounds__(kStepThreads) void attend_finalize_evict(const StepParams P) {
+  constexpr int GD = G * D;
+  constexpr int kStepWaves = kStepThreads / 64;
+  static_assert(kSlots % 2 == 0, "slot pairs");
+  extern __shared__ float w_sh[];           // [G][nstrips] strip weights 2^(m_s - m) / l
+  __shared__ float m_sh[G], inv_sh[G];
+  __shared__ float o_red[kStepThreads];
+  __shared__ unsigned long long best_sh[kStepWaves];
+  __shared__ int ev_sh[kStepEvict], hole_l[kStepEvict], mover_l[kStepEvict];
+  __shared__ int moves_sh;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int strip_rows = P.strip_rows;
+  const int64_t REC = kHalf ? half_record_floats(G, D, strip_rows) : record_floats(G, D, strip_rows);
+  const int lg_floats = kHalf ? strip_rows / 2 : strip_rows;
+  const int lo = blockIdx.x / P.n_kv_heads;
+  const int h = blockIdx.x - lo * P.n_kv_heads;
+  const PairDesc pd = P.pairs[lo];
+  const int n = pd.n;
+  const int kk = P.keep[lo];
+  const int pair = P.pair_base + lo;
+  float* out = P.out + (static_cast<int64_t>(pair) * P.n_kv_heads + h) * GD;
+  if (n == 0) {
+    for (int idx = tid; idx < GD; idx += kStepThreads) out[idx] = 0.0f;
+    return;
+  }
+  const int nstrips = (n + strip_rows - 1) / strip_rows;
+  const float* rec0 = P.ws + (static_cast<int64_t>(pd.strip0) + static_cast<int64_t>(h) * nstrips) * REC;
+  const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
+  float* score = P.score + stream_slot;
+  const int shift = __ffs(strip_rows) - 1;  // strip lengths are powers of two
+  // Slot of register e of this thread: with 16-bit records a thread takes pairs of
+  // neighbouring slots (one word of distances per head), else every 1024th slot.
+  auto slot_of = [&](int e) { return kHalf ? 2 * (tid + (e >> 1) * kStepThreads) + (e & 1) : tid + e * kStepThreads; };
+
+  // Distance words (16-bit records) and old scores, requested before the statistics.
+  unsigned wpre[kHalf ? kSlots / 2 : 1][G];
+  float sc[kSlots];
+#pragma unroll
+  for (int e = 0; e < kSlots; ++e) {
+    const int j = slot_of(e);
+    const int jc = j < n ? j : 0;
+    if (kHalf && (e & 1) == 0) {
+      const float* lg = rec0 + static_cast<int64_t>(jc >> shift) * REC + ((jc & (strip_rows - 1)) >> 1);
+#pragma unroll
+      for (int g = 0; g < G; ++g) wpre[e >> 1][g] = __float_as_uint(lg[g * lg_floats]);
+    }
+    sc[e] = (j >= n || (P.append && j == n - 1)) ? 0.0f : score[jc];            // the appended token starts from zero
+  }
+
+  // Stream statistics from the strip statistics, one wave per query head at a time.
+  for (int g = wave; g < G; g += kStepWaves) {
+    const float* ml = rec0 + G * (lg_floats + D) + 2 * g;
+    float m = -INFINITY;
+    for (int c = lane; c < nstrips; c += 64) m = fmaxf(m, ml[static_cast<int64_t>(c) * REC]);
+    m = wave_max(m);
+    float l = 0.0f;
+    for (int c = lane; c < nstrips; c += 64) {
+      const float wgt = fast_exp2(ml[static_cast<int64_t>(c) * REC] - m);
+      w_sh[g * nstrips + c] = wgt;
+      l = fmaf(wgt, ml[static_cast<int64_t>(c) * REC + 1], l);
+    }
+    l = wave_sum(l);
+    const float inv = 1.0f / l;
+    for (int c = lane; c < nstrips; c += 64) w_sh[g * nstrips + c] *= inv;
+    if (lane == 0) { m_sh[g] = m; inv_sh[g] = inv; }
+  }
+  if (P.append && tid == 0) P.pos[stream_slot + n - 1] = P.pos_new[lo];
+  __syncthreads();
+
+  // score_j += sum_g p_gj, kept in registers and written back.
+  if constexpr (kHalf) {
+#pragma unroll
+    for (int it = 0; it < kSlots / 2; ++it) {
+      const int j = slot_of(2 * it);
+      if (j < n) {
+        const int c = j >> shift;
+        float add0 = 0.0f, add1 = 0.0f;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          const unsigned word = wpre[it][g];
+          const float wgt = w_sh[g * nstrips + c];
+          add0 = fmaf(fast_exp2(static_cast<float>(word & 0xffffu) * (-1.0f / kLogitFixScale)), wgt, add0);
+          add1 = fmaf(fast_exp2(static_cast<float>(word >> 16) * (-1.0f / kLogitFixScale)), wgt, add1);
+        }
+        sc[2 * it] += add0;
+        score[j] = sc[2 * it];
+        if (j + 1 < n) {
+          sc[2 * it + 1] += add1;
+          score[j + 1] = sc[2 * it + 1];
+        }
+      }
+    }
+  } else {
+    float m_g[G], inv_g[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) { m_g[g] = m_sh[g]; inv_g[g] = inv_sh[g]; }
+#pragma unroll
+    for (int e = 0; e < kSlots; ++e) {
+      const int j = slot_of(e);
+      if (j < n) {
+        const float* lg = rec0 + static_cast<int64_t>(j >> shift) * REC + (j & (strip_rows - 1));
+        float add = 0.0f;
+#pragma unroll
+        for (int g = 0; g < G; ++g) add = fmaf(fast_exp2(lg[g * strip_rows] - m_g[g]), inv_g[g], add);
+        sc[e] += add;
+        score[j] = sc[e];
+      }
+    }
+  }
+
+  // ---- eviction: the E = n - kk smallest (score, -slot), one per round ----------------
+  int32_t* kept = P.kept_idx ? P.kept_idx + stream_slot : nullptr;
+  const int E = (kk >= n || kk == 0) ? 0 : n - kk;        // nothing to select when all or none stay
+  unsigned long long last = 0;              // every pack is > 0: ~slot has its top bit set
+  for (int r = 0; r < E; ++r) {
+    unsigned long long best = ~0ull;
+#pragma unroll
+    for (int e = 0; e < kSlots; ++e) {
+      const int j = slot_of(e);
+      const unsigned long long pk =
+          (static_cast<unsigned long long>(__float_as_uint(sc[e])) << 32) | (0xffffffffu - static_cast<unsigned>(j));
+      if (j < n && pk > last && pk < best) best = pk;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      const unsigned long long o = __shfl_xor(best, off);
+      best = o < best ? o : best;
+    }
+    if (lane == 0) best_sh[wave] = best;
+    __syncthreads();
+    best = best_sh[0];
+#pragma unroll
+    for (int w = 1; w < kStepWaves; ++w) best = best_sh[w] < best ? best_sh[w] : best;
+    last = best;
+    if (tid == 0) ev_sh[r] = static_cast<int>(0xffffffffu - static_cast<unsigned>(best & 0xffffffffull));
+    __syncthreads();
+  }
+  if (tid == 0) {
+    // holes: evicted slots below kk, ascending; movers: the survivors among the slots [kk, n), ascending.
+    for (int a = 1; a < E; ++a) {
+      const int x = ev_sh[a];
+      int b = a - 1;
+      while (b >= 0 && ev_sh[b] > x) { ev_sh[b + 1] = ev_sh[b]; --b; }
+      ev_sh[b + 1] = x;
+    }
+    int nh = 0, nm = 0;
+    for (int a = 0; a < E; ++a)
+      if (ev_sh[a] < kk) hole_l[nh++] = ev_sh[a];
+    for (int s = kk; s < n && E > 0; ++s) {
+      bool evicted = false;
+      for (int a = 0; a < E; ++a) evicted = evicted || ev_sh[a] == s;
+      if (!evicted) mover_l[nm++] = s;
+    }
+    moves_sh = nh;
+  }
+  __syncthreads();                          // also: the new scores and the appended pos are visible to the movers
+  const int moves = moves_sh;
+  if (kept != nullptr)
+    for (int j = tid; j < kk; j += kStepThreads) {
+      bool is_hole = false;
+      for (int a = 0; a < moves; ++a) is_hole = is_hole || hole_l[a] == j;
+      if (!is_hole) kept[j] = j;
+    }
+  for (int i = wave; i < moves; i += kStepWaves) {
+    const int dst = hole_l[i], src = mover_l[i];
+    const int frags = P.row_bytes >> 4;     // 16-byte pieces per row: 8, 16 or 32
+    if (lane < frags) {
+      char* kb = static_cast<char*>(P.k) + stream_slot * P.row_bytes;
+      char* vb = static_cast<char*>(P.v) + stream_slot * P.row_bytes;
+      const int64_t so = static_cast<int64_t>(src) * P.row_bytes + lane * 16;
+      const int64_t dof = static_cast<int64_t>(dst) * P.row_bytes + lane * 16;
+      const uint4 a = *reinterpret_cast<const uint4*>(kb + so);
+      const uint4 b = *reinterpret_cast<const uint4*>(vb + so);
+      *reinterpret_cast<uint4*>(kb + dof) = a;
+      *reinterpret_cast<uint4*>(vb + dof) = b;
+    } else if (lane == 32) {
+      P.score[stream_slot + dst] = P.score[stream_slot + src];
+    } else if (lane == 33) {
+      P.pos[stream_slot + dst] = P.pos[stream_slot + src];
+    } else if (lane == 34 && kept != nullptr) {
+      kept[dst] = src;
+    }
+  }
+
+  // out = sum_s w_s o_s: threads form (channel, slice) pairs; a slice sums every
+  // S-th strip, then the slices are added in order.
+  for (int tb = 0; tb < GD; tb += kStepThreads) {
+    const int tn = min(kStepThreads, GD - tb);
+    const int S = kStepThreads / tn;
+    const int ch_l = tid % tn, slice = tid / tn;
+    float o = 0.0f;
+    if (slice < S) {
+      const int idx = tb + ch_l;
+      const int g = idx / D;
+      const float* col = rec0 + G * lg_floats + idx;
+#pragma unroll 4
+      for (int c = slice; c < nstrips; c += S)
+        o = fmaf(w_sh[g * nstrips + c], col[static_cast<int64_t>(c) * REC], o);
+    }
+    __syncthreads();
+    o_red[tid] = o;
+    __syncthreads();
+    if (tid < tn) {
+      float tot = o_red[tid];
+      for (int sl = 1; sl < S; ++sl) tot += o_red[sl * tn + tid];
+      out[tb + tid] = tot;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Writes one chunk of the geometry tables of a large call into device memory: the
 // entries travel in the kernel arguments, so no host-to-device copy is involved
 // and the call stays capturable in a graph.  (Kernel arguments of this size, 36 KB,
@@ -1510,6 +1750,8 @@ struct Kernels {
   TableKernelFn finalize_tab = nullptr;
   KernelFn merge = nullptr;                // matrix-core path: attend_gqa_merge, then `finalize` = attend_gqa_scores
   TableKernelFn merge_tab = nullptr;
+  void (*finalize_evict[3])(const StepParams) = {nullptr, nullptr, nullptr};   // attend_finalize plus the steady-state
+                                                                               // eviction, one per kStepShapes entry
   int max_strip_rows = kChunk;  // longest strip the streaming kernel is given (a power of two)
   bool lds_logits = false;      // the streaming kernel collects the strip's logits in dynamic LDS
   bool half_records = false;    // attend_strip over bf16: records with 16-bit distances
@@ -1525,6 +1767,9 @@ bool pick_group(int group, Kernels* k) {
       k->finalize_tab = attend_finalize<D, 1, std::is_same<T, BF16>::value, AttendTableParams>;
       k->max_strip_rows = kMaxStripRows; k->lds_logits = true;
       k->fused = attend_fused<T, D, 1, 8>;
+      k->finalize_evict[0] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 256, 20>;
+      k->finalize_evict[1] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 512, 16>;
+      k->finalize_evict[2] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 1024, 16>;
       return true;
     case 2:
       k->half_records = std::is_same<T, BF16>::value;
@@ -1533,13 +1778,20 @@ bool pick_group(int group, Kernels* k) {
       k->finalize_tab = attend_finalize<D, 2, std::is_same<T, BF16>::value, AttendTableParams>;
       k->max_strip_rows = kMaxStripRows; k->lds_logits = true;
       k->fused = attend_fused<T, D, 2, 8>;
+      k->finalize_evict[0] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 256, 20>;
+      k->finalize_evict[1] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 512, 16>;
+      k->finalize_evict[2] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 1024, 16>;
       return true;
     case 4:
       k->stream = attend_chunk<T, D, 4>; k->finalize = attend_finalize<D, 4>;
       k->stream_tab = attend_chunk<T, D, 4, AttendTableParams>;
       k->finalize_tab = attend_finalize<D, 4, false, AttendTableParams>;
       k->fused = attend_fused<T, D, 4, 4>;
+      k->finalize_evict[0] = attend_finalize_evict<D, 4, false, 256, 20>;
+      k->finalize_evict[1] = attend_finalize_evict<D, 4, false, 512, 16>;
+      k->finalize_evict[2] = attend_finalize_evict<D, 4, false, 1024, 16>;
       if constexpr (std::is_same<T, BF16>::value && D == 128) {
+        k->finalize_evict[0] = k->finalize_evict[1] = k->finalize_evict[2] = nullptr;
         k->stream = attend_gqa<4>; k->merge = attend_gqa_merge<4>; k->finalize = attend_gqa_scores<4>;
         k->stream_tab = attend_gqa<4, AttendTableParams>;
         k->merge_tab = attend_gqa_merge<4, AttendTableParams>;
@@ -1552,7 +1804,11 @@ bool pick_group(int group, Kernels* k) {
       k->stream_tab = attend_chunk<T, D, 8, AttendTableParams>;
       k->finalize_tab = attend_finalize<D, 8, false, AttendTableParams>;
       k->fused = attend_fused<T, D, 8, 2>;
+      k->finalize_evict[0] = attend_finalize_evict<D, 8, false, 256, 20>;
+      k->finalize_evict[1] = attend_finalize_evict<D, 8, false, 512, 16>;
+      k->finalize_evict[2] = attend_finalize_evict<D, 8, false, 1024, 16>;
       if constexpr (std::is_same<T, BF16>::value && D == 128) {
+        k->finalize_evict[0] = k->finalize_evict[1] = k->finalize_evict[2] = nullptr;
         k->stream = attend_gqa<8>; k->merge = attend_gqa_merge<8>; k->finalize = attend_gqa_scores<8>;
         k->stream_tab = attend_gqa<8, AttendTableParams>;
         k->merge_tab = attend_gqa_merge<8, AttendTableParams>;
@@ -1791,13 +2047,21 @@ extern "C" xkv_status xkv_fused_status(int32_t* gave_up_out) {
   return XKV_OK;
 }
 
-// The call behind both entry points.  allow_fused: whether the cooperative launch
+// An eviction that may ride on the finalize kernel (xkv_decode_step): the budgets of the call's regions and
+// where the kept indices go; `done` says afterwards whether it did.
+struct StepEvict {
+  const int32_t* budgets;
+  int32_t* kept_idx;
+  bool done;
+};
+
+// The call behind the entry points.  allow_fused: whether the cooperative launch
 // may be chosen (it needs occupancy queries; the entry point that must not
 // allocate keeps to the two kernels).
 static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t layer_end, const void* q,
                                 const void* k_new, const void* v_new, const int32_t* pos_new,
                                 float softmax_scale, float* out, void* workspace, size_t workspace_bytes,
-                                void* hip_stream, bool allow_fused) {
+                                void* hip_stream, bool allow_fused, StepEvict* ev = nullptr) {
   using namespace xkv;
   xkv_status st = check_cache(cache);
   if (st != XKV_OK) return st;
@@ -1873,6 +2137,17 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
   while (fin_strips > 1 && total_strips / fin_strips < 1024) fin_strips >>= 1;
   if (fin_lds > 48 * 1024) return XKV_ERR_UNSUPPORTED;
   const size_t stream_lds = kern.lds_logits ? static_cast<size_t>(G) * strip_rows * sizeof(float) : 0;
+
+  // The eviction rides on the finalize kernel when that kernel exists for this geometry, the call is one
+  // launch group, and every stream is short enough and evicts few enough tokens for one workgroup.
+  bool fuse_evict = ev != nullptr && kern.finalize_evict[0] != nullptr && !gqa && n_pairs <= kMaxPairs;
+  for (int64_t i = 0; fuse_evict && i < n_pairs; ++i) {
+    const int64_t n = static_cast<int64_t>(cache->len[first + i]) + (append ? 1 : 0);
+    const int64_t kk = std::min<int64_t>(ev->budgets[i], n);
+    fuse_evict = n <= kStepMaxRows && (kk == 0 || n - kk <= kStepEvict);
+  }
+  int step_shape = 2;
+  while (step_shape > 0 && max_n <= kStepShapes[step_shape - 1].threads * kStepShapes[step_shape - 1].slots) --step_shape;
 
   P.strip_rows = strip_rows;
   P.rec_floats = static_cast<int32_t>(rec);
@@ -2011,7 +2286,18 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
       fin_blocks += (gqa ? std::max<int64_t>(ceil_div(pd.n, kGqaScoreRows), 1)
                          : ceil_div(std::max<int64_t>(ceil_div(pd.n, strip_rows), 1), fin_strips)) * hkv;
     }
-    if (gqa) {
+    if (fuse_evict) {
+      StepParams S;
+      static_cast<AttendParams&>(S) = P;
+      for (int i = 0; i < np; ++i)
+        S.keep[i] = static_cast<int32_t>(std::min<int64_t>(ev->budgets[g0 + i], P.pairs[i].n));
+      S.kept_idx = ev->kept_idx;
+      S.row_bytes = D * (cache->dtype == XKV_F32 ? 4 : 2);
+      const int tok = profile_begin(3, stream);
+      hipLaunchKernelGGL(kern.finalize_evict[step_shape], dim3(static_cast<unsigned>(np * hkv)),
+                         dim3(kStepShapes[step_shape].threads), fin_lds, stream, S);
+      profile_end(tok, stream);
+    } else if (gqa) {
       hipLaunchKernelGGL(kern.merge, dim3(static_cast<unsigned>(np * hkv)), dim3(kThreads), fin_lds, stream, P);
       hipLaunchKernelGGL(kern.finalize, dim3(static_cast<unsigned>(fin_blocks)), dim3(kThreads), 0, stream, P);
     } else {
@@ -2023,7 +2309,35 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
   }
   if (append)
     for (int64_t i = 0; i < n_pairs; ++i) cache->len[first + i] += 1;
+  if (fuse_evict) {
+    for (int64_t i = 0; i < n_pairs; ++i)
+      cache->len[first + i] = static_cast<int32_t>(std::min<int64_t>(ev->budgets[i], cache->len[first + i]));
+    ev->done = true;
+  }
   return XKV_OK;
+}
+
+extern "C" xkv_status xkv_decode_step(xkv_cache* cache, int32_t layer_begin, int32_t layer_end, const void* q,
+                                      const void* k_new, const void* v_new, const int32_t* pos_new,
+                                      float softmax_scale, float* out, const int32_t* budgets, int32_t pool_size,
+                                      int32_t n_protect, int32_t* kept_idx_out, void* workspace,
+                                      size_t workspace_bytes, void* hip_stream) {
+  using namespace xkv;
+  // Everything xkv_evict_compact would refuse is refused here, before the attention is enqueued.
+  xkv_status st = check_cache(cache);
+  if (st != XKV_OK) return st;
+  st = check_layers(cache, layer_begin, layer_end);
+  if (st != XKV_OK) return st;
+  st = evict_check_args(cache, layer_begin, layer_end, budgets, pool_size, n_protect, k_new != nullptr ? 1 : 0,
+                        workspace, workspace_bytes);
+  if (st != XKV_OK) return st;
+  StepEvict ev{budgets, kept_idx_out, false};
+  const bool plain_keys = pool_size == 1 && n_protect == 0;
+  st = decode_attend(cache, layer_begin, layer_end, q, k_new, v_new, pos_new, softmax_scale, out, workspace,
+                     workspace_bytes, hip_stream, true, plain_keys ? &ev : nullptr);
+  if (st != XKV_OK || ev.done) return st;
+  return xkv_evict_compact(cache, layer_begin, layer_end, budgets, pool_size, n_protect, kept_idx_out, workspace,
+                           workspace_bytes, hip_stream);
 }
 
 extern "C" xkv_status xkv_decode_attend_score(xkv_cache* cache, int32_t layer_begin,

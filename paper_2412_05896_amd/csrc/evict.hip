@@ -344,6 +344,30 @@ __global__ __launch_bounds__(kMoveThreads) void evict_move(const PT P) {
 }
 
 }  // namespace
+
+xkv_status evict_check_args(const xkv_cache* cache, int32_t layer_begin, int32_t layer_end, const int32_t* budgets,
+                            int32_t pool_size, int32_t n_protect, int32_t extra_rows, const void* workspace,
+                            size_t workspace_bytes) {
+  if (budgets == nullptr) return XKV_ERR_INVALID_ARG;
+  if (pool_size < 1 || (pool_size & 1) == 0 || n_protect < 0) return XKV_ERR_INVALID_ARG;
+  const int B = cache->batch, hkv = cache->n_kv_heads;
+  const int64_t first = static_cast<int64_t>(layer_begin) * B;
+  const int64_t n_pairs = static_cast<int64_t>(layer_end - layer_begin) * B;
+  int64_t words = 0;
+  for (int64_t i = 0; i < n_pairs; ++i) {
+    if (budgets[i] < 0 || budgets[i] < n_protect) return XKV_ERR_INVALID_ARG;
+    words += ceil_div(static_cast<int64_t>(cache->len[first + i]) + extra_rows, kWsAlign) * kWsAlign * hkv;
+  }
+  if (words > std::numeric_limits<int32_t>::max()) return XKV_ERR_UNSUPPORTED;
+  const int64_t units = n_pairs * hkv;
+  const uint64_t table_off = (static_cast<uint64_t>(words) * 12 + static_cast<uint64_t>(units) * 4 + 255) / 256 * 256;
+  const uint64_t need_bytes = n_pairs > kMaxPairs ? table_off + static_cast<uint64_t>(n_pairs) * sizeof(EvictPair)
+                                                  : static_cast<uint64_t>(words) * 12 + static_cast<uint64_t>(units) * 4;
+  if (workspace == nullptr || need_bytes > workspace_bytes) return XKV_ERR_CAPACITY;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return XKV_ERR_INVALID_ARG;
+  return XKV_OK;
+}
+
 }  // namespace xkv
 
 extern "C" xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, int32_t layer_end,

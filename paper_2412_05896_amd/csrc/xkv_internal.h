@@ -27,6 +27,12 @@ xkv_status check_layers(const xkv_cache* c, int32_t layer_begin, int32_t layer_e
 size_t attend_workspace_bytes(const xkv_cache* c, int32_t layers);
 size_t evict_workspace_bytes(const xkv_cache* c, int32_t layers);
 
+// What xkv_evict_compact checks of its arguments before it enqueues anything, for a
+// cache whose regions will hold extra_rows more tokens each by then.
+xkv_status evict_check_args(const xkv_cache* cache, int32_t layer_begin, int32_t layer_end, const int32_t* budgets,
+                            int32_t pool_size, int32_t n_protect, int32_t extra_rows, const void* workspace,
+                            size_t workspace_bytes);
+
 // Remembers the control words of the most recent launch that waits inside a kernel
 // (word 1: some workgroup gave up its wait), for xkv_fused_status; null: the most
 // recent call had no such launch.
