@@ -1486,27 +1486,29 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
 
 // ---------------------------------------------------------------------------
 // attend_finalize and the steady-state eviction in one kernel (xkv_decode_step):
-// one workgroup per stream.  It does what attend_finalize does
-// for the whole stream (statistics, score update, output) with the same
-// arithmetic in the same order, keeps the updated scores of its slots in
-// registers, finds the at most kStepEvict tokens to evict by repeated minimum
-// search over them (the smallest (score, -slot) first: equal scores go to the
-// higher slot, as in the selection kernel), and moves the kept tokens of the
-// slots at or beyond the budget into the holes.  The host takes this kernel only
-// when every stream of the call has at most kStepMaxRows slots and evicts at most
-// kStepEvict tokens, without pooling or protected tokens.
-// Three workgroup sizes, the smallest that holds the call's longest stream: the kernel is a chain of
-// dependent steps, and the more workgroups are resident at once the sooner the call is through.
-constexpr int kStepMaxRows = 16384;
+// one workgroup per stream.  It does what attend_finalize does for the whole
+// stream (statistics, score update, output) with the same arithmetic in the same
+// order, and while it writes the updated scores it keeps track of the smallest
+// (score, -slot) it has seen: that is the first token to evict (equal scores go
+// to the higher slot, as in the selection kernel), found without a second pass.
+// Further evictions (at most kStepEvict per stream) each take one more pass over
+// the scores just written, which the L2 still holds.  Then the kept tokens of
+// the slots at or beyond the budget move into the holes.  The host takes this
+// kernel only when every stream of the call evicts at most kStepEvict tokens,
+// without pooling or protected tokens.
+//
+// Three workgroup sizes: 256 threads when the call has enough streams to fill the
+// chip with such workgroups (the kernel is a chain of dependent steps, and the
+// more streams are resident at once the sooner the call is through) or its
+// streams are short, 512 when such a call has streams beyond 8192 slots (a
+// workgroup's time grows with its stream), 1024 for calls of few long streams.
 constexpr int kStepEvict = 8;
-struct StepShape { int threads, slots; };
-constexpr StepShape kStepShapes[3] = {{256, 20}, {512, 16}, {1024, 16}};
 
-template <int D, int G, bool kHalf, int kStepThreads, int kSlots>
+template <int D, int G, bool kHalf, int kStepThreads>
 __global__ __launch_bounds__(kStepThreads) void attend_finalize_evict(const StepParams P) {
   constexpr int GD = G * D;
   constexpr int kStepWaves = kStepThreads / 64;
-  static_assert(kSlots % 2 == 0, "slot pairs");
+  constexpr int kBatch = 8;                 // slot pairs (16-bit records) or slots per thread in flight
   extern __shared__ float w_sh[];           // [G][nstrips] strip weights 2^(m_s - m) / l
   __shared__ float m_sh[G], inv_sh[G];
   __shared__ float o_red[kStepThreads];
@@ -1536,24 +1538,28 @@ __global__ __launch_bounds__(kStepThreads) void attend_finalize_evict(const Step
   const int64_t stream_slot = pd.slot0 + static_cast<int64_t>(h) * pd.cap;
   float* score = P.score + stream_slot;
   const int shift = __ffs(strip_rows) - 1;  // strip lengths are powers of two
-  // Slot of register e of this thread: with 16-bit records a thread takes pairs of
-  // neighbouring slots (one word of distances per head), else every 1024th slot.
-  auto slot_of = [&](int e) { return kHalf ? 2 * (tid + (e >> 1) * kStepThreads) + (e & 1) : tid + e * kStepThreads; };
-
-  // Distance words (16-bit records) and old scores, requested before the statistics.
-  unsigned wpre[kHalf ? kSlots / 2 : 1][G];
-  float sc[kSlots];
+  constexpr int kStride = kHalf ? 2 : 1;    // slots per thread and turn
+  // Turn `it` of the pass: this thread's first slot, and what it needs of it (the distance word
+  // of a slot pair, or nothing yet for fp32 logits) and the old scores.
+  auto first_slot = [&](int it) { return kStride * (tid + it * kStepThreads); };
+  const int turns = (n + kStride * kStepThreads - 1) / (kStride * kStepThreads);
+  unsigned wv[kBatch][G];
+  float old0[kBatch], old1[kBatch];
+  auto request = [&](int it0) {
 #pragma unroll
-  for (int e = 0; e < kSlots; ++e) {
-    const int j = slot_of(e);
-    const int jc = j < n ? j : 0;
-    if (kHalf && (e & 1) == 0) {
-      const float* lg = rec0 + static_cast<int64_t>(jc >> shift) * REC + ((jc & (strip_rows - 1)) >> 1);
+    for (int u = 0; u < kBatch; ++u) {
+      const int j = first_slot(it0 + u);
+      const int jc = j < n ? j : 0;                          // past the end: slot 0 again, not used
+      if constexpr (kHalf) {
+        const float* lg = rec0 + static_cast<int64_t>(jc >> shift) * REC + ((jc & (strip_rows - 1)) >> 1);
 #pragma unroll
-      for (int g = 0; g < G; ++g) wpre[e >> 1][g] = __float_as_uint(lg[g * lg_floats]);
+        for (int g = 0; g < G; ++g) wv[u][g] = __float_as_uint(lg[g * lg_floats]);
+        old1[u] = (jc + 1 >= n || (P.append && jc + 1 == n - 1)) ? 0.0f : score[jc + 1];
+      }
+      old0[u] = (P.append && jc == n - 1) ? 0.0f : score[jc];          // the appended token starts from zero
     }
-    sc[e] = (j >= n || (P.append && j == n - 1)) ? 0.0f : score[jc];            // the appended token starts from zero
-  }
+  };
+  request(0);                               // in flight while the statistics below take their own round trip
 
   // Stream statistics from the strip statistics, one wave per query head at a time.
   for (int g = wave; g < G; g += kStepWaves) {
@@ -1575,43 +1581,49 @@ __global__ __launch_bounds__(kStepThreads) void attend_finalize_evict(const Step
   if (P.append && tid == 0) P.pos[stream_slot + n - 1] = P.pos_new[lo];
   __syncthreads();
 
-  // score_j += sum_g p_gj, kept in registers and written back.
-  if constexpr (kHalf) {
+  // score_j += sum_g p_gj; the smallest (score, -slot) of this thread's slots on the way.
+  unsigned long long mine = ~0ull;
+  auto see = [&](float sc, int j) {
+    const unsigned long long pk =
+        (static_cast<unsigned long long>(__float_as_uint(sc)) << 32) | (0xffffffffu - static_cast<unsigned>(j));
+    mine = pk < mine ? pk : mine;
+  };
+  float m_g[G], inv_g[G];
 #pragma unroll
-    for (int it = 0; it < kSlots / 2; ++it) {
-      const int j = slot_of(2 * it);
+  for (int g = 0; g < G; ++g) { m_g[g] = m_sh[g]; inv_g[g] = inv_sh[g]; }
+  for (int it0 = 0; it0 < turns; it0 += kBatch) {
+    if (it0 > 0) request(it0);
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int j = first_slot(it0 + u);
       if (j < n) {
-        const int c = j >> shift;
-        float add0 = 0.0f, add1 = 0.0f;
+        if constexpr (kHalf) {
+          const int c = j >> shift;
+          float add0 = 0.0f, add1 = 0.0f;
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-          const unsigned word = wpre[it][g];
-          const float wgt = w_sh[g * nstrips + c];
-          add0 = fmaf(fast_exp2(static_cast<float>(word & 0xffffu) * (-1.0f / kLogitFixScale)), wgt, add0);
-          add1 = fmaf(fast_exp2(static_cast<float>(word >> 16) * (-1.0f / kLogitFixScale)), wgt, add1);
+          for (int g = 0; g < G; ++g) {
+            const unsigned word = wv[u][g];
+            const float wgt = w_sh[g * nstrips + c];
+            add0 = fmaf(fast_exp2(static_cast<float>(word & 0xffffu) * (-1.0f / kLogitFixScale)), wgt, add0);
+            add1 = fmaf(fast_exp2(static_cast<float>(word >> 16) * (-1.0f / kLogitFixScale)), wgt, add1);
+          }
+          const float s0 = old0[u] + add0;
+          score[j] = s0;
+          see(s0, j);
+          if (j + 1 < n) {
+            const float s1 = old1[u] + add1;
+            score[j + 1] = s1;
+            see(s1, j + 1);
+          }
+        } else {
+          const float* lg = rec0 + static_cast<int64_t>(j >> shift) * REC + (j & (strip_rows - 1));
+          float add = 0.0f;
+#pragma unroll
+          for (int g = 0; g < G; ++g) add = fmaf(fast_exp2(lg[g * strip_rows] - m_g[g]), inv_g[g], add);
+          const float s0 = old0[u] + add;
+          score[j] = s0;
+          see(s0, j);
         }
-        sc[2 * it] += add0;
-        score[j] = sc[2 * it];
-        if (j + 1 < n) {
-          sc[2 * it + 1] += add1;
-          score[j + 1] = sc[2 * it + 1];
-        }
-      }
-    }
-  } else {
-    float m_g[G], inv_g[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) { m_g[g] = m_sh[g]; inv_g[g] = inv_sh[g]; }
-#pragma unroll
-    for (int e = 0; e < kSlots; ++e) {
-      const int j = slot_of(e);
-      if (j < n) {
-        const float* lg = rec0 + static_cast<int64_t>(j >> shift) * REC + (j & (strip_rows - 1));
-        float add = 0.0f;
-#pragma unroll
-        for (int g = 0; g < G; ++g) add = fmaf(fast_exp2(lg[g * strip_rows] - m_g[g]), inv_g[g], add);
-        sc[e] += add;
-        score[j] = sc[e];
       }
     }
   }
@@ -1621,13 +1633,16 @@ __global__ __launch_bounds__(kStepThreads) void attend_finalize_evict(const Step
   const int E = (kk >= n || kk == 0) ? 0 : n - kk;        // nothing to select when all or none stay
   unsigned long long last = 0;              // every pack is > 0: ~slot has its top bit set
   for (int r = 0; r < E; ++r) {
-    unsigned long long best = ~0ull;
-#pragma unroll
-    for (int e = 0; e < kSlots; ++e) {
-      const int j = slot_of(e);
-      const unsigned long long pk =
-          (static_cast<unsigned long long>(__float_as_uint(sc[e])) << 32) | (0xffffffffu - static_cast<unsigned>(j));
-      if (j < n && pk > last && pk < best) best = pk;
+    unsigned long long best = mine;         // round 0: from the pass above
+    if (r > 0) {
+      __syncthreads();                      // the scores written above are visible to the whole workgroup
+      best = ~0ull;
+#pragma unroll 4
+      for (int j = tid; j < n; j += kStepThreads) {
+        const unsigned long long pk =
+            (static_cast<unsigned long long>(__float_as_uint(score[j])) << 32) | (0xffffffffu - static_cast<unsigned>(j));
+        if (pk > last && pk < best) best = pk;
+      }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
@@ -1751,7 +1766,7 @@ struct Kernels {
   KernelFn merge = nullptr;                // matrix-core path: attend_gqa_merge, then `finalize` = attend_gqa_scores
   TableKernelFn merge_tab = nullptr;
   void (*finalize_evict[3])(const StepParams) = {nullptr, nullptr, nullptr};   // attend_finalize plus the steady-state
-                                                                               // eviction, one per kStepShapes entry
+                                                                               // eviction: 256, 512 and 1024 threads
   int max_strip_rows = kChunk;  // longest strip the streaming kernel is given (a power of two)
   bool lds_logits = false;      // the streaming kernel collects the strip's logits in dynamic LDS
   bool half_records = false;    // attend_strip over bf16: records with 16-bit distances
@@ -1767,9 +1782,9 @@ bool pick_group(int group, Kernels* k) {
       k->finalize_tab = attend_finalize<D, 1, std::is_same<T, BF16>::value, AttendTableParams>;
       k->max_strip_rows = kMaxStripRows; k->lds_logits = true;
       k->fused = attend_fused<T, D, 1, 8>;
-      k->finalize_evict[0] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 256, 20>;
-      k->finalize_evict[1] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 512, 16>;
-      k->finalize_evict[2] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 1024, 16>;
+      k->finalize_evict[0] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 256>;
+      k->finalize_evict[1] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 512>;
+      k->finalize_evict[2] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 1024>;
       return true;
     case 2:
       k->half_records = std::is_same<T, BF16>::value;
@@ -1778,18 +1793,18 @@ bool pick_group(int group, Kernels* k) {
       k->finalize_tab = attend_finalize<D, 2, std::is_same<T, BF16>::value, AttendTableParams>;
       k->max_strip_rows = kMaxStripRows; k->lds_logits = true;
       k->fused = attend_fused<T, D, 2, 8>;
-      k->finalize_evict[0] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 256, 20>;
-      k->finalize_evict[1] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 512, 16>;
-      k->finalize_evict[2] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 1024, 16>;
+      k->finalize_evict[0] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 256>;
+      k->finalize_evict[1] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 512>;
+      k->finalize_evict[2] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 1024>;
       return true;
     case 4:
       k->stream = attend_chunk<T, D, 4>; k->finalize = attend_finalize<D, 4>;
       k->stream_tab = attend_chunk<T, D, 4, AttendTableParams>;
       k->finalize_tab = attend_finalize<D, 4, false, AttendTableParams>;
       k->fused = attend_fused<T, D, 4, 4>;
-      k->finalize_evict[0] = attend_finalize_evict<D, 4, false, 256, 20>;
-      k->finalize_evict[1] = attend_finalize_evict<D, 4, false, 512, 16>;
-      k->finalize_evict[2] = attend_finalize_evict<D, 4, false, 1024, 16>;
+      k->finalize_evict[0] = attend_finalize_evict<D, 4, false, 256>;
+      k->finalize_evict[1] = attend_finalize_evict<D, 4, false, 512>;
+      k->finalize_evict[2] = attend_finalize_evict<D, 4, false, 1024>;
       if constexpr (std::is_same<T, BF16>::value && D == 128) {
         k->finalize_evict[0] = k->finalize_evict[1] = k->finalize_evict[2] = nullptr;
         k->stream = attend_gqa<4>; k->merge = attend_gqa_merge<4>; k->finalize = attend_gqa_scores<4>;
@@ -1804,9 +1819,9 @@ bool pick_group(int group, Kernels* k) {
       k->stream_tab = attend_chunk<T, D, 8, AttendTableParams>;
       k->finalize_tab = attend_finalize<D, 8, false, AttendTableParams>;
       k->fused = attend_fused<T, D, 8, 2>;
-      k->finalize_evict[0] = attend_finalize_evict<D, 8, false, 256, 20>;
-      k->finalize_evict[1] = attend_finalize_evict<D, 8, false, 512, 16>;
-      k->finalize_evict[2] = attend_finalize_evict<D, 8, false, 1024, 16>;
+      k->finalize_evict[0] = attend_finalize_evict<D, 8, false, 256>;
+      k->finalize_evict[1] = attend_finalize_evict<D, 8, false, 512>;
+      k->finalize_evict[2] = attend_finalize_evict<D, 8, false, 1024>;
       if constexpr (std::is_same<T, BF16>::value && D == 128) {
         k->finalize_evict[0] = k->finalize_evict[1] = k->finalize_evict[2] = nullptr;
         k->stream = attend_gqa<8>; k->merge = attend_gqa_merge<8>; k->finalize = attend_gqa_scores<8>;
@@ -2144,10 +2159,10 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
   for (int64_t i = 0; fuse_evict && i < n_pairs; ++i) {
     const int64_t n = static_cast<int64_t>(cache->len[first + i]) + (append ? 1 : 0);
     const int64_t kk = std::min<int64_t>(ev->budgets[i], n);
-    fuse_evict = n <= kStepMaxRows && (kk == 0 || n - kk <= kStepEvict);
+    fuse_evict = kk == 0 || n - kk <= kStepEvict;
   }
-  int step_shape = 2;
-  while (step_shape > 0 && max_n <= kStepShapes[step_shape - 1].threads * kStepShapes[step_shape - 1].slots) --step_shape;
+  // Small workgroups once there are two per compute unit of them, or when the streams are short anyway.
+  const int step_shape = max_n <= 4096 ? 0 : n_pairs * hkv >= 512 ? (max_n > 8192 ? 1 : 0) : 2;
 
   P.strip_rows = strip_rows;
   P.rec_floats = static_cast<int32_t>(rec);
@@ -2295,7 +2310,7 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
       S.row_bytes = D * (cache->dtype == XKV_F32 ? 4 : 2);
       const int tok = profile_begin(3, stream);
       hipLaunchKernelGGL(kern.finalize_evict[step_shape], dim3(static_cast<unsigned>(np * hkv)),
-                         dim3(kStepShapes[step_shape].threads), fin_lds, stream, S);
+                         dim3(256 << step_shape), fin_lds, stream, S);
       profile_end(tok, stream);
     } else if (gqa) {
       hipLaunchKernelGGL(kern.merge, dim3(static_cast<unsigned>(np * hkv)), dim3(kThreads), fin_lds, stream, P);

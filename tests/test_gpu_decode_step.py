@@ -19,9 +19,9 @@ def twin_caches(xkv, L, B, Hq, Hkv, d, dtype, caps, lens, seed, ties):
     return a, b
 
 
-def run_both(xkv, dtype, d, G, lens, evict, append, seed, pool=1, protect=0, ties=False, expect_one_kernel=None):
+def run_both(xkv, dtype, d, G, lens, evict, append, seed, pool=1, protect=0, ties=False, expect_one_kernel=None,
+             Hkv=2):
     """evict[l][b]: tokens to evict from the length after the append (budget = that length - evict)."""
-    Hkv = 2
     lens = np.asarray(lens, np.int32)
     L, B = lens.shape
     after = lens + (1 if append else 0)
@@ -83,7 +83,7 @@ def test_step_keeps_nothing_or_everything(xkv):
     run_both(xkv, "f32", 64, 2, lens, [[-5, -100]], True, seed=231, expect_one_kernel=True)
 
 
-@pytest.mark.parametrize("case", ["many evictions", "pooling", "protected", "long stream", "matrix cores"])
+@pytest.mark.parametrize("case", ["many evictions", "pooling", "protected", "matrix cores"])
 def test_step_falls_back_to_the_two_calls(xkv, case):
     """Calls outside the steady state run the two calls' kernels: same result, no score-and-evict launch."""
     print(f"case step fallback {case}", flush=True)
@@ -93,15 +93,21 @@ def test_step_falls_back_to_the_two_calls(xkv, case):
         run_both(xkv, "bf16", 128, 1, [[300, 900]], [[1, 1]], True, seed=241, pool=3, expect_one_kernel=False)
     elif case == "protected":
         run_both(xkv, "f32", 64, 1, [[300, 900]], [[1, 1]], True, seed=242, protect=4, expect_one_kernel=False)
-    elif case == "long stream":
-        run_both(xkv, "bf16", 128, 1, [[16384, 100]], [[1, 1]], True, seed=243, expect_one_kernel=False)
     else:
         run_both(xkv, "bf16", 128, 4, [[300, 900]], [[1, 1]], True, seed=244, expect_one_kernel=False)
 
 
-def test_longest_stream_of_the_one_kernel_step(xkv):
-    run_both(xkv, "bf16", 128, 1, [[16383, 12000]], [[1, 8]], True, seed=250, expect_one_kernel=True)
-    run_both(xkv, "f32", 64, 2, [[16384]], [[2]], False, seed=251, expect_one_kernel=True)
+def test_long_streams_and_both_workgroup_sizes(xkv):
+    """Two long streams per layer (few streams: the 1024-thread workgroups) and the same lengths in a
+    call of 512 streams (256-thread workgroups)."""
+    run_both(xkv, "bf16", 128, 1, [[20001, 12000]], [[1, 8]], True, seed=250, expect_one_kernel=True)
+    run_both(xkv, "f32", 64, 2, [[16385]], [[2]], False, seed=251, expect_one_kernel=True)
+    lens = np.full((8, 16), 40, np.int32)
+    lens[3, 5] = 9000
+    lens[7, 15] = 4097
+    evict = np.ones((8, 16), np.int32)
+    evict[3, 5] = 7
+    run_both(xkv, "bf16", 128, 1, lens, evict, True, seed=252, expect_one_kernel=True, Hkv=4)
 
 
 @pytest.mark.parametrize("dtype,d,G", [("bf16", 128, 1), ("f32", 64, 2)])
