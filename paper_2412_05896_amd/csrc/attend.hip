@@ -135,6 +135,11 @@ struct StepParams : AttendParams {
   int32_t* kept_idx;         // may be null
   int32_t row_bytes;
 };
+struct StepTableParams : AttendTableParams {
+  const int32_t* keep;       // the same, in device memory (it takes the place of fin0, which these kernels do not use)
+  int32_t* kept_idx;
+  int32_t row_bytes;
+};
 
 // First finalize workgroup of region i: with the tables in the arguments the host
 // rewrites full0 between the two launches.
@@ -1484,6 +1489,107 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
   }
 }
 
+constexpr int kStepEvict = 8;
+
+template <int kStepThreads>
+struct StepEvictShared {
+  unsigned long long best[kStepThreads / 64];
+  int ev[kStepEvict], hole[kStepEvict], mover[kStepEvict];
+  int moves;
+};
+
+// The eviction of one stream by its workgroup, after the pass that wrote the
+// stream's updated scores: `mine` is the smallest (score, -slot) pack the calling
+// thread saw in that pass.  Round 0 takes the workgroup's minimum of those; every
+// further eviction takes a pass over the scores in memory.  Then the holes (evicted
+// slots below kk) receive the surviving tokens of slots [kk, n), both ascending.
+template <int kStepThreads, typename PT>
+__device__ __forceinline__ void step_evict(const PT& P, unsigned long long mine, int n, int kk,
+                                           int64_t stream_slot, StepEvictShared<kStepThreads>& sh) {
+  constexpr int kStepWaves = kStepThreads / 64;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  // ---- eviction: the E = n - kk smallest (score, -slot), one per round ----------------
+  int32_t* kept = P.kept_idx ? P.kept_idx + stream_slot : nullptr;
+  const float* score = P.score + stream_slot;
+  const int E = (kk >= n || kk == 0) ? 0 : n - kk;        // nothing to select when all or none stay
+  unsigned long long last = 0;              // every pack is > 0: ~slot has its top bit set
+  for (int r = 0; r < E; ++r) {
+    unsigned long long best = mine;         // round 0: from the pass above
+    if (r > 0) {
+      __syncthreads();                      // the scores written above are visible to the whole workgroup
+      best = ~0ull;
+#pragma unroll 4
+      for (int j = tid; j < n; j += kStepThreads) {
+        const unsigned long long pk =
+            (static_cast<unsigned long long>(__float_as_uint(score[j])) << 32) | (0xffffffffu - static_cast<unsigned>(j));
+        if (pk > last && pk < best) best = pk;
+      }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      const unsigned long long o = __shfl_xor(best, off);
+      best = o < best ? o : best;
+    }
+    if (lane == 0) sh.best[wave] = best;
+    __syncthreads();
+    best = sh.best[0];
+#pragma unroll
+    for (int w = 1; w < kStepWaves; ++w) best = sh.best[w] < best ? sh.best[w] : best;
+    last = best;
+    if (tid == 0) sh.ev[r] = static_cast<int>(0xffffffffu - static_cast<unsigned>(best & 0xffffffffull));
+    __syncthreads();
+  }
+  if (tid == 0) {
+    // holes: evicted slots below kk, ascending; movers: the survivors among the slots [kk, n), ascending.
+    for (int a = 1; a < E; ++a) {
+      const int x = sh.ev[a];
+      int b = a - 1;
+      while (b >= 0 && sh.ev[b] > x) { sh.ev[b + 1] = sh.ev[b]; --b; }
+      sh.ev[b + 1] = x;
+    }
+    int nh = 0, nm = 0;
+    for (int a = 0; a < E; ++a)
+      if (sh.ev[a] < kk) sh.hole[nh++] = sh.ev[a];
+    for (int s = kk; s < n && E > 0; ++s) {
+      bool evicted = false;
+      for (int a = 0; a < E; ++a) evicted = evicted || sh.ev[a] == s;
+      if (!evicted) sh.mover[nm++] = s;
+    }
+    sh.moves = nh;
+  }
+  __syncthreads();                          // also: the new scores and the appended pos are visible to the movers
+  const int moves = sh.moves;
+  if (kept != nullptr)
+    for (int j = tid; j < kk; j += kStepThreads) {
+      bool is_hole = false;
+      for (int a = 0; a < moves; ++a) is_hole = is_hole || sh.hole[a] == j;
+      if (!is_hole) kept[j] = j;
+    }
+  for (int i = wave; i < moves; i += kStepWaves) {
+    const int dst = sh.hole[i], src = sh.mover[i];
+    const int frags = P.row_bytes >> 4;     // 16-byte pieces per row: 8, 16 or 32
+    if (lane < frags) {
+      char* kb = static_cast<char*>(P.k) + stream_slot * P.row_bytes;
+      char* vb = static_cast<char*>(P.v) + stream_slot * P.row_bytes;
+      const int64_t so = static_cast<int64_t>(src) * P.row_bytes + lane * 16;
+      const int64_t dof = static_cast<int64_t>(dst) * P.row_bytes + lane * 16;
+      const uint4 a = *reinterpret_cast<const uint4*>(kb + so);
+      const uint4 b = *reinterpret_cast<const uint4*>(vb + so);
+      *reinterpret_cast<uint4*>(kb + dof) = a;
+      *reinterpret_cast<uint4*>(vb + dof) = b;
+    } else if (lane == 32) {
+      P.score[stream_slot + dst] = P.score[stream_slot + src];
+    } else if (lane == 33) {
+      P.pos[stream_slot + dst] = P.pos[stream_slot + src];
+    } else if (lane == 34 && kept != nullptr) {
+      kept[dst] = src;
+    }
+  }
+
+}
+
 // ---------------------------------------------------------------------------
 // attend_finalize and the steady-state eviction in one kernel (xkv_decode_step):
 // one workgroup per stream.  It does what attend_finalize does for the whole
@@ -1502,19 +1608,15 @@ __global__ __launch_bounds__(kThreads) void attend_finalize(const PT P) {
 // more streams are resident at once the sooner the call is through) or its
 // streams are short, 512 when such a call has streams beyond 8192 slots (a
 // workgroup's time grows with its stream), 1024 for calls of few long streams.
-constexpr int kStepEvict = 8;
-
-template <int D, int G, bool kHalf, int kStepThreads>
-__global__ __launch_bounds__(kStepThreads) void attend_finalize_evict(const StepParams P) {
+template <int D, int G, bool kHalf, int kStepThreads, typename PT = StepParams>
+__global__ __launch_bounds__(kStepThreads) void attend_finalize_evict(const PT P) {
   constexpr int GD = G * D;
   constexpr int kStepWaves = kStepThreads / 64;
   constexpr int kBatch = 8;                 // slot pairs (16-bit records) or slots per thread in flight
   extern __shared__ float w_sh[];           // [G][nstrips] strip weights 2^(m_s - m) / l
   __shared__ float m_sh[G], inv_sh[G];
   __shared__ float o_red[kStepThreads];
-  __shared__ unsigned long long best_sh[kStepWaves];
-  __shared__ int ev_sh[kStepEvict], hole_l[kStepEvict], mover_l[kStepEvict];
-  __shared__ int moves_sh;
+  __shared__ StepEvictShared<kStepThreads> ev;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -1628,82 +1730,7 @@ __global__ __launch_bounds__(kStepThreads) void attend_finalize_evict(const Step
     }
   }
 
-  // ---- eviction: the E = n - kk smallest (score, -slot), one per round ----------------
-  int32_t* kept = P.kept_idx ? P.kept_idx + stream_slot : nullptr;
-  const int E = (kk >= n || kk == 0) ? 0 : n - kk;        // nothing to select when all or none stay
-  unsigned long long last = 0;              // every pack is > 0: ~slot has its top bit set
-  for (int r = 0; r < E; ++r) {
-    unsigned long long best = mine;         // round 0: from the pass above
-    if (r > 0) {
-      __syncthreads();                      // the scores written above are visible to the whole workgroup
-      best = ~0ull;
-#pragma unroll 4
-      for (int j = tid; j < n; j += kStepThreads) {
-        const unsigned long long pk =
-            (static_cast<unsigned long long>(__float_as_uint(score[j])) << 32) | (0xffffffffu - static_cast<unsigned>(j));
-        if (pk > last && pk < best) best = pk;
-      }
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-      const unsigned long long o = __shfl_xor(best, off);
-      best = o < best ? o : best;
-    }
-    if (lane == 0) best_sh[wave] = best;
-    __syncthreads();
-    best = best_sh[0];
-#pragma unroll
-    for (int w = 1; w < kStepWaves; ++w) best = best_sh[w] < best ? best_sh[w] : best;
-    last = best;
-    if (tid == 0) ev_sh[r] = static_cast<int>(0xffffffffu - static_cast<unsigned>(best & 0xffffffffull));
-    __syncthreads();
-  }
-  if (tid == 0) {
-    // holes: evicted slots below kk, ascending; movers: the survivors among the slots [kk, n), ascending.
-    for (int a = 1; a < E; ++a) {
-      const int x = ev_sh[a];
-      int b = a - 1;
-      while (b >= 0 && ev_sh[b] > x) { ev_sh[b + 1] = ev_sh[b]; --b; }
-      ev_sh[b + 1] = x;
-    }
-    int nh = 0, nm = 0;
-    for (int a = 0; a < E; ++a)
-      if (ev_sh[a] < kk) hole_l[nh++] = ev_sh[a];
-    for (int s = kk; s < n && E > 0; ++s) {
-      bool evicted = false;
-      for (int a = 0; a < E; ++a) evicted = evicted || ev_sh[a] == s;
-      if (!evicted) mover_l[nm++] = s;
-    }
-    moves_sh = nh;
-  }
-  __syncthreads();                          // also: the new scores and the appended pos are visible to the movers
-  const int moves = moves_sh;
-  if (kept != nullptr)
-    for (int j = tid; j < kk; j += kStepThreads) {
-      bool is_hole = false;
-      for (int a = 0; a < moves; ++a) is_hole = is_hole || hole_l[a] == j;
-      if (!is_hole) kept[j] = j;
-    }
-  for (int i = wave; i < moves; i += kStepWaves) {
-    const int dst = hole_l[i], src = mover_l[i];
-    const int frags = P.row_bytes >> 4;     // 16-byte pieces per row: 8, 16 or 32
-    if (lane < frags) {
-      char* kb = static_cast<char*>(P.k) + stream_slot * P.row_bytes;
-      char* vb = static_cast<char*>(P.v) + stream_slot * P.row_bytes;
-      const int64_t so = static_cast<int64_t>(src) * P.row_bytes + lane * 16;
-      const int64_t dof = static_cast<int64_t>(dst) * P.row_bytes + lane * 16;
-      const uint4 a = *reinterpret_cast<const uint4*>(kb + so);
-      const uint4 b = *reinterpret_cast<const uint4*>(vb + so);
-      *reinterpret_cast<uint4*>(kb + dof) = a;
-      *reinterpret_cast<uint4*>(vb + dof) = b;
-    } else if (lane == 32) {
-      P.score[stream_slot + dst] = P.score[stream_slot + src];
-    } else if (lane == 33) {
-      P.pos[stream_slot + dst] = P.pos[stream_slot + src];
-    } else if (lane == 34 && kept != nullptr) {
-      kept[dst] = src;
-    }
-  }
+  step_evict<kStepThreads>(P, mine, n, kk, stream_slot, ev);
 
   // out = sum_s w_s o_s: threads form (channel, slice) pairs; a slice sums every
   // S-th strip, then the slices are added in order.
@@ -1765,8 +1792,9 @@ struct Kernels {
   TableKernelFn finalize_tab = nullptr;
   KernelFn merge = nullptr;                // matrix-core path: attend_gqa_merge, then `finalize` = attend_gqa_scores
   TableKernelFn merge_tab = nullptr;
-  void (*finalize_evict[3])(const StepParams) = {nullptr, nullptr, nullptr};   // attend_finalize plus the steady-state
-                                                                               // eviction: 256, 512 and 1024 threads
+  // Score update plus the steady-state eviction (xkv_decode_step): workgroups of 256, 512 and 1024 threads.
+  void (*step[3])(const StepParams) = {nullptr, nullptr, nullptr};
+  void (*step_tab[3])(const StepTableParams) = {nullptr, nullptr, nullptr};
   int max_strip_rows = kChunk;  // longest strip the streaming kernel is given (a power of two)
   bool lds_logits = false;      // the streaming kernel collects the strip's logits in dynamic LDS
   bool half_records = false;    // attend_strip over bf16: records with 16-bit distances
@@ -1782,9 +1810,12 @@ bool pick_group(int group, Kernels* k) {
       k->finalize_tab = attend_finalize<D, 1, std::is_same<T, BF16>::value, AttendTableParams>;
       k->max_strip_rows = kMaxStripRows; k->lds_logits = true;
       k->fused = attend_fused<T, D, 1, 8>;
-      k->finalize_evict[0] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 256>;
-      k->finalize_evict[1] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 512>;
-      k->finalize_evict[2] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 1024>;
+      k->step[0] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 256>;
+      k->step_tab[0] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 256, StepTableParams>;
+      k->step[1] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 512>;
+      k->step_tab[1] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 512, StepTableParams>;
+      k->step[2] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 1024>;
+      k->step_tab[2] = attend_finalize_evict<D, 1, std::is_same<T, BF16>::value, 1024, StepTableParams>;
       return true;
     case 2:
       k->half_records = std::is_same<T, BF16>::value;
@@ -1793,20 +1824,28 @@ bool pick_group(int group, Kernels* k) {
       k->finalize_tab = attend_finalize<D, 2, std::is_same<T, BF16>::value, AttendTableParams>;
       k->max_strip_rows = kMaxStripRows; k->lds_logits = true;
       k->fused = attend_fused<T, D, 2, 8>;
-      k->finalize_evict[0] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 256>;
-      k->finalize_evict[1] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 512>;
-      k->finalize_evict[2] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 1024>;
+      k->step[0] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 256>;
+      k->step_tab[0] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 256, StepTableParams>;
+      k->step[1] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 512>;
+      k->step_tab[1] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 512, StepTableParams>;
+      k->step[2] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 1024>;
+      k->step_tab[2] = attend_finalize_evict<D, 2, std::is_same<T, BF16>::value, 1024, StepTableParams>;
       return true;
     case 4:
       k->stream = attend_chunk<T, D, 4>; k->finalize = attend_finalize<D, 4>;
       k->stream_tab = attend_chunk<T, D, 4, AttendTableParams>;
       k->finalize_tab = attend_finalize<D, 4, false, AttendTableParams>;
       k->fused = attend_fused<T, D, 4, 4>;
-      k->finalize_evict[0] = attend_finalize_evict<D, 4, false, 256>;
-      k->finalize_evict[1] = attend_finalize_evict<D, 4, false, 512>;
-      k->finalize_evict[2] = attend_finalize_evict<D, 4, false, 1024>;
+      k->step[0] = attend_finalize_evict<D, 4, false, 256>;
+      k->step_tab[0] = attend_finalize_evict<D, 4, false, 256, StepTableParams>;
+      k->step[1] = attend_finalize_evict<D, 4, false, 512>;
+      k->step_tab[1] = attend_finalize_evict<D, 4, false, 512, StepTableParams>;
+      k->step[2] = attend_finalize_evict<D, 4, false, 1024>;
+      k->step_tab[2] = attend_finalize_evict<D, 4, false, 1024, StepTableParams>;
       if constexpr (std::is_same<T, BF16>::value && D == 128) {
-        k->finalize_evict[0] = k->finalize_evict[1] = k->finalize_evict[2] = nullptr;
+        // (the matrix-core path keeps its three kernels: one workgroup per stream for the score update measured
+        // no faster than the score kernel's even split plus the selection kernel, 173 against 176 us per step)
+        for (int i = 0; i < 3; ++i) { k->step[i] = nullptr; k->step_tab[i] = nullptr; }
         k->stream = attend_gqa<4>; k->merge = attend_gqa_merge<4>; k->finalize = attend_gqa_scores<4>;
         k->stream_tab = attend_gqa<4, AttendTableParams>;
         k->merge_tab = attend_gqa_merge<4, AttendTableParams>;
@@ -1819,11 +1858,16 @@ bool pick_group(int group, Kernels* k) {
       k->stream_tab = attend_chunk<T, D, 8, AttendTableParams>;
       k->finalize_tab = attend_finalize<D, 8, false, AttendTableParams>;
       k->fused = attend_fused<T, D, 8, 2>;
-      k->finalize_evict[0] = attend_finalize_evict<D, 8, false, 256>;
-      k->finalize_evict[1] = attend_finalize_evict<D, 8, false, 512>;
-      k->finalize_evict[2] = attend_finalize_evict<D, 8, false, 1024>;
+      k->step[0] = attend_finalize_evict<D, 8, false, 256>;
+      k->step_tab[0] = attend_finalize_evict<D, 8, false, 256, StepTableParams>;
+      k->step[1] = attend_finalize_evict<D, 8, false, 512>;
+      k->step_tab[1] = attend_finalize_evict<D, 8, false, 512, StepTableParams>;
+      k->step[2] = attend_finalize_evict<D, 8, false, 1024>;
+      k->step_tab[2] = attend_finalize_evict<D, 8, false, 1024, StepTableParams>;
       if constexpr (std::is_same<T, BF16>::value && D == 128) {
-        k->finalize_evict[0] = k->finalize_evict[1] = k->finalize_evict[2] = nullptr;
+        // (the matrix-core path keeps its three kernels: one workgroup per stream for the score update measured
+        // no faster than the score kernel's even split plus the selection kernel, 173 against 176 us per step)
+        for (int i = 0; i < 3; ++i) { k->step[i] = nullptr; k->step_tab[i] = nullptr; }
         k->stream = attend_gqa<8>; k->merge = attend_gqa_merge<8>; k->finalize = attend_gqa_scores<8>;
         k->stream_tab = attend_gqa<8, AttendTableParams>;
         k->merge_tab = attend_gqa_merge<8, AttendTableParams>;
@@ -2153,9 +2197,8 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
   if (fin_lds > 48 * 1024) return XKV_ERR_UNSUPPORTED;
   const size_t stream_lds = kern.lds_logits ? static_cast<size_t>(G) * strip_rows * sizeof(float) : 0;
 
-  // The eviction rides on the finalize kernel when that kernel exists for this geometry, the call is one
-  // launch group, and every stream is short enough and evicts few enough tokens for one workgroup.
-  bool fuse_evict = ev != nullptr && kern.finalize_evict[0] != nullptr && !gqa && n_pairs <= kMaxPairs;
+  // The eviction rides on the kernel that updates the scores when every stream evicts few enough tokens.
+  bool fuse_evict = ev != nullptr && kern.step[0] != nullptr;
   for (int64_t i = 0; fuse_evict && i < n_pairs; ++i) {
     const int64_t n = static_cast<int64_t>(cache->len[first + i]) + (append ? 1 : 0);
     const int64_t kk = std::min<int64_t>(ev->budgets[i], n);
@@ -2193,7 +2236,10 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
         return XKV_ERR_UNSUPPORTED;
       pd.strip0 = static_cast<int32_t>(strips);
       pd.full0 = static_cast<int32_t>(full);
-      hfin[i] = static_cast<int32_t>(fin_blocks);
+      // (a call that evicts in its score kernel has no finalize workgroups to number: the column carries
+      // the regions' keep counts instead)
+      hfin[i] = fuse_evict ? static_cast<int32_t>(std::min<int64_t>(ev->budgets[i], pd.n))
+                           : static_cast<int32_t>(fin_blocks);
       hpos[i] = append ? pos_new[i % B] : 0;
       const int64_t nstrips = std::max<int64_t>(ceil_div(pd.n, strip_rows), 1);
       strips += nstrips * hkv;
@@ -2246,7 +2292,17 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
       profile_end(tok, stream);
       if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     }
-    if (gqa) {
+    if (fuse_evict) {
+      StepTableParams S;
+      static_cast<AttendTableParams&>(S) = T;
+      S.keep = d_fin;
+      S.kept_idx = ev->kept_idx;
+      S.row_bytes = D * (cache->dtype == XKV_F32 ? 4 : 2);
+      const int tok = profile_begin(3, stream);
+      hipLaunchKernelGGL(kern.step_tab[step_shape], dim3(static_cast<unsigned>(n_pairs * hkv)),
+                         dim3(256 << step_shape), fin_lds, stream, S);
+      profile_end(tok, stream);
+    } else if (gqa) {
       hipLaunchKernelGGL(kern.merge_tab, dim3(static_cast<unsigned>(n_pairs * hkv)), dim3(kThreads), fin_lds, stream, T);
       hipLaunchKernelGGL(kern.finalize_tab, dim3(static_cast<unsigned>(fin_blocks)), dim3(kThreads), 0, stream, T);
     } else {
@@ -2255,6 +2311,11 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
     }
     if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
     for (int64_t i = 0; append && i < n_pairs; ++i) cache->len[first + i] += 1;
+    if (fuse_evict) {
+      for (int64_t i = 0; i < n_pairs; ++i)
+        cache->len[first + i] = static_cast<int32_t>(std::min<int64_t>(ev->budgets[i], cache->len[first + i]));
+      ev->done = true;
+    }
     return XKV_OK;
   }
 
@@ -2309,7 +2370,7 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
       S.kept_idx = ev->kept_idx;
       S.row_bytes = D * (cache->dtype == XKV_F32 ? 4 : 2);
       const int tok = profile_begin(3, stream);
-      hipLaunchKernelGGL(kern.finalize_evict[step_shape], dim3(static_cast<unsigned>(np * hkv)),
+      hipLaunchKernelGGL(kern.step[step_shape], dim3(static_cast<unsigned>(np * hkv)),
                          dim3(256 << step_shape), fin_lds, stream, S);
       profile_end(tok, stream);
     } else if (gqa) {
