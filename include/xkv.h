@@ -281,11 +281,12 @@ xkv_status xkv_evict_compact(xkv_cache* cache, int32_t layer_begin, int32_t laye
  * and moved rows bit for bit; out up to the order of its fp32 sums).
  *
  * In the steady state of decoding (every stream of the call evicts at most 8
- * tokens, pool_size 1, n_protect 0, and a query group the split-K kernels serve
- * without the matrix cores) the eviction runs inside the kernel that updates the
- * scores, on the scores it has just computed: one launch less and no second pass
- * over the scores.  Any other call runs the two calls' kernels one after the
- * other.
+ * tokens, at most 1 with pooling or protected tokens, and a query group the
+ * split-K kernels serve without the matrix cores)
+ * the eviction runs inside the kernel that updates the scores, on the scores it
+ * has just computed: one launch less, no key workspace and, without pooling and
+ * protected tokens, no second pass over the scores.  Any other call runs the two
+ * calls' kernels one after the other.
  *
  *   arguments   as for xkv_decode_attend_score and xkv_evict_compact; budgets apply
  *               to the lengths after the append; workspace at least

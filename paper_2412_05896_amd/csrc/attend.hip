@@ -134,11 +134,13 @@ struct StepParams : AttendParams {
   int32_t keep[kMaxPairs];   // min(budget, n) of every region
   int32_t* kept_idx;         // may be null
   int32_t row_bytes;
+  int32_t pool, n_protect;   // as for xkv_evict_compact
 };
 struct StepTableParams : AttendTableParams {
   const int32_t* keep;       // the same, in device memory (it takes the place of fin0, which these kernels do not use)
   int32_t* kept_idx;
   int32_t row_bytes;
+  int32_t pool, n_protect;
 };
 
 // First finalize workgroup of region i: with the tables in the arguments the host
@@ -1500,19 +1502,19 @@ struct StepEvictShared {
 
 // The eviction of one stream by its workgroup, after the pass that wrote the
 // stream's updated scores: `mine` is the smallest (score, -slot) pack the calling
-// thread saw in that pass.  Round 0 takes the workgroup's minimum of those; every
-// further eviction takes a pass over the scores in memory.  Then the holes (evicted
+// thread saw in that pass (or in a pass of its own over key_at, for derived keys).
+// Round 0 takes the workgroup's minimum of those; every further eviction takes a
+// pass over key_at(slot), the key of a slot from the scores in memory.  Then the holes (evicted
 // slots below kk) receive the surviving tokens of slots [kk, n), both ascending.
-template <int kStepThreads, typename PT>
+template <int kStepThreads, typename PT, typename KeyAt>
 __device__ __forceinline__ void step_evict(const PT& P, unsigned long long mine, int n, int kk,
-                                           int64_t stream_slot, StepEvictShared<kStepThreads>& sh) {
+                                           int64_t stream_slot, StepEvictShared<kStepThreads>& sh, KeyAt key_at) {
   constexpr int kStepWaves = kStepThreads / 64;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
   // ---- eviction: the E = n - kk smallest (score, -slot), one per round ----------------
   int32_t* kept = P.kept_idx ? P.kept_idx + stream_slot : nullptr;
-  const float* score = P.score + stream_slot;
   const int E = (kk >= n || kk == 0) ? 0 : n - kk;        // nothing to select when all or none stay
   unsigned long long last = 0;              // every pack is > 0: ~slot has its top bit set
   for (int r = 0; r < E; ++r) {
@@ -1523,7 +1525,7 @@ __device__ __forceinline__ void step_evict(const PT& P, unsigned long long mine,
 #pragma unroll 4
       for (int j = tid; j < n; j += kStepThreads) {
         const unsigned long long pk =
-            (static_cast<unsigned long long>(__float_as_uint(score[j])) << 32) | (0xffffffffu - static_cast<unsigned>(j));
+            (static_cast<unsigned long long>(key_at(j)) << 32) | (0xffffffffu - static_cast<unsigned>(j));
         if (pk > last && pk < best) best = pk;
       }
     }
@@ -1600,8 +1602,9 @@ __device__ __forceinline__ void step_evict(const PT& P, unsigned long long mine,
 // Further evictions (at most kStepEvict per stream) each take one more pass over
 // the scores just written, which the L2 still holds.  Then the kept tokens of
 // the slots at or beyond the budget move into the holes.  The host takes this
-// kernel only when every stream of the call evicts at most kStepEvict tokens,
-// without pooling or protected tokens.
+// kernel only when every stream of the call evicts at most kStepEvict tokens.
+// With pooling or protected tokens the keys are derived from the scores just
+// written (a pass of its own over them, out of the L2).
 //
 // Three workgroup sizes: 256 threads when the call has enough streams to fill the
 // chip with such workgroups (the kernel is a chain of dependent steps, and the
@@ -1730,7 +1733,97 @@ __global__ __launch_bounds__(kStepThreads) void attend_finalize_evict(const PT P
     }
   }
 
-  step_evict<kStepThreads>(P, mine, n, kk, stream_slot, ev);
+  // Keys of the eviction: the score itself, or (pooling, protected tokens) derived from the
+  // scores just written, as in the selection kernel: the fp32 window sum, left to right, zeros
+  // outside the stream; +inf for the n_protect highest positions.
+  const bool derived = P.pool > 1 || P.n_protect > 0;
+  const int32_t* pos = P.pos + stream_slot;
+  int limit = std::numeric_limits<int>::min();             // protected: pos >= limit
+  const int E_all = (kk >= n || kk == 0) ? 0 : n - kk;
+  if (derived && E_all > 0) {
+    __syncthreads();                        // the new scores and the appended pos are visible
+    if (P.n_protect > 0) {
+      int mx = std::numeric_limits<int>::min();
+#pragma unroll 4
+      for (int j = tid; j < n; j += kStepThreads) mx = max(mx, pos[j]);
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) mx = max(mx, __shfl_xor(mx, off));
+      if (lane == 0) reinterpret_cast<int*>(ev.best)[wave] = mx;
+      __syncthreads();
+      mx = reinterpret_cast<int*>(ev.best)[0];
+#pragma unroll
+      for (int w = 1; w < kStepWaves; ++w) mx = max(mx, reinterpret_cast<int*>(ev.best)[w]);
+      const long long lim = static_cast<long long>(mx) + 1 - P.n_protect;
+      limit = lim < std::numeric_limits<int>::min() ? std::numeric_limits<int>::min() : static_cast<int>(lim);
+      __syncthreads();
+    }
+  }
+  const int half = P.pool >> 1;
+  auto key_at = [&](int j) -> unsigned {
+    if (!derived) return __float_as_uint(score[j]);
+    float acc = 0.0f;
+    for (int t0 = 0; t0 < P.pool; t0 += 8) {              // the terms are fetched eight at a time so that their loads overlap
+      float term[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int x = j - half + t0 + q;
+        term[q] = (t0 + q < P.pool && x >= 0 && x < n) ? score[x] : 0.0f;
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (t0 + q < P.pool) acc = (t0 + q == 0) ? term[q] : acc + term[q];
+    }
+    unsigned key = __float_as_uint(acc);
+    if (P.n_protect > 0 && pos[j] >= limit) key = 0x7f800000u;
+    return key;
+  };
+  if (derived && E_all > 0) {
+    mine = ~0ull;
+    if (P.pool <= 64) {
+      // Tiles of one slot per thread: the tile's scores and the window's overhang on both sides pass
+      // through LDS (two buffers: the next tile is requested while this one is summed), so that a score
+      // is read from memory once instead of pool times.
+      __shared__ float tile_sh[2][kStepThreads + 64];
+      const int span = kStepThreads + P.pool - 1;          // tile plus overhang
+      const int tiles = (n + kStepThreads - 1) / kStepThreads;
+      auto fetch = [&](int t, float& a, float& b, int& pj) {
+        const int x0 = t * kStepThreads - half + tid, x1 = x0 + kStepThreads;
+        a = (x0 >= 0 && x0 < n) ? score[x0] : 0.0f;
+        b = (tid + kStepThreads < span && x1 >= 0 && x1 < n) ? score[x1] : 0.0f;
+        const int j = t * kStepThreads + tid;
+        pj = (P.n_protect > 0 && j < n) ? pos[j] : std::numeric_limits<int>::min();
+      };
+      float a, b;
+      int pj;
+      fetch(0, a, b, pj);
+      for (int t = 0; t < tiles; ++t) {
+        float* tile = tile_sh[t & 1];
+        tile[tid] = a;
+        if (tid + kStepThreads < span) tile[tid + kStepThreads] = b;
+        const int pj_now = pj;
+        __syncthreads();                      // tile t is in LDS; the other buffer's readers (tile t-1) are past it
+        if (t + 1 < tiles) fetch(t + 1, a, b, pj);
+        const int j = t * kStepThreads + tid;
+        if (j < n) {
+          float acc = tile[tid];              // window sum, fp32, left to right
+          for (int q = 1; q < P.pool; ++q) acc = acc + tile[tid + q];
+          unsigned key = __float_as_uint(acc);
+          if (P.n_protect > 0 && pj_now >= limit) key = 0x7f800000u;
+          const unsigned long long pk =
+              (static_cast<unsigned long long>(key) << 32) | (0xffffffffu - static_cast<unsigned>(j));
+          mine = pk < mine ? pk : mine;
+        }
+      }
+    } else {
+#pragma unroll 2
+      for (int j = tid; j < n; j += kStepThreads) {
+        const unsigned long long pk =
+            (static_cast<unsigned long long>(key_at(j)) << 32) | (0xffffffffu - static_cast<unsigned>(j));
+        mine = pk < mine ? pk : mine;
+      }
+    }
+  }
+  step_evict<kStepThreads>(P, mine, n, kk, stream_slot, ev, key_at);
 
   // out = sum_s w_s o_s: threads form (channel, slice) pairs; a slice sums every
   // S-th strip, then the slices are added in order.
@@ -2111,6 +2204,7 @@ extern "C" xkv_status xkv_fused_status(int32_t* gave_up_out) {
 struct StepEvict {
   const int32_t* budgets;
   int32_t* kept_idx;
+  int32_t pool, n_protect;
   bool done;
 };
 
@@ -2202,7 +2296,8 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
   for (int64_t i = 0; fuse_evict && i < n_pairs; ++i) {
     const int64_t n = static_cast<int64_t>(cache->len[first + i]) + (append ? 1 : 0);
     const int64_t kk = std::min<int64_t>(ev->budgets[i], n);
-    fuse_evict = kk == 0 || n - kk <= kStepEvict;
+    // (derived keys cost a pass over the pooled scores per eviction after the first: one eviction only)
+    fuse_evict = kk == 0 || n - kk <= ((ev->pool > 1 || ev->n_protect > 0) ? 1 : kStepEvict);
   }
   // Small workgroups once there are two per compute unit of them, or when the streams are short anyway.
   const int step_shape = max_n <= 4096 ? 0 : n_pairs * hkv >= 512 ? (max_n > 8192 ? 1 : 0) : 2;
@@ -2298,6 +2393,8 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
       S.keep = d_fin;
       S.kept_idx = ev->kept_idx;
       S.row_bytes = D * (cache->dtype == XKV_F32 ? 4 : 2);
+      S.pool = ev->pool;
+      S.n_protect = ev->n_protect;
       const int tok = profile_begin(3, stream);
       hipLaunchKernelGGL(kern.step_tab[step_shape], dim3(static_cast<unsigned>(n_pairs * hkv)),
                          dim3(256 << step_shape), fin_lds, stream, S);
@@ -2369,6 +2466,8 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
         S.keep[i] = static_cast<int32_t>(std::min<int64_t>(ev->budgets[g0 + i], P.pairs[i].n));
       S.kept_idx = ev->kept_idx;
       S.row_bytes = D * (cache->dtype == XKV_F32 ? 4 : 2);
+      S.pool = ev->pool;
+      S.n_protect = ev->n_protect;
       const int tok = profile_begin(3, stream);
       hipLaunchKernelGGL(kern.step[step_shape], dim3(static_cast<unsigned>(np * hkv)),
                          dim3(256 << step_shape), fin_lds, stream, S);
@@ -2407,10 +2506,9 @@ extern "C" xkv_status xkv_decode_step(xkv_cache* cache, int32_t layer_begin, int
   st = evict_check_args(cache, layer_begin, layer_end, budgets, pool_size, n_protect, k_new != nullptr ? 1 : 0,
                         workspace, workspace_bytes);
   if (st != XKV_OK) return st;
-  StepEvict ev{budgets, kept_idx_out, false};
-  const bool plain_keys = pool_size == 1 && n_protect == 0;
+  StepEvict ev{budgets, kept_idx_out, pool_size, n_protect, false};
   st = decode_attend(cache, layer_begin, layer_end, q, k_new, v_new, pos_new, softmax_scale, out, workspace,
-                     workspace_bytes, hip_stream, true, plain_keys ? &ev : nullptr);
+                     workspace_bytes, hip_stream, true, &ev);
   if (st != XKV_OK || ev.done) return st;
   return xkv_evict_compact(cache, layer_begin, layer_end, budgets, pool_size, n_protect, kept_idx_out, workspace,
                            workspace_bytes, hip_stream);

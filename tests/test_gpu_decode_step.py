@@ -85,16 +85,26 @@ def test_step_keeps_nothing_or_everything(xkv):
     run_both(xkv, "f32", 64, 2, lens, [[-5, -100]], True, seed=231, expect_one_kernel=True)
 
 
-@pytest.mark.parametrize("case", ["many evictions", "pooling", "protected"])
-def test_step_falls_back_to_the_two_calls(xkv, case):
-    """Calls outside the steady state run the two calls' kernels: same result, no score-and-evict launch."""
-    print(f"case step fallback {case}", flush=True)
-    if case == "many evictions":
-        run_both(xkv, "bf16", 128, 1, [[300, 900]], [[9, 1]], True, seed=240, expect_one_kernel=False)
-    elif case == "pooling":
-        run_both(xkv, "bf16", 128, 1, [[300, 900]], [[1, 1]], True, seed=241, pool=3, expect_one_kernel=False)
-    else:
-        run_both(xkv, "f32", 64, 1, [[300, 900]], [[1, 1]], True, seed=242, protect=4, expect_one_kernel=False)
+def test_step_falls_back_to_the_two_calls(xkv):
+    """More than 8 evictions in some stream: the two calls' kernels, same result, no score-and-evict launch."""
+    run_both(xkv, "bf16", 128, 1, [[300, 900]], [[9, 1]], True, seed=240, expect_one_kernel=False)
+    run_both(xkv, "f32", 64, 2, [[300, 900]], [[2, 500]], False, seed=241, pool=3, protect=2, expect_one_kernel=False)
+
+
+@pytest.mark.parametrize("dtype,d,G", [("bf16", 128, 1), ("f32", 64, 2), ("f32", 128, 4)])
+@pytest.mark.parametrize("pool,protect", [(7, 8), (3, 0), (1, 5), (63, 1)])
+def test_step_with_pooling_and_protected_tokens(xkv, dtype, d, G, pool, protect):
+    """The paper's settings (pooling 7, the 8 most recent positions never evicted) and others: keys derived
+    from the scores the step has just written."""
+    print(f"case step derived keys dtype={dtype} d={d} G={G} pool={pool} protect={protect}", flush=True)
+    lens = [[8, 9, 40], [255, 256, 257], [700, 5000, 1030]]
+    evict = [[1, 1, 0], [1, 0, 1], [1, 1, 1]]
+    run_both(xkv, dtype, d, G, lens, evict, True, seed=280 + G, pool=pool, protect=protect, expect_one_kernel=True)
+    run_both(xkv, dtype, d, G, lens, evict, False, seed=290 + G, pool=pool, protect=protect, ties=True,
+             expect_one_kernel=True)
+    # more than one eviction with derived keys: the two calls' kernels
+    run_both(xkv, dtype, d, G, lens, [[1, 1, 8], [1, 0, 3], [8, 2, 1]], True, seed=295 + G, pool=pool, protect=protect,
+             expect_one_kernel=False)
 
 
 def test_long_streams_and_both_workgroup_sizes(xkv):
