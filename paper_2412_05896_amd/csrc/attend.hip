@@ -1780,38 +1780,52 @@ __global__ __launch_bounds__(kStepThreads) void attend_finalize_evict(const PT P
   if (derived && E_all > 0) {
     mine = ~0ull;
     if (P.pool <= 64) {
-      // Tiles of one slot per thread: the tile's scores and the window's overhang on both sides pass
+      // Tiles of kPer slots per thread: the tile's scores and the window's overhang on both sides pass
       // through LDS (two buffers: the next tile is requested while this one is summed), so that a score
       // is read from memory once instead of pool times.
-      __shared__ float tile_sh[2][kStepThreads + 64];
-      const int span = kStepThreads + P.pool - 1;          // tile plus overhang
-      const int tiles = (n + kStepThreads - 1) / kStepThreads;
-      auto fetch = [&](int t, float& a, float& b, int& pj) {
-        const int x0 = t * kStepThreads - half + tid, x1 = x0 + kStepThreads;
-        a = (x0 >= 0 && x0 < n) ? score[x0] : 0.0f;
-        b = (tid + kStepThreads < span && x1 >= 0 && x1 < n) ? score[x1] : 0.0f;
-        const int j = t * kStepThreads + tid;
-        pj = (P.n_protect > 0 && j < n) ? pos[j] : std::numeric_limits<int>::min();
+      constexpr int kPer = 4, kTileSlots = kPer * kStepThreads;
+      __shared__ float tile_sh[2][kTileSlots + 64];
+      const int span = kTileSlots + P.pool - 1;            // tile plus overhang
+      const int tiles = (n + kTileSlots - 1) / kTileSlots;
+      float pre[kPer + 1];
+      int pj[kPer];
+      auto fetch = [&](int t) {
+#pragma unroll
+        for (int k = 0; k <= kPer; ++k) {
+          const int i = tid + k * kStepThreads;
+          const int x = t * kTileSlots - half + i;
+          pre[k] = (i < span && x >= 0 && x < n) ? score[x] : 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+          const int j = t * kTileSlots + tid + k * kStepThreads;
+          pj[k] = (P.n_protect > 0 && j < n) ? pos[j] : std::numeric_limits<int>::min();
+        }
       };
-      float a, b;
-      int pj;
-      fetch(0, a, b, pj);
+      fetch(0);
       for (int t = 0; t < tiles; ++t) {
         float* tile = tile_sh[t & 1];
-        tile[tid] = a;
-        if (tid + kStepThreads < span) tile[tid + kStepThreads] = b;
-        const int pj_now = pj;
+#pragma unroll
+        for (int k = 0; k <= kPer; ++k)
+          if (tid + k * kStepThreads < span) tile[tid + k * kStepThreads] = pre[k];
+        int pj_now[kPer];
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) pj_now[k] = pj[k];
         __syncthreads();                      // tile t is in LDS; the other buffer's readers (tile t-1) are past it
-        if (t + 1 < tiles) fetch(t + 1, a, b, pj);
-        const int j = t * kStepThreads + tid;
-        if (j < n) {
-          float acc = tile[tid];              // window sum, fp32, left to right
-          for (int q = 1; q < P.pool; ++q) acc = acc + tile[tid + q];
-          unsigned key = __float_as_uint(acc);
-          if (P.n_protect > 0 && pj_now >= limit) key = 0x7f800000u;
-          const unsigned long long pk =
-              (static_cast<unsigned long long>(key) << 32) | (0xffffffffu - static_cast<unsigned>(j));
-          mine = pk < mine ? pk : mine;
+        if (t + 1 < tiles) fetch(t + 1);
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+          const int jl = tid + k * kStepThreads;
+          const int j = t * kTileSlots + jl;
+          if (j < n) {
+            float acc = tile[jl];             // window sum, fp32, left to right
+            for (int q = 1; q < P.pool; ++q) acc = acc + tile[jl + q];
+            unsigned key = __float_as_uint(acc);
+            if (P.n_protect > 0 && pj_now[k] >= limit) key = 0x7f800000u;
+            const unsigned long long pk =
+                (static_cast<unsigned long long>(key) << 32) | (0xffffffffu - static_cast<unsigned>(j));
+            mine = pk < mine ? pk : mine;
+          }
         }
       }
     } else {
