@@ -198,7 +198,8 @@ class XkvCache:
     """Owns the arenas (torch tensors) and the host tables of one ragged cache
     and the xkv_cache struct that points at them."""
 
-    def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, dtype, caps, device="cuda"):
+    def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, dtype, caps, device="cuda", zero=True):
+        """zero=False leaves the arenas uninitialised (the library never reads a slot at or beyond len)."""
         import torch
         caps = np.ascontiguousarray(caps, dtype=np.int32).reshape(n_layers * batch)
         self.n_layers, self.batch = int(n_layers), int(batch)
@@ -213,10 +214,11 @@ class XkvCache:
         self.len = np.zeros(n_layers * batch, dtype=np.int32)
         self.arena_slots = int(sizes.sum())
         slots = max(self.arena_slots, 1)
-        self.k = torch.zeros((slots, head_dim), dtype=self.torch_dtype, device=device)
-        self.v = torch.zeros((slots, head_dim), dtype=self.torch_dtype, device=device)
-        self.score = torch.zeros(slots, dtype=torch.float32, device=device)
-        self.pos = torch.zeros(slots, dtype=torch.int32, device=device)
+        alloc = torch.zeros if zero else torch.empty
+        self.k = alloc((slots, head_dim), dtype=self.torch_dtype, device=device)
+        self.v = alloc((slots, head_dim), dtype=self.torch_dtype, device=device)
+        self.score = alloc(slots, dtype=torch.float32, device=device)
+        self.pos = alloc(slots, dtype=torch.int32, device=device)
         self.struct = _CacheStruct()
         self.refresh()
 
@@ -238,7 +240,7 @@ class XkvCache:
         stream.  Used to leave the prompt-sized arena once the first eviction has
         shrunk every layer to its budget."""
         new = XkvCache(self.n_layers, self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim,
-                       self.dtype, caps, device=self.k.device)
+                       self.dtype, caps, device=self.k.device, zero=False)
         xkv_repack(self, new, 0, self.n_layers, stream=stream)
         return new
 

@@ -8,7 +8,7 @@ from gpu_util import random_fill
 pytestmark = pytest.mark.gpu
 
 
-def _check_copy(src, dst):
+def _check_copy(src, dst, zeroed=True):
     assert np.array_equal(dst.len, src.len)
     sk, sv = src.k.view(torch.int16).cpu().numpy(), src.v.view(torch.int16).cpu().numpy()
     dk, dv = dst.k.view(torch.int16).cpu().numpy(), dst.v.view(torch.int16).cpu().numpy()
@@ -24,6 +24,8 @@ def _check_copy(src, dst):
                 assert np.array_equal(ds[d:d + n].view(np.uint32), ss[a:a + n].view(np.uint32))
                 assert np.array_equal(dp[d:d + n], sp[a:a + n])
                 touched[d:d + n] = True
+    if not zeroed:
+        return
     # nothing beyond the live slots was written: the new arenas start as zeros
     assert not dk[~touched].any() and not dv[~touched].any() and not ds[~touched].any() and not dp[~touched].any()
 
@@ -39,9 +41,13 @@ def test_repack_matches_slicing(xkv, dtype, d, Hkv, L, B):
     random_fill(src, lens, 5)
     new_caps = lens + r.integers(0, 5, size=(L, B)).astype(np.int32)      # some streams exactly full
     print(f"case repack dtype={dtype} d={d} Hkv={Hkv} L={L} B={B}", flush=True)
-    dst = src.resized(new_caps)
+    dst = xkv.XkvCache(L, B, Hkv * 2, Hkv, d, dtype, new_caps)            # zero-filled arenas
+    xkv.xkv_repack(src, dst, 0, L)
     torch.cuda.synchronize()
     _check_copy(src, dst)
+    dst2 = src.resized(new_caps)                                           # the same into uninitialised arenas
+    torch.cuda.synchronize()
+    _check_copy(src, dst2, zeroed=False)
 
 
 def test_repack_layer_range_and_errors(xkv):
