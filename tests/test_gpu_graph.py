@@ -10,11 +10,20 @@ from gpu_util import random_fill
 pytestmark = pytest.mark.gpu
 
 
+@pytest.mark.parametrize("one_call", [False, True], ids=["two-calls", "decode-step"])
 @pytest.mark.parametrize("dtype,d,Hq,Hkv,many", [("bf16", 128, 4, 4, False), ("bf16", 128, 8, 2, False),
-                                                 ("f32", 64, 4, 4, False), ("bf16", 128, 8, 2, True)])
-def test_captured_step_replays_like_eager(xkv, dtype, d, Hq, Hkv, many):
+                                                 ("f32", 64, 4, 4, False), ("bf16", 128, 8, 2, True),
+                                                 ("bf16", 128, 2, 2, True)])
+def test_captured_step_replays_like_eager(xkv, dtype, d, Hq, Hkv, many, one_call):
     """many: more regions than the kernel arguments hold, so the graph also holds the launches
-    that write the geometry tables."""
+    that write the geometry tables.  one_call: the step is xkv_decode_step (eager and captured)."""
+    def run_step(c, q_, kn_, vn_, out_, ws_, stream=None):
+        if one_call:
+            xkv.xkv_decode_step(c, 0, L, q_, kn_, vn_, pos_new, out_, budgets, ws_, stream=stream)
+        else:
+            xkv.xkv_decode_attend_score(c, 0, L, q_, kn_, vn_, pos_new, out_, ws_, stream=stream)
+            xkv.xkv_evict_compact(c, 0, L, budgets, ws_, stream=stream)
+
     if many:
         L, B = 3, 50
         budgets = np.random.default_rng(4).integers(8, 200, size=(L, B)).astype(np.int32)
@@ -42,8 +51,7 @@ def test_captured_step_replays_like_eager(xkv, dtype, d, Hq, Hkv, many):
     out_ref = torch.empty((L, B, Hq, d), dtype=torch.float32, device="cuda")
     states = []
     for s in range(steps):
-        xkv.xkv_decode_attend_score(ref, 0, L, qs[s], kns[s], vns[s], pos_new, out_ref, ws_ref)
-        xkv.xkv_evict_compact(ref, 0, L, budgets, ws_ref)
+        run_step(ref, qs[s], kns[s], vns[s], out_ref, ws_ref)
         torch.cuda.synchronize()
         states.append((out_ref.clone(), ref.k.clone(), ref.score.clone(), ref.pos.clone()))
 
@@ -58,16 +66,14 @@ def test_captured_step_replays_like_eager(xkv, dtype, d, Hq, Hkv, many):
     snapshot = (cache.k.clone(), cache.v.clone(), cache.score.clone(), cache.pos.clone())
     with torch.cuda.stream(side):
         # warm-up launch outside the capture (loads the code objects), then restore the state
-        xkv.xkv_decode_attend_score(cache, 0, L, q, kn, vn, pos_new, out, ws, stream=side)
-        xkv.xkv_evict_compact(cache, 0, L, budgets, ws, stream=side)
+        run_step(cache, q, kn, vn, out, ws, stream=side)
         side.synchronize()
         for dst, src in zip((cache.k, cache.v, cache.score, cache.pos), snapshot):
             dst.copy_(src)
         side.synchronize()
         assert np.array_equal(cache.len.reshape(L, B), budgets)       # the step returns to its lengths
         with torch.cuda.graph(graph, stream=side):
-            xkv.xkv_decode_attend_score(cache, 0, L, q, kn, vn, pos_new, out, ws, stream=side)
-            xkv.xkv_evict_compact(cache, 0, L, budgets, ws, stream=side)
+            run_step(cache, q, kn, vn, out, ws, stream=side)
     torch.cuda.current_stream().wait_stream(side)
     assert np.array_equal(cache.len.reshape(L, B), budgets)
     for s in range(steps):
