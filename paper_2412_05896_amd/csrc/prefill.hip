@@ -508,7 +508,7 @@ __global__ __launch_bounds__(kThreads) void window_merge(const WindowParams P) {
   }
   float fm, fil;
   stream_fin(P, u, part_sh, fm, fil);
-  if (threadIdx.x < P.nq_pad) {
+  if (static_cast<int>(threadIdx.x) < P.nq_pad) {
     float* f = P.fin + (static_cast<int64_t>(u) * P.nq_pad + threadIdx.x) * 2;
     f[0] = fm;
     f[1] = fil;
