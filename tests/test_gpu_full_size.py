@@ -27,7 +27,9 @@ def unit_mass(cache):
     return out
 
 
-def run_full(xkv, name, steps, n_sample):
+def run_full(xkv, name, steps, n_sample, step_twin=False):
+    """step_twin: from the second step on (budget-sized arena, steady state) a copy of the cache takes
+    xkv_decode_step, the call bench.py times, and must equal the two calls' cache bit for bit."""
     w = wl.WORKLOADS[name]
     L, B, G = w.n_layers, w.batch, w.group
     if w.budget_rule == "dirichlet":
@@ -58,8 +60,15 @@ def run_full(xkv, name, steps, n_sample):
             units.append(u)
     orcs = {u: orc.OracleUnit(*get_unit(cache, *u)) for u in units}
     evicted = np.zeros((L, B, w.n_kv_heads))
+    twin, out_b, one_kernel_steps = None, None, 0
     for step in range(steps):
         print(f"{name}: step {step}", flush=True)
+        if twin is not None:
+            xkv.xkv_profile_enable(True)
+            xkv.xkv_decode_step(twin, 0, L, q[step], kn[step], vn[step], pos_new[step], out_b, budgets, ws_b)
+            torch.cuda.synchronize()
+            one_kernel_steps += 1 if xkv.xkv_profile_read(3)[0] > 0 else 0
+            xkv.xkv_profile_enable(False)
         xkv.xkv_decode_attend_score(cache, 0, L, q[step], kn[step], vn[step], pos_new[step], out, ws)
         torch.cuda.synchronize()
         o_host = out.cpu().numpy()
@@ -92,12 +101,25 @@ def run_full(xkv, name, steps, n_sample):
             assert np.array_equal(K, u.K) and np.array_equal(V, u.V)
             assert np.array_equal(sc, u.score) and np.array_equal(pos, u.pos)
         del kept
+        if twin is not None:
+            assert np.array_equal(twin.len, cache.len)
+            assert torch.equal(twin.k, cache.k) and torch.equal(twin.v, cache.v), f"step {step}: twin K/V"
+            assert torch.equal(twin.score, cache.score) and torch.equal(twin.pos, cache.pos), f"step {step}: twin"
+            assert rel_err(out_b.cpu().numpy(), o_host) <= 1e-5
         if step == 0:
             small = cache.resized(((budgets.astype(np.int64) + 1 + 7) // 8 * 8).astype(np.int32))
             del cache, ws
             torch.cuda.empty_cache()
             cache = small
             ws = torch.empty(xkv.xkv_workspace_bytes(cache, L), dtype=torch.uint8, device="cuda")
+            if step_twin:
+                torch.cuda.synchronize()
+                twin = xkv.XkvCache(L, B, w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, cache.cap.reshape(L, B), zero=False)
+                twin.k.copy_(cache.k); twin.v.copy_(cache.v); twin.score.copy_(cache.score); twin.pos.copy_(cache.pos)
+                twin.len[:] = cache.len
+                ws_b = torch.empty(xkv.xkv_workspace_bytes(twin, L), dtype=torch.uint8, device="cuda")
+                out_b = torch.empty_like(out)
+    return one_kernel_steps
 
 
 @pytest.fixture(params=[2, 1], ids=["fused", "two-kernels"])
@@ -113,6 +135,14 @@ def test_llama2_7b_4k_full_size(xkv, attend_path):
 
 def test_llama2_7b_32k_full_size(xkv, attend_path):
     run_full(xkv, "llama2_7b_32k", steps=3, n_sample=8)
+
+
+@pytest.mark.parametrize("name", ["llama2_7b_4k", "llama2_7b_32k"])
+def test_decode_step_at_full_size(xkv, name):
+    """The call the benchmark times, xkv_decode_step, on the budget-sized arena: three steady-state steps
+    on a copy of the cache, each through the kernel that updates the scores and evicts, bit for bit equal
+    to the two calls (which are held against the oracle as above)."""
+    assert run_full(xkv, name, steps=4, n_sample=4, step_twin=True) == 3
 
 
 def test_mistral_7b_gqa_b32_full_size(xkv):
