@@ -11,9 +11,16 @@
  *                               attention probability into its importance
  *   - xkv_evict_compact         keep the top-budget tokens per (layer, KV
  *                               head) and compact K, V, score, pos in place
+ *   - xkv_decode_step           the two above as one call
  *   - xkv_prefill_evict         fill the cache from a dense prompt, keeping per
  *                               (layer, KV head) the tokens the observation
- *                               window attends to most
+ *                               window attends to most (xkv_prefill_evict_lse:
+ *                               with the window rows' softmax normalisers given)
+ *   - xkv_window_importance, xkv_cache_importance, xkv_allocate_budgets_device,
+ *     xkv_average_allocations   the per-layer score vectors and the allocation
+ *                               on the device, for budgets that follow the task
+ *   - xkv_repack                move the live tokens into arenas of other
+ *                               capacities
  *
  * Conventions for every call
  *   - Pointers marked HOST are ordinary host memory, pointers marked DEVICE
