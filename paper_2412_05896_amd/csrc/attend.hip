@@ -165,6 +165,13 @@ __host__ __device__ inline int64_t record_floats(int group, int head_dim, int st
 // m_tile[strip_rows / 32][G], then o[G][D] and (m, l)[G]; padded to a 128-byte line.
 constexpr int kGqaTile = 32;
 constexpr float kLogitFixScale = 1024.0f;
+// attend_gqa holds a strip's distances back in LDS (this many bytes per workgroup) and writes them in
+// chip-wide bursts: all waves of the chip flush when the wall clock (s_memrealtime, 100 MHz) enters a new
+// window of this many ticks.  Stores that trickle into a read stream cost read bandwidth far beyond their
+// volume; arriving together they cost about half of that (read-only probe with 4 KiB stored per 128 KiB
+// read: 5.9 TB/s written at once, 6.1 held back per workgroup, 6.4 in windows of 40-80 us, 7.2 without).
+constexpr int kGqaHeldBytes = 32 * 1024;
+constexpr unsigned long long kStoreWindowTicks = 4000;
 __host__ __device__ inline int64_t gqa_tilem_offset(int group, int strip_rows) {
   return static_cast<int64_t>(strip_rows) * group / 2;
 }
@@ -944,13 +951,18 @@ template <int G, typename PT = AttendParams>
 __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
   constexpr int D = 128, ROWB = 256, NS = D / 32, kTile = 32;
   typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
-  __shared__ float o_sh[kWaves][G][D];
   __shared__ float ml_sh[kWaves][G][2];
-  __shared__ __attribute__((aligned(16))) unsigned short d_sh[kWaves][kTile * G];   // a tile's logit distances, [row][head]
+  constexpr int kBufTiles = kGqaHeldBytes / (kWaves * kTile * G * 2);        // tiles a wave can hold back: 32 or 16
+  __shared__ __attribute__((aligned(16))) unsigned short d_sh[kWaves][kBufTiles][kTile * G];   // logit distances, [row][head]
   __shared__ float tm_sh[kGqaStripRows / kTile][G];                         // reference of every tile of the strip
   static_assert(kTile == kGqaTile, "");
   constexpr int kPitch = ROWB + 16;         // staged K rows, padded against bank conflicts
   __shared__ __attribute__((aligned(16))) char kt_sh[kWaves][kTile * kPitch];
+  // The waves' partial outputs at the end take the place of their K staging areas, which are free by then.
+  static_assert(G * D * sizeof(float) <= kTile * kPitch, "a wave's outputs fit its staging area");
+  auto o_sh = [&](int w, int g, int ch) -> float& {
+    return reinterpret_cast<float*>(kt_sh[w])[g * D + ch];
+  };
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -1017,6 +1029,8 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
   // sit in LDS, the V rows after the output MFMAs, so each request has most of a
   // tile's work (and the other resident waves) to hide behind.
   uint4 kb[8], vb[8];
+  int held = 0;
+  unsigned long long last_win = wall_clock64() / kStoreWindowTicks;
   char* kt = kt_sh[wave];
   if (wave < tiles) {
     issue_k(kb, wave);
@@ -1083,7 +1097,7 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const float dist = fminf((m_new - sv[i]) * kLogitFixScale, 65535.0f);
-        d_sh[wave][((i < 4 ? 0 : 12) + 4 * j + i) * G + x] = static_cast<unsigned short>(__float2uint_rn(dist));
+        d_sh[wave][held][((i < 4 ? 0 : 12) + 4 * j + i) * G + x] = static_cast<unsigned short>(__float2uint_rn(dist));
       }
       if (j == 0) tm_sh[t][x] = m_new;
     }
@@ -1122,15 +1136,28 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
     __builtin_amdgcn_sched_barrier(0);
     if (more) issue_v(vb, t + kWaves);
     __builtin_amdgcn_sched_barrier(0);
-    // The tile's distances leave as one contiguous, line-aligned block [row][head]
-    // of 64 G bytes (the wave's own LDS staging turns them; LDS keeps a wave's
-    // accesses in order).  The store comes after the requests for the next tile:
-    // the waits for those then do not include it.
+    // The tile's distances stay in the wave's LDS buffer; the held tiles are written when the wall clock
+    // (the same on every compute unit) enters a new window, when the buffer is full, or after the wave's
+    // last tile: the chip's stores then come in bursts instead of a trickle inside the read stream.
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    if (8 * lane < kTile * G) {
-      const uint4 dv = *reinterpret_cast<const uint4*>(&d_sh[wave][8 * lane]);
-      store_stream16(reinterpret_cast<char*>(rec) + (static_cast<int64_t>(row0 - r_begin) * G + 8 * lane) * 2, dv);
+    ++held;
+    {
+      const unsigned long long win = wall_clock64() / kStoreWindowTicks;
+      if (win != last_win || held == kBufTiles || !more) {
+        constexpr int kLanesPerTile = kTile * G / 8, kTilesPerInst = 64 / kLanesPerTile;
+        const int sub = lane / kLanesPerTile, piece = lane % kLanesPerTile;
+        for (int k0 = 0; k0 < held; k0 += kTilesPerInst) {
+          const int k = k0 + sub;
+          if (k < held) {
+            const int tile_id = t - (held - 1 - k) * kWaves;                 // the wave's tiles are kWaves apart
+            const uint4 dv = *reinterpret_cast<const uint4*>(&d_sh[wave][k][8 * piece]);
+            store_stream16(reinterpret_cast<char*>(rec) + (static_cast<int64_t>(tile_id) * kTile * G + 8 * piece) * 2, dv);
+          }
+        }
+        held = 0;
+        last_win = win;
+      }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -1150,7 +1177,7 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
     const int g = 4 * j + i;
     if (g < G) {
 #pragma unroll
-      for (int c = 0; c < 8; ++c) o_sh[wave][g][8 * x + c] = acc[c][i];
+      for (int c = 0; c < 8; ++c) o_sh(wave, g, 8 * x + c) = acc[c][i];
     }
   }
   __syncthreads();
@@ -1166,7 +1193,7 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
     float tot = 0.0f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
-      const float part = ch < D ? o_sh[w][g][ch] : ml_sh[w][g][1];
+      const float part = ch < D ? o_sh(w, g, ch) : ml_sh[w][g][1];
       tot += part * fast_exp2(ml_sh[w][g][0] - m);
     }
     if (ch < D) {
