@@ -218,6 +218,37 @@ def test_bit_reproducible(xkv):
     assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
 
 
+@pytest.mark.parametrize("G", [4, 8])
+def test_matrix_core_path_does_not_depend_on_when_distances_are_written(xkv, G):
+    """The matrix-core kernel writes its logit distances when the wall clock enters a new window, so
+    the moments differ from run to run; streams long enough for several windows must still give
+    the same bits every time, and the oracle's result."""
+    lens = [[60000, 33000]]
+    first = None
+    for rep in range(3):
+        cache = xkv.XkvCache(1, 2, 2 * G, 2, 128, "bf16", np.asarray(lens) + 8)
+        random_fill(cache, lens, 61)
+        g = torch.Generator(device="cpu").manual_seed(62)
+        q = torch.randn((1, 2, 2 * G, 128), generator=g).bfloat16().cuda()
+        kn = torch.randn((1, 2, 2, 128), generator=g).bfloat16().cuda()
+        out = torch.empty((1, 2, 2 * G, 128), dtype=torch.float32, device="cuda")
+        ws = torch.empty(xkv.xkv_workspace_bytes(cache, 1), dtype=torch.uint8, device="cuda")
+        before = get_unit(cache, 0, 0, 1)
+        xkv.xkv_decode_attend_score(cache, 0, 1, q, kn, kn, np.array([7, 8], np.int32), out, ws)
+        torch.cuda.synchronize()
+        got = (out.cpu().numpy().copy(), cache.score.cpu().numpy().copy())
+        if first is None:
+            first = got
+            u = orc.OracleUnit(*before)
+            u.append(storage(kn[0, 0, 1]), storage(kn[0, 0, 1]), 7)
+            o, _ = u.attend(storage(q[0, 0, G:2 * G]))
+            assert rel_err(got[0][0, 0, G:2 * G], o) <= TOL["bf16"]
+            _, _, sc, _ = get_unit(cache, 0, 0, 1)
+            assert rel_err(sc, u.score) <= TOL["bf16"]
+        else:
+            assert np.array_equal(got[0], first[0]) and np.array_equal(got[1], first[1]), f"run {rep} differs"
+
+
 def test_mass_conservation_on_device(xkv):
     """Each decode step adds exactly G to the total score of a stream."""
     cache = xkv.XkvCache(1, 2, 8, 2, 128, "bf16", [[3000, 3000]])
