@@ -165,13 +165,15 @@ __host__ __device__ inline int64_t record_floats(int group, int head_dim, int st
 // m_tile[strip_rows / 32][G], then o[G][D] and (m, l)[G]; padded to a 128-byte line.
 constexpr int kGqaTile = 32;
 constexpr float kLogitFixScale = 1024.0f;
-// attend_gqa holds a strip's distances back in LDS (this many bytes per workgroup) and writes them in
-// chip-wide bursts: all waves of the chip flush when the wall clock (s_memrealtime, 100 MHz) enters a new
-// window of this many ticks.  Stores that trickle into a read stream cost read bandwidth far beyond their
-// volume; arriving together they cost about half of that (read-only probe with 4 KiB stored per 128 KiB
-// read: 5.9 TB/s written at once, 6.1 held back per workgroup, 6.4 in windows of 40-80 us, 7.2 without).
+// attend_gqa holds its distances back in LDS (this many bytes per workgroup) and writes them in chip-wide
+// bursts: all waves of the chip flush when the wall clock (s_memrealtime, 100 MHz) enters a new window of
+// this many ticks, or when their buffer is full.  Stores that trickle into a read stream cost read bandwidth
+// far beyond their volume; arriving together they cost about half of that (read-only probe with 4 KiB stored
+// per 128 KiB read: 5.9 TB/s written at once, 6.1 held back per workgroup, 6.4 in windows of 40-80 us, 7.2
+// without).  The window is as long as the buffer allows: a wave fills 32 tiles (G = 4) in about 130 us, 16
+// tiles (G = 8) in about 65 us.
 constexpr int kGqaHeldBytes = 32 * 1024;
-constexpr unsigned long long kStoreWindowTicks = 4000;
+constexpr unsigned long long kStoreWindowTicksG4 = 12000, kStoreWindowTicksG8 = 6000;
 __host__ __device__ inline int64_t gqa_tilem_offset(int group, int strip_rows) {
   return static_cast<int64_t>(strip_rows) * group / 2;
 }
@@ -969,8 +971,32 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
   const int wave = tid >> 6;
   const int x = lane & 15, j = lane >> 4;
 
+  // The kernel is persistent: workgroup b takes the launch's strips b, 2 grid - 1 - b, 2 grid + b, ...
+  // (the strips are sorted by length, so every workgroup gets about the same number of rows), and a
+  // wave's held tiles may belong to several strips: each remembers where it goes.
+  constexpr unsigned long long kWindowTicks = G == 4 ? kStoreWindowTicksG4 : kStoreWindowTicksG8;
+  __shared__ char* dst_sh[kWaves][kBufTiles];
+  int held = 0;
+  unsigned long long last_win = wall_clock64() / kWindowTicks;
+  constexpr int kLanesPerTile = kTile * G / 8, kTilesPerInst = 64 / kLanesPerTile;
+  auto flush = [&]() {
+    const int sub = lane / kLanesPerTile, piece = lane % kLanesPerTile;
+    for (int k0 = 0; k0 < held; k0 += kTilesPerInst) {
+      const int kk2 = k0 + sub;
+      if (kk2 < held) {
+        const uint4 dv = *reinterpret_cast<const uint4*>(&d_sh[wave][kk2][8 * piece]);
+        store_stream16(dst_sh[wave][kk2] + 16 * piece, dv);
+      }
+    }
+    held = 0;
+  };
+  const int n_units = P.full_blocks + P.n_tail_pairs * P.n_kv_heads;
+  const int grid = gridDim.x;
+  for (int round = 0;; ++round) {
+  const int unit = round * grid + ((round & 1) ? grid - 1 - static_cast<int>(blockIdx.x) : static_cast<int>(blockIdx.x));
+  if (unit >= n_units) break;
   StreamCtx<BF16, D, G> cx;
-  cx.init(P, locate_stream_block(P, blockIdx.x));
+  cx.init(P, locate_stream_block(P, unit));
   const int n = cx.n;
   const int strip_rows = P.strip_rows;
   const int r_begin = cx.s * strip_rows;
@@ -1029,8 +1055,6 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
   // sit in LDS, the V rows after the output MFMAs, so each request has most of a
   // tile's work (and the other resident waves) to hide behind.
   uint4 kb[8], vb[8];
-  int held = 0;
-  unsigned long long last_win = wall_clock64() / kStoreWindowTicks;
   char* kt = kt_sh[wave];
   if (wave < tiles) {
     issue_k(kb, wave);
@@ -1137,25 +1161,18 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
     if (more) issue_v(vb, t + kWaves);
     __builtin_amdgcn_sched_barrier(0);
     // The tile's distances stay in the wave's LDS buffer; the held tiles are written when the wall clock
-    // (the same on every compute unit) enters a new window, when the buffer is full, or after the wave's
-    // last tile: the chip's stores then come in bursts instead of a trickle inside the read stream.
+    // (the same on every compute unit) enters a new window or when the buffer is full: the chip's stores
+    // then come in bursts instead of a trickle inside the read stream.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (lane == 0) dst_sh[wave][held] = reinterpret_cast<char*>(rec) + static_cast<int64_t>(t) * kTile * G * 2;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     ++held;
     {
-      const unsigned long long win = wall_clock64() / kStoreWindowTicks;
-      if (win != last_win || held == kBufTiles || !more) {
-        constexpr int kLanesPerTile = kTile * G / 8, kTilesPerInst = 64 / kLanesPerTile;
-        const int sub = lane / kLanesPerTile, piece = lane % kLanesPerTile;
-        for (int k0 = 0; k0 < held; k0 += kTilesPerInst) {
-          const int k = k0 + sub;
-          if (k < held) {
-            const int tile_id = t - (held - 1 - k) * kWaves;                 // the wave's tiles are kWaves apart
-            const uint4 dv = *reinterpret_cast<const uint4*>(&d_sh[wave][k][8 * piece]);
-            store_stream16(reinterpret_cast<char*>(rec) + (static_cast<int64_t>(tile_id) * kTile * G + 8 * piece) * 2, dv);
-          }
-        }
-        held = 0;
+      const unsigned long long win = wall_clock64() / kWindowTicks;
+      if (win != last_win || held == kBufTiles) {
+        flush();
         last_win = win;
       }
     }
@@ -1203,6 +1220,9 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
       store_stream(&rec_ml[2 * g + 1], tot);
     }
   }
+  __syncthreads();                            // the staging areas and tm_sh are free for the next strip
+  }
+  flush();
 }
 
 // ---------------------------------------------------------------------------
@@ -2423,7 +2443,7 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
     T.ws = static_cast<float*>(workspace);
     if (blocks > 0) {
       const int tok = profile_begin(0, stream);
-      hipLaunchKernelGGL(kern.stream_tab, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), stream_lds,
+      hipLaunchKernelGGL(kern.stream_tab, dim3(static_cast<unsigned>(gqa ? std::min<int64_t>(blocks, 2 * std::max(compute_units(), 1)) : blocks)), dim3(kThreads), stream_lds,
                          stream, T);
       profile_end(tok, stream);
       if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
@@ -2488,7 +2508,7 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
     const int64_t blocks = full + static_cast<int64_t>(tails) * hkv;
     if (blocks > 0) {
       const int tok = profile_begin(0, stream);
-      hipLaunchKernelGGL(kern.stream, dim3(static_cast<unsigned>(blocks)), dim3(kThreads),
+      hipLaunchKernelGGL(kern.stream, dim3(static_cast<unsigned>(gqa ? std::min<int64_t>(blocks, 2 * std::max(compute_units(), 1)) : blocks)), dim3(kThreads),
                          stream_lds, stream, P);
       profile_end(tok, stream);
       if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
