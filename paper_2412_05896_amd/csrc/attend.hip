@@ -172,7 +172,7 @@ constexpr float kLogitFixScale = 1024.0f;
 // per 128 KiB read: 5.9 TB/s written at once, 6.1 held back per workgroup, 6.4 in windows of 40-80 us, 7.2
 // without).  The window is as long as the buffer allows: a wave fills 32 tiles (G = 4) in about 130 us, 16
 // tiles (G = 8) in about 65 us.
-constexpr int kGqaHeldBytes = 32 * 1024;
+constexpr int kGqaHeldBytesG4 = 32 * 1024, kGqaHeldBytesG8 = 48 * 1024;
 constexpr unsigned long long kStoreWindowTicksG4 = 12000, kStoreWindowTicksG8 = 6000;
 __host__ __device__ inline int64_t gqa_tilem_offset(int group, int strip_rows) {
   return static_cast<int64_t>(strip_rows) * group / 2;
@@ -954,14 +954,16 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
   constexpr int D = 128, ROWB = 256, NS = D / 32, kTile = 32;
   typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
   __shared__ float ml_sh[kWaves][G][2];
-  constexpr int kBufTiles = kGqaHeldBytes / (kWaves * kTile * G * 2);        // tiles a wave can hold back: 32 or 16
+  constexpr int kBufTiles = (G == 4 ? kGqaHeldBytesG4 : kGqaHeldBytesG8) / (kWaves * kTile * G * 2);   // tiles a wave can hold back
   __shared__ __attribute__((aligned(16))) unsigned short d_sh[kWaves][kBufTiles][kTile * G];   // logit distances, [row][head]
   __shared__ float tm_sh[kGqaStripRows / kTile][G];                         // reference of every tile of the strip
   static_assert(kTile == kGqaTile, "");
   constexpr int kPitch = ROWB + 16;         // staged K rows, padded against bank conflicts
-  __shared__ __attribute__((aligned(16))) char kt_sh[kWaves][kTile * kPitch];
+  // A wave stages the tile's K rows 16 at a time (one logit MFMA group): half the LDS of a whole tile,
+  // which the held distances take.
+  __shared__ __attribute__((aligned(16))) char kt_sh[kWaves][(kTile / 2) * kPitch];
   // The waves' partial outputs at the end take the place of their K staging areas, which are free by then.
-  static_assert(G * D * sizeof(float) <= kTile * kPitch, "a wave's outputs fit its staging area");
+  static_assert(G * D * sizeof(float) <= (kTile / 2) * kPitch, "a wave's outputs fit its staging area");
   auto o_sh = [&](int w, int g, int ch) -> float& {
     return reinterpret_cast<float*>(kt_sh[w])[g * D + ch];
   };
@@ -1064,29 +1066,32 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
     const int row0 = r_begin + t * kTile;
     const bool more = t + kWaves < tiles;
     const bool last_tile = append_here && row0 + kTile >= n;   // holds the appended row n-1
-    // The K tile passes through the wave's LDS staging area to reach the MFMA
-    // operand layout (row x of each 16-row group, 16 bytes at column 4 sl + j).
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      *reinterpret_cast<uint4*>(kt + vrow(i) * kPitch + x * 16) = kb[i];
+    // The K tile passes through the wave's LDS staging area, 16 rows at a time, to reach the MFMA
+    // operand layout (row x of the 16-row group, 16 bytes at column 4 sl + j).  Loads 0..3 of a
+    // lane are rows 4 j + i of the first group, loads 4..7 the same rows of the second.
     if (last_tile) {                          // the append itself, K part
 #pragma unroll
       for (int i = 0; i < 8; ++i)
         if (row0 + vrow(i) == n - 1)
           *reinterpret_cast<uint4*>(cx.kbase + static_cast<int64_t>(n - 1) * ROWB + x * 16) = kb[i];
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    if (more) issue_k(kb, t + kWaves);
-    __builtin_amdgcn_sched_barrier(0);
     float sv[8];
 #pragma unroll
     for (int grp = 0; grp < 2; ++grp) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<uint4*>(kt + (4 * j + i) * kPitch + x * 16) = kb[4 * grp + i];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      if (grp == 1) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) issue_k(kb, t + kWaves);
+        __builtin_amdgcn_sched_barrier(0);
+      }
       floatx4 a = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
       for (int sl = 0; sl < NS; ++sl) {
-        const uint4 ka = *reinterpret_cast<const uint4*>(kt + (grp * 16 + x) * kPitch + sl * 64 + j * 16);
+        const uint4 ka = *reinterpret_cast<const uint4*>(kt + x * kPitch + sl * 64 + j * 16);
         a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka), qb[sl], a, 0, 0, 0);
       }
       const int r = row0 + grp * 16 + 4 * j;
@@ -1094,9 +1099,9 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
       for (int i = 0; i < 4; ++i) {
         sv[grp * 4 + i] = r + i < r_end ? a[i] * P.scale_log2e : -INFINITY;
       }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
 
     // Online softmax for head x: the tile's first row is live, so the maximum is finite.
     float tm = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
