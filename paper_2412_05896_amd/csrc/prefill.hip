@@ -1160,18 +1160,19 @@ __global__ __launch_bounds__(kThreads) void prefill_gather(const GatherParams P)
   const char* vs = static_cast<const char*>(P.v_src) + u * t * P.row_bytes;
   char* kd = static_cast<char*>(P.k) + stream_slot * P.row_bytes;
   char* vd = static_cast<char*>(P.v) + stream_slot * P.row_bytes;
-  // Four passes at a time: their eight loads are requested before the first store.
-  for (int s0 = first + tid / frags; s0 < last; s0 += 4 * rows_per_pass) {
-    uint4 a[4], b[4];
+  // kPasses passes at a time: their loads are all requested before the first store.
+  constexpr int kPasses = 8;
+  for (int s0 = first + tid / frags; s0 < last; s0 += kPasses * rows_per_pass) {
+    uint4 a[kPasses], b[kPasses];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int p = 0; p < kPasses; ++p) {
       const int s = min(s0 + p * rows_per_pass, last - 1);      // past the end: a kept row again, not stored
       const int64_t so = static_cast<int64_t>(idx[s]) * P.row_bytes + fr * 16;
       a[p] = load_stream16(ks + so);
       b[p] = load_stream16(vs + so);
     }
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int p = 0; p < kPasses; ++p) {
       const int s = s0 + p * rows_per_pass;
       if (s < last) {
         const int64_t dof = static_cast<int64_t>(s) * P.row_bytes + fr * 16;

@@ -71,17 +71,18 @@ __global__ __launch_bounds__(kThreads) void repack_copy(const RepackParams P) {
   const char* sv = static_cast<const char*>(P.src_v) + (s_slot + r0) * P.row_bytes;
   char* dk = static_cast<char*>(P.dst_k) + (d_slot + r0) * P.row_bytes;
   char* dv = static_cast<char*>(P.dst_v) + (d_slot + r0) * P.row_bytes;
-  for (int64_t off = static_cast<int64_t>(tid) * 16; off < bytes; off += 4 * kThreads * 16) {
-    uint4 a[4], b[4];
+  constexpr int kPasses = 8;
+  for (int64_t off = static_cast<int64_t>(tid) * 16; off < bytes; off += kPasses * kThreads * 16) {
+    uint4 a[kPasses], b[kPasses];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kPasses; ++u) {
       const int64_t o = off + static_cast<int64_t>(u) * kThreads * 16;
       const int64_t oc = o < bytes ? o : off;           // past the end: a valid piece again, not stored
       a[u] = load_stream16(sk + oc);
       b[u] = load_stream16(sv + oc);
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kPasses; ++u) {
       const int64_t o = off + static_cast<int64_t>(u) * kThreads * 16;
       if (o < bytes) {
         *reinterpret_cast<uint4*>(dk + o) = a[u];
