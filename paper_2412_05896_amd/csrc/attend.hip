@@ -950,7 +950,7 @@ __global__ __launch_bounds__(kThreads) void attend_chunk(const PT P) {
 // A probability enters the MFMA as the sum of two bf16 numbers (the rounded
 // value and the rounded remainder), which keeps its relative error below 2^-16.
 template <int G, typename PT = AttendParams>
-__global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
+__global__ __launch_bounds__(kThreads, G == 4 ? 2 : 1) void attend_gqa(const PT P) {
   constexpr int D = 128, ROWB = 256, NS = D / 32, kTile = 32;
   typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
   __shared__ float ml_sh[kWaves][G][2];
@@ -975,7 +975,10 @@ __global__ __launch_bounds__(kThreads) void attend_gqa(const PT P) {
 
   // The kernel is persistent: workgroup b takes the launch's strips b, 2 grid - 1 - b, 2 grid + b, ...
   // (the strips are sorted by length, so every workgroup gets about the same number of rows), and a
-  // wave's held tiles may belong to several strips: each remembers where it goes.
+  // wave's held tiles may belong to several strips: each remembers where it goes.  At G = 4 the
+  // registers are held to two waves per SIMD (two workgroups per compute unit: 3.29 -> 3.24 ms per
+  // launch of the batched 16k workload); at G = 8 one workgroup per compute unit measured faster
+  // (4.13 against 4.19 ms on the 128k workload), and the host launches one per unit.
   constexpr unsigned long long kWindowTicks = G == 4 ? kStoreWindowTicksG4 : kStoreWindowTicksG8;
   __shared__ char* dst_sh[kWaves][kBufTiles];
   int held = 0;
@@ -2448,7 +2451,7 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
     T.ws = static_cast<float*>(workspace);
     if (blocks > 0) {
       const int tok = profile_begin(0, stream);
-      hipLaunchKernelGGL(kern.stream_tab, dim3(static_cast<unsigned>(gqa ? std::min<int64_t>(blocks, 2 * std::max(compute_units(), 1)) : blocks)), dim3(kThreads), stream_lds,
+      hipLaunchKernelGGL(kern.stream_tab, dim3(static_cast<unsigned>(gqa ? std::min<int64_t>(blocks, (G == 4 ? 2 : 1) * std::max(compute_units(), 1)) : blocks)), dim3(kThreads), stream_lds,
                          stream, T);
       profile_end(tok, stream);
       if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
@@ -2513,7 +2516,7 @@ static xkv_status decode_attend(xkv_cache* cache, int32_t layer_begin, int32_t l
     const int64_t blocks = full + static_cast<int64_t>(tails) * hkv;
     if (blocks > 0) {
       const int tok = profile_begin(0, stream);
-      hipLaunchKernelGGL(kern.stream, dim3(static_cast<unsigned>(gqa ? std::min<int64_t>(blocks, 2 * std::max(compute_units(), 1)) : blocks)), dim3(kThreads),
+      hipLaunchKernelGGL(kern.stream, dim3(static_cast<unsigned>(gqa ? std::min<int64_t>(blocks, (G == 4 ? 2 : 1) * std::max(compute_units(), 1)) : blocks)), dim3(kThreads),
                          stream_lds, stream, P);
       profile_end(tok, stream);
       if (hipGetLastError() != hipSuccess) return XKV_ERR_DEVICE;
